@@ -1,0 +1,66 @@
+"""Host-side statistics of the oracle (float64) -- TEST INFRASTRUCTURE ONLY.
+
+The decision rules of the certification procedure (Alg. 1) and the prediction
+procedure (Alg. 2), written with library routines as the individual steps.
+"""
+from __future__ import annotations
+
+from scipy import stats as _st
+
+ABSTAIN = -1
+
+
+def cp_lower(k: int, n: int, alpha: float) -> float:
+    """One-sided (1 - alpha) Clopper-Pearson lower confidence bound on a
+    binomial proportion after k successes in n trials (Alg. 1, the step that
+    defines the lower bound p_A; the exact interval of the cited smoothing
+    work): the p at which P[Bin(n, p) >= k] = alpha, i.e. the alpha-quantile of
+    Beta(k, n - k + 1); 0 when k = 0."""
+    if k == 0:
+        return 0.0
+    return float(_st.beta.ppf(alpha, k, n - k + 1))
+
+
+def radius(sigma: float, p_lower: float) -> float:
+    """Certified l2 radius sigma * Phi^{-1}(p_A) (Alg. 1, return step), Phi the
+    standard normal cdf."""
+    return float(sigma * _st.norm.ppf(p_lower))
+
+
+def lowest_argmax(counts) -> int:
+    best = 0
+    for i in range(1, len(counts)):
+        if counts[i] > counts[best]:
+            best = i
+    return best
+
+
+def certify_decision(counts0, counts1, sigma: float, n: int, alpha: float):
+    """Alg. 1 after the two Monte-Carlo loops: returns (class, radius, p_lower,
+    n_top); class is ABSTAIN and radius 0.0 when the bound is not above 1/2."""
+    c_a = lowest_argmax(counts0)
+    k = int(counts1[c_a])
+    p_l = cp_lower(k, n, alpha)
+    if p_l > 0.5:
+        return c_a, radius(sigma, p_l), p_l, k
+    return ABSTAIN, 0.0, p_l, k
+
+
+def binom_pvalue(n_a: int, n_b: int) -> float:
+    """Two-sided p-value of the hypothesis that n_a successes out of
+    n_a + n_b trials come from a fair coin (Alg. 2, the binomial test):
+    min(1, 2 * P[Bin(n_a + n_b, 1/2) >= n_a]) for n_a >= n_b."""
+    m = n_a + n_b
+    return float(min(1.0, 2.0 * _st.binom.sf(n_a - 1, m, 0.5)))
+
+
+def predict_decision(counts, alpha: float):
+    """Alg. 2 after the Monte-Carlo loop: (class or ABSTAIN, p-value, n_A, n_B).
+    The top two classes are taken with lowest index winning ties; the class is
+    returned when the p-value is at most alpha."""
+    c_a = lowest_argmax(counts)
+    rest = [(-int(c), i) for i, c in enumerate(counts) if i != c_a]
+    n_b = -min(rest)[0] if rest else 0
+    n_a = int(counts[c_a])
+    pv = binom_pvalue(n_a, n_b)
+    return (c_a if pv <= alpha else ABSTAIN), pv, n_a, n_b
