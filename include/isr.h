@@ -1,0 +1,151 @@
+/*
+ * isr.h -- C ABI of the MI355X integer-randomized-smoothing library.
+ *
+ * The library runs the Monte-Carlo loop behind the paper's certification
+ * procedure (Alg. 1) and prediction procedure (Alg. 2, appendix "Practical
+ * Prediction"): for every sample index it adds discrete-Gaussian noise
+ * (Def. 3.3) to the quantized image on the integer pixel grid, runs the
+ * int8 base classifier with integer-only arithmetic (Thm. 3.2, step 1) and
+ * tallies the predicted class; the tallies then give the one-sided lower
+ * confidence bound and the l2 radius sigma * Phi^-1(p_A) (Alg. 1) or the
+ * binomial test (Alg. 2).  Every step of the loop runs in HIP kernels on the
+ * GPU; only the O(classes) decision on the tallies runs on the host in fp64.
+ *
+ * Conventions
+ *   - "host" / "device" on a pointer says which memory it must point to.
+ *   - All functions return ISR_OK or an ISR_ERR_* code; abstention is not an
+ *     error (cls == ISR_ABSTAIN, radius == 0, status ISR_OK).
+ *   - sigma and radius are in grid units of the uint8 pixel lattice (one unit
+ *     = one step of the 8-bit grid); 1 <= sigma <= 1024.
+ *   - Results are a pure function of (model, x, sigma, n0, n, alpha, seed,
+ *     image_id): independent of the chunk size and of kernel choices.
+ *   - Calls on one isr_model must not overlap in time (one workspace).
+ */
+#ifndef ISR_H
+#define ISR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ISR_OK 0
+#define ISR_ERR_ARG 1          /* null pointer or value outside the documented domain */
+#define ISR_ERR_FORMAT 2       /* model blob malformed or fails validation */
+#define ISR_ERR_UNSUPPORTED 3  /* well-formed, but a shape/op the kernels do not cover */
+#define ISR_ERR_WORKSPACE 4    /* no workspace set, or too small for the chunk size */
+#define ISR_ERR_DEVICE 5       /* a HIP call failed; isr_last_device_error() has the code */
+
+#define ISR_ABSTAIN (-1)
+
+typedef struct isr_model isr_model; /* opaque; owned by the library until isr_free_model */
+
+typedef struct isr_result {
+    int32_t cls;      /* predicted class 0..classes-1, or ISR_ABSTAIN */
+    double radius;    /* certified l2 radius in grid units (Alg. 1); 0 on abstain / for predict */
+    double p_lower;   /* certify: Clopper-Pearson lower bound of p_A; predict: binomial p-value */
+    uint32_t n_top;   /* certify: estimation votes of the selected class; predict: n_A */
+    uint32_t n_second;/* predict: n_B (runner-up votes); certify: 0 */
+} isr_result;
+
+/* ---- model ------------------------------------------------------------- */
+
+/* ISRM model blob (little-endian 32-bit fields):
+ *   header : 'ISRM', version 1, in_C, in_H, in_W, classes, n_tensors, n_ops
+ *   tensors: n_tensors x {C, H, W, zero_point}; tensor 0 = input (pixel - 128, zp 0)
+ *   ops    : n_ops x {type, payload_bytes, payload}, executed in order:
+ *     1 CONV    in, out, k, stride, pad, relu, w int8[Cout][Cin][k][k] (padded
+ *               to 4 bytes), bias i32[Cout], M0 i32[Cout] in [2^30,2^31), shift i32[Cout] in [0,31]
+ *               acc = bias + sum over in-bounds taps (q - z_in) w;
+ *               q_out = clamp(z_out + RHA(acc * M0, 31 + shift), relu ? z_out : -128, 127)
+ *     2 ADD     a, b, out, Ma, Mb, shift, relu:  RHA((qa-za) Ma + (qb-zb) Mb, shift), same clamp
+ *     3 MAXPOOL in, out, k, stride, pad (max over in-bounds taps)
+ *     4 GAP     in, out, M0, shift: requantised sum over H x W of (q - z_in)
+ *     5 FC      in, out, w int8[Cout][Cin], bias i32[Cout]: int32 logits, no requantisation
+ *   RHA(v, s) = round-half-away-from-zero of v / 2^s (one rounding).
+ *
+ * isr_load_model parses and validates a blob (host memory), re-lays the weights
+ * for the MFMA kernels and uploads them to the current HIP device.  The blob is
+ * not referenced after the call returns. */
+int isr_load_model(const void *blob_host, size_t bytes, isr_model **out);
+int isr_free_model(isr_model *m);
+/* Host-only structural validation of a blob (no GPU needed). */
+int isr_validate_model(const void *blob_host, size_t bytes);
+int isr_model_info(const isr_model *m, int *C, int *H, int *W, int *num_classes);
+
+/* Device scratch for activations of `chunk_samples` noisy copies processed at a
+ * time.  The caller allocates it (e.g. a torch uint8 tensor), keeps it alive
+ * while the model uses it, and passes the HIP stream all work is enqueued on
+ * (NULL = the default stream). */
+size_t isr_workspace_bytes(const isr_model *m, uint32_t chunk_samples);
+int isr_set_workspace(isr_model *m, void *workspace_device, size_t bytes, uint32_t chunk_samples,
+                      void *hip_stream);
+
+/* ---- the two procedures -------------------------------------------------- */
+
+/* Alg. 1 (certification).  x_device: uint8 [C][H][W] image in device memory.
+ * Runs n0 selection samples (phase 0) and n estimation samples (phase 1),
+ * takes c_A = the most voted class of phase 0 (lowest index on ties), the
+ * one-sided (1-alpha) Clopper-Pearson lower bound p_A from phase-1 votes of
+ * c_A, and returns (c_A, sigma * Phi^-1(p_A)) if p_A > 1/2, else abstains.
+ * counts0_host / counts1_host: optional uint32[classes] outputs (host). */
+int isr_certify(isr_model *m, const uint8_t *x_device, uint32_t sigma, uint32_t n0, uint32_t n,
+                double alpha, uint64_t seed, uint32_t image_id, isr_result *out,
+                uint32_t *counts0_host, uint32_t *counts1_host);
+
+/* Alg. 2 (prediction).  Runs n samples (phase 0), takes the two most voted
+ * classes (n_A >= n_B) and returns c_A if the two-sided binomial p-value of
+ * n_A out of n_A + n_B at 1/2 is <= alpha, else abstains. */
+int isr_predict(isr_model *m, const uint8_t *x_device, uint32_t sigma, uint32_t n, double alpha,
+                uint64_t seed, uint32_t image_id, isr_result *out, uint32_t *counts_host);
+
+/* ---- parity / resume hooks (sample-index ranges are reproducible) -------- */
+
+/* Noisy copies for sample indices [sample_begin, sample_begin+count) of one
+ * phase: out_host gets count * C*H*W int8 values in [C][H][W] order, each
+ * clamp(x + delta, 0, 255) - 128.  count <= chunk_samples. */
+int isr_debug_noisy(isr_model *m, const uint8_t *x_device, uint32_t sigma, uint64_t seed,
+                    uint32_t image_id, uint32_t phase, uint32_t sample_begin, uint32_t count,
+                    int8_t *out_host);
+
+/* Full forward for a sample-index range: any of logits_host (count*classes
+ * int32), argmax_host (count int32), counts_host (classes uint32, accumulated
+ * into) may be NULL.  Votes are additive over ranges.  Any count >= 1. */
+int isr_debug_forward(isr_model *m, const uint8_t *x_device, uint32_t sigma, uint64_t seed,
+                      uint32_t image_id, uint32_t phase, uint32_t sample_begin, uint32_t count,
+                      int32_t *logits_host, int32_t *argmax_host, uint32_t *counts_host);
+
+/* One intermediate tensor (id as in the blob's tensor table; not the logits)
+ * of ONE noisy copy, converted to int8 [C][H][W] on the host. */
+int isr_debug_tensor(isr_model *m, const uint8_t *x_device, uint32_t sigma, uint64_t seed,
+                     uint32_t image_id, uint32_t phase, uint32_t sample, int32_t tensor_id,
+                     int8_t *out_host);
+
+/* ---- host-only pieces (no GPU needed) ------------------------------------ */
+
+/* Inverse-CDF thresholds of the discrete Gaussian N_Z(0, sigma^2) (Def. 3.3):
+ * T[i] = floor(2^64 P[delta <= i - R]) for i in [0, 2R); a uniform 64-bit u
+ * gives delta = -R + #{i : T[i] <= u}.  Writes min(cap, 2R) entries to T_host
+ * (may be NULL with cap 0) and R to R_out. */
+int isr_noise_table(uint32_t sigma, uint64_t *T_host, size_t cap, uint32_t *R_out);
+
+/* One-sided (1-alpha) Clopper-Pearson lower bound after k successes in n trials (Alg. 1). */
+int isr_cp_lower(uint32_t k, uint32_t n, double alpha, double *p_lower);
+/* Standard normal quantile Phi^-1(p), 0 < p < 1 (radius factor of Alg. 1). */
+int isr_normal_quantile(double p, double *z);
+/* Two-sided binomial p-value min(1, 2 P[Bin(n_a+n_b, 1/2) >= n_a]) (Alg. 2). */
+int isr_binom_pvalue(uint32_t n_a, uint32_t n_b, double *pvalue);
+/* Decisions of Alg. 1 / Alg. 2 on tallies already on the host. */
+int isr_decide_certify(const uint32_t *counts0, const uint32_t *counts1, uint32_t classes,
+                       double sigma, uint32_t n, double alpha, isr_result *out);
+int isr_decide_predict(const uint32_t *counts, uint32_t classes, double alpha, isr_result *out);
+
+const char *isr_strerror(int status);
+int isr_last_device_error(void); /* hipError_t of the last failing HIP call on this thread */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ISR_H */

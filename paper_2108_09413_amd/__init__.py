@@ -1,0 +1,255 @@
+"""Python binding of the integer-randomized-smoothing HIP library (libisr.so).
+
+Argument marshalling only: every step of the Monte-Carlo loop runs in the HIP
+kernels behind the C ABI declared in include/isr.h.  torch is used for device
+memory (workspace, images) and the stream.  There is no CPU fallback: if the
+library cannot be loaded the import of a compute entry point raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libisr.so")
+
+ISR_OK, ISR_ERR_ARG, ISR_ERR_FORMAT, ISR_ERR_UNSUPPORTED, ISR_ERR_WORKSPACE, ISR_ERR_DEVICE = range(6)
+ABSTAIN = -1
+
+EXPORTS = [
+    "isr_load_model", "isr_free_model", "isr_validate_model", "isr_model_info", "isr_workspace_bytes",
+    "isr_set_workspace", "isr_certify", "isr_predict", "isr_debug_noisy", "isr_debug_forward",
+    "isr_debug_tensor", "isr_noise_table", "isr_cp_lower", "isr_normal_quantile", "isr_binom_pvalue",
+    "isr_decide_certify", "isr_decide_predict", "isr_strerror", "isr_last_device_error",
+]
+
+
+class IsrError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        msg = lib().isr_strerror(status).decode()
+        if status == ISR_ERR_DEVICE:
+            msg += f" (hipError {lib().isr_last_device_error()})"
+        super().__init__(f"{what}: {msg}")
+
+
+class Result(C.Structure):
+    _fields_ = [("cls", C.c_int32), ("radius", C.c_double), ("p_lower", C.c_double),
+                ("n_top", C.c_uint32), ("n_second", C.c_uint32)]
+
+    def __repr__(self):
+        return (f"Result(cls={self.cls}, radius={self.radius!r}, p_lower={self.p_lower!r}, "
+                f"n_top={self.n_top}, n_second={self.n_second})")
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C-ABI library; builds it in-tree first if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            from .build import build_library
+            build_library()
+        L = C.CDLL(LIB_PATH)
+        vp, u32, u64, i32, dbl, sz = C.c_void_p, C.c_uint32, C.c_uint64, C.c_int32, C.c_double, C.c_size_t
+        L.isr_load_model.argtypes = [vp, sz, C.POINTER(vp)]
+        L.isr_free_model.argtypes = [vp]
+        L.isr_validate_model.argtypes = [vp, sz]
+        L.isr_model_info.argtypes = [vp] + [C.POINTER(C.c_int)] * 4
+        L.isr_workspace_bytes.argtypes = [vp, u32]
+        L.isr_workspace_bytes.restype = sz
+        L.isr_set_workspace.argtypes = [vp, vp, sz, u32, vp]
+        L.isr_certify.argtypes = [vp, vp, u32, u32, u32, dbl, u64, u32, C.POINTER(Result), vp, vp]
+        L.isr_predict.argtypes = [vp, vp, u32, u32, dbl, u64, u32, C.POINTER(Result), vp]
+        L.isr_debug_noisy.argtypes = [vp, vp, u32, u64, u32, u32, u32, u32, vp]
+        L.isr_debug_forward.argtypes = [vp, vp, u32, u64, u32, u32, u32, u32, vp, vp, vp]
+        L.isr_debug_tensor.argtypes = [vp, vp, u32, u64, u32, u32, u32, i32, vp]
+        L.isr_noise_table.argtypes = [u32, vp, sz, C.POINTER(u32)]
+        L.isr_cp_lower.argtypes = [u32, u32, dbl, C.POINTER(dbl)]
+        L.isr_normal_quantile.argtypes = [dbl, C.POINTER(dbl)]
+        L.isr_binom_pvalue.argtypes = [u32, u32, C.POINTER(dbl)]
+        L.isr_decide_certify.argtypes = [vp, vp, u32, dbl, u32, dbl, C.POINTER(Result)]
+        L.isr_decide_predict.argtypes = [vp, u32, dbl, C.POINTER(Result)]
+        L.isr_strerror.argtypes = [C.c_int]
+        L.isr_strerror.restype = C.c_char_p
+        L.isr_last_device_error.argtypes = []
+        for name in EXPORTS:
+            if name not in ("isr_workspace_bytes", "isr_strerror"):
+                getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _check(status: int, what: str):
+    if status != ISR_OK:
+        raise IsrError(status, what)
+
+
+def _np_ptr(a):
+    return a.ctypes.data_as(C.c_void_p) if a is not None else None
+
+
+# ---- host-only entry points -------------------------------------------------
+
+def isr_validate_model(blob: bytes) -> int:
+    buf = (C.c_char * len(blob)).from_buffer_copy(blob)
+    return lib().isr_validate_model(buf, len(blob))
+
+
+def isr_noise_table(sigma: int):
+    R = C.c_uint32(0)
+    _check(lib().isr_noise_table(sigma, None, 0, C.byref(R)), "isr_noise_table")
+    T = np.zeros(2 * R.value, dtype=np.uint64)
+    _check(lib().isr_noise_table(sigma, _np_ptr(T), T.size, C.byref(R)), "isr_noise_table")
+    return T, R.value
+
+
+def isr_cp_lower(k: int, n: int, alpha: float) -> float:
+    out = C.c_double(0)
+    _check(lib().isr_cp_lower(k, n, alpha, C.byref(out)), "isr_cp_lower")
+    return out.value
+
+
+def isr_normal_quantile(p: float) -> float:
+    out = C.c_double(0)
+    _check(lib().isr_normal_quantile(p, C.byref(out)), "isr_normal_quantile")
+    return out.value
+
+
+def isr_binom_pvalue(n_a: int, n_b: int) -> float:
+    out = C.c_double(0)
+    _check(lib().isr_binom_pvalue(n_a, n_b, C.byref(out)), "isr_binom_pvalue")
+    return out.value
+
+
+def isr_decide_certify(counts0, counts1, sigma: float, n: int, alpha: float) -> Result:
+    c0 = np.ascontiguousarray(counts0, dtype=np.uint32)
+    c1 = np.ascontiguousarray(counts1, dtype=np.uint32)
+    res = Result()
+    _check(lib().isr_decide_certify(_np_ptr(c0), _np_ptr(c1), c0.size, sigma, n, alpha, C.byref(res)),
+           "isr_decide_certify")
+    return res
+
+
+def isr_decide_predict(counts, alpha: float) -> Result:
+    c = np.ascontiguousarray(counts, dtype=np.uint32)
+    res = Result()
+    _check(lib().isr_decide_predict(_np_ptr(c), c.size, alpha, C.byref(res)), "isr_decide_predict")
+    return res
+
+
+# ---- device entry points ----------------------------------------------------
+
+class Model:
+    """Handle returned by isr_load_model plus the torch-owned workspace."""
+
+    def __init__(self, handle, blob_len):
+        self.handle = handle
+        self.workspace = None
+        self.chunk = 0
+        info = [C.c_int(0) for _ in range(4)]
+        _check(lib().isr_model_info(handle, *[C.byref(v) for v in info]), "isr_model_info")
+        self.C, self.H, self.W, self.classes = [v.value for v in info]
+        self.blob_len = blob_len
+
+    def close(self):
+        if self.handle:
+            lib().isr_free_model(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def isr_load_model(blob: bytes) -> Model:
+    import torch
+    if not torch.cuda.is_available():
+        raise RuntimeError("isr_load_model needs a HIP device")
+    buf = (C.c_char * len(blob)).from_buffer_copy(blob)
+    h = C.c_void_p(None)
+    _check(lib().isr_load_model(buf, len(blob), C.byref(h)), "isr_load_model")
+    return Model(h, len(blob))
+
+
+def isr_workspace_bytes(model: Model, chunk_samples: int) -> int:
+    return int(lib().isr_workspace_bytes(model.handle, chunk_samples))
+
+
+def isr_set_workspace(model: Model, chunk_samples: int, stream=None):
+    """Allocates the device scratch as a torch uint8 tensor and hands it over
+    together with the current (or given) torch stream."""
+    import torch
+    need = isr_workspace_bytes(model, chunk_samples)
+    if need == 0:
+        raise IsrError(ISR_ERR_ARG, "isr_workspace_bytes")
+    ws = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
+    ptr = (ws.data_ptr() + 255) // 256 * 256
+    st = stream if stream is not None else torch.cuda.current_stream()
+    _check(lib().isr_set_workspace(model.handle, C.c_void_p(ptr), need, chunk_samples, C.c_void_p(st.cuda_stream)),
+           "isr_set_workspace")
+    model.workspace, model.chunk, model.stream = ws, chunk_samples, st
+
+
+def _dev_image(x):
+    """uint8 [C][H][W] image on the device (torch tensor); numpy input is uploaded."""
+    import torch
+    if isinstance(x, np.ndarray):
+        x = torch.from_numpy(np.ascontiguousarray(x, dtype=np.uint8)).cuda()
+    assert x.dtype == torch.uint8 and x.is_cuda and x.is_contiguous()
+    return x
+
+
+def isr_certify(model: Model, x, sigma: int, n0: int, n: int, alpha: float, seed: int = 0, image_id: int = 0,
+                want_counts: bool = True):
+    x = _dev_image(x)
+    res = Result()
+    c0 = np.zeros(model.classes, dtype=np.uint32) if want_counts else None
+    c1 = np.zeros(model.classes, dtype=np.uint32) if want_counts else None
+    _check(lib().isr_certify(model.handle, C.c_void_p(x.data_ptr()), sigma, n0, n, alpha, C.c_uint64(seed), image_id,
+                             C.byref(res), _np_ptr(c0), _np_ptr(c1)), "isr_certify")
+    return res, c0, c1
+
+
+def isr_predict(model: Model, x, sigma: int, n: int, alpha: float, seed: int = 0, image_id: int = 0):
+    x = _dev_image(x)
+    res = Result()
+    c = np.zeros(model.classes, dtype=np.uint32)
+    _check(lib().isr_predict(model.handle, C.c_void_p(x.data_ptr()), sigma, n, alpha, C.c_uint64(seed), image_id,
+                             C.byref(res), _np_ptr(c)), "isr_predict")
+    return res, c
+
+
+def isr_debug_noisy(model: Model, x, sigma: int, seed: int, image_id: int, phase: int, sample_begin: int, count: int):
+    x = _dev_image(x)
+    out = np.zeros((count, model.C, model.H, model.W), dtype=np.int8)
+    _check(lib().isr_debug_noisy(model.handle, C.c_void_p(x.data_ptr()), sigma, C.c_uint64(seed), image_id, phase,
+                                 sample_begin, count, _np_ptr(out)), "isr_debug_noisy")
+    return out
+
+
+def isr_debug_forward(model: Model, x, sigma: int, seed: int, image_id: int, phase: int, sample_begin: int,
+                      count: int, want_logits: bool = True):
+    x = _dev_image(x)
+    logits = np.zeros((count, model.classes), dtype=np.int32) if want_logits else None
+    argmax = np.zeros(count, dtype=np.int32)
+    counts = np.zeros(model.classes, dtype=np.uint32)
+    _check(lib().isr_debug_forward(model.handle, C.c_void_p(x.data_ptr()), sigma, C.c_uint64(seed), image_id, phase,
+                                   sample_begin, count, _np_ptr(logits), _np_ptr(argmax), _np_ptr(counts)),
+           "isr_debug_forward")
+    return logits, argmax, counts
+
+
+def isr_debug_tensor(model: Model, x, sigma: int, seed: int, image_id: int, phase: int, sample: int,
+                     tensor_id: int, shape):
+    x = _dev_image(x)
+    out = np.zeros(shape, dtype=np.int8)
+    _check(lib().isr_debug_tensor(model.handle, C.c_void_p(x.data_ptr()), sigma, C.c_uint64(seed), image_id, phase,
+                                  sample, tensor_id, _np_ptr(out)), "isr_debug_tensor")
+    return out

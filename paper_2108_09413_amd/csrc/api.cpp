@@ -1,0 +1,538 @@
+// C ABI: model loading, workspace planning and the Monte-Carlo driver that
+// enqueues noise -> layers -> vote kernels for chunks of sample indices.
+#include <algorithm>
+#include <cstring>
+#include <map>
+#include <new>
+
+#include "isr_internal.h"
+
+using namespace isr;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+#define HIP_TRY(expr)                                     \
+    do {                                                  \
+        hipError_t e_ = (expr);                           \
+        if (e_ != hipSuccess) {                           \
+            g_last_hip_error = (int)e_;                   \
+            return ISR_ERR_DEVICE;                        \
+        }                                                 \
+    } while (0)
+
+constexpr int TABLE_SLOTS = 8;
+
+struct DevOp {
+    OpType type;
+    int a = -1, b = -1, out = -1;
+    ConvParams conv{};
+    AddParams add{};
+    PoolParams pool{};
+    GapParams gap{};
+    FcParams fc{};
+};
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// MFMA 32x32 accumulator row r of lane half h, register i is 8*(i/4) + 4*h + i%4;
+// weights of output channel 16*h + i go to that row so that a lane ends up
+// holding 16 consecutive channels.
+int mfma32_row_of_channel(int oc_local) {
+    int h = oc_local >> 4, a = (oc_local & 15) >> 2, b = oc_local & 3;
+    return 8 * a + 4 * h + b;
+}
+
+}  // namespace
+
+struct isr_model {
+    ParsedModel pm;
+    std::vector<DevOp> ops;
+    uint8_t *dconst = nullptr;          // weights and per-channel tables
+    DeviceNoiseTable *dtables = nullptr;  // TABLE_SLOTS entries
+    DeviceNoiseTable *htables = nullptr;  // pinned staging, TABLE_SLOTS entries
+    uint32_t table_sigma[TABLE_SLOTS] = {0};
+    int table_next = 0;
+    uint32_t *dcounts = nullptr;        // 2 * classes
+    uint32_t *hcounts = nullptr;        // pinned, 2 * classes
+    // workspace
+    uint8_t *ws = nullptr;
+    size_t ws_bytes = 0;
+    uint32_t chunk = 0;
+    hipStream_t stream = nullptr;
+    std::vector<size_t> toff;           // per tensor offset inside the workspace
+    size_t logits_off = 0, argmax_off = 0, plan_bytes = 0;
+};
+
+namespace {
+
+// Offsets of every tensor for a chunk of B samples; buffers are reused once the
+// last op reading a tensor has been issued (stream order makes that safe).
+size_t plan_workspace(const ParsedModel &pm, uint32_t B, std::vector<size_t> &toff, size_t &logits_off,
+                      size_t &argmax_off) {
+    const int nt = (int)pm.tensors.size();
+    std::vector<int> last_use(nt, -1);
+    for (int i = 0; i < (int)pm.ops.size(); ++i) {
+        const HostOp &o = pm.ops[i];
+        if (o.a >= 0) last_use[o.a] = i;
+        if (o.b >= 0) last_use[o.b] = i;
+    }
+    auto tbytes = [&](int t) {
+        const TensorDesc &d = pm.tensors[t];
+        return round_up((size_t)B * d.H * d.W * d.Cp + 64, 256);
+    };
+    struct Block { size_t off, size; };
+    std::vector<Block> freelist;
+    size_t top = 0;
+    auto alloc = [&](size_t n) {
+        for (size_t i = 0; i < freelist.size(); ++i)
+            if (freelist[i].size >= n) {
+                size_t off = freelist[i].off;
+                freelist[i].off += n;
+                freelist[i].size -= n;
+                if (freelist[i].size == 0) freelist.erase(freelist.begin() + i);
+                return off;
+            }
+        size_t off = top;
+        top += n;
+        return off;
+    };
+    auto release = [&](size_t off, size_t n) {
+        freelist.push_back({off, n});
+        std::sort(freelist.begin(), freelist.end(), [](const Block &x, const Block &y) { return x.off < y.off; });
+        for (size_t i = 0; i + 1 < freelist.size();)
+            if (freelist[i].off + freelist[i].size == freelist[i + 1].off) {
+                freelist[i].size += freelist[i + 1].size;
+                freelist.erase(freelist.begin() + i + 1);
+            } else {
+                ++i;
+            }
+    };
+    toff.assign(nt, 0);
+    toff[0] = alloc(tbytes(0));
+    for (int i = 0; i < (int)pm.ops.size(); ++i) {
+        const HostOp &o = pm.ops[i];
+        if (o.type != OP_FC) toff[o.out] = alloc(tbytes(o.out));
+        for (int t : {o.a, o.b})
+            if (t >= 0 && last_use[t] == i && !(t == o.b && o.a == o.b)) release(toff[t], tbytes(t));
+    }
+    logits_off = round_up(top, 256);
+    argmax_off = logits_off + round_up((size_t)B * pm.classes * 4, 256);
+    return argmax_off + round_up((size_t)B * 4, 256);
+}
+
+struct ConstArena {
+    std::vector<uint8_t> host;
+    size_t put(const void *src, size_t n) {
+        size_t off = round_up(host.size(), 256);
+        host.resize(off + round_up(n, 16), 0);
+        if (src) std::memcpy(host.data() + off, src, n);
+        return off;
+    }
+};
+
+// Builds device descriptors; pointers into the constant arena are stored as
+// offsets first and rebased after the upload.
+int build_device_ops(isr_model *m, ConstArena &arena) {
+    const ParsedModel &pm = m->pm;
+    for (const HostOp &o : pm.ops) {
+        DevOp d;
+        d.type = o.type; d.a = o.a; d.b = o.b; d.out = o.out;
+        switch (o.type) {
+        case OP_CONV: {
+            const TensorDesc &ti = pm.tensors[o.a], &to = pm.tensors[o.out];
+            const bool c4 = o.a == 0;
+            const int cin_p = ti.Cp, cout_p = to.Cp, k = o.k;
+            const int kwp = (k + 3) & ~3;
+            const int kreal = c4 ? k * kwp * 4 : k * k * cin_p;
+            const int Kp = (int)round_up((size_t)kreal, 64), Mp = (int)round_up((size_t)cout_p, 128);
+            const bool perm = conv_tile_m(cout_p) != 16;
+            std::vector<int8_t> w((size_t)Mp * Kp, 0);
+            std::vector<int32_t> bias(Mp, 0);
+            std::vector<uint32_t> m0x2(Mp, 0x80000000u), rlo(Mp, 0), rhi(Mp, 1), sh(Mp, 1);
+            for (int oc = 0; oc < to.C; ++oc) {
+                int row = perm ? (oc & ~31) + mfma32_row_of_channel(oc & 31) : oc;
+                int64_t wsum = 0;
+                for (int ic = 0; ic < ti.C; ++ic)
+                    for (int ky = 0; ky < k; ++ky)
+                        for (int kx = 0; kx < k; ++kx) {
+                            int8_t v = o.w[(((size_t)oc * ti.C + ic) * k + ky) * k + kx];
+                            int kk = c4 ? (ky * kwp + kx) * 4 + ic : (ky * k + kx) * cin_p + ic;
+                            w[(size_t)row * Kp + kk] = v;
+                            wsum += v;
+                        }
+                int64_t b = (int64_t)o.bias[oc] - (int64_t)ti.zp * wsum;
+                if (b < INT32_MIN || b > INT32_MAX) return ISR_ERR_UNSUPPORTED;
+                bias[oc] = (int32_t)b;
+                m0x2[oc] = (uint32_t)o.M0[oc] << 1;
+                uint64_t rnd = 1ull << (31 + o.shift[oc]);
+                rlo[oc] = (uint32_t)rnd; rhi[oc] = (uint32_t)(rnd >> 32); sh[oc] = (uint32_t)o.shift[oc];
+            }
+            const bool flat = !c4 && k == 1 && o.stride == 1 && o.pad == 0 && cin_p % 64 == 0;
+            std::vector<uint32_t> ktab(Kp / 16, 0xFFFFFFFFu);
+            for (int j = 0; j < Kp / 16; ++j) {
+                if (c4) {
+                    int per_row = kwp / 4, ky = j / per_row, kx0 = (j % per_row) * 4;
+                    if (ky < k) ktab[j] = (uint32_t)ky | ((uint32_t)kx0 << 8);
+                } else {
+                    int k0 = j * 16, tap = k0 / cin_p, ic = k0 % cin_p;
+                    if (tap < k * k) ktab[j] = (uint32_t)(tap / k) | ((uint32_t)(tap % k) << 8) | ((uint32_t)ic << 16);
+                }
+            }
+            ConvParams &c = d.conv;
+            c.w = (const int8_t *)arena.put(w.data(), w.size());
+            c.bias = (const int32_t *)arena.put(bias.data(), bias.size() * 4);
+            c.m0x2 = (const uint32_t *)arena.put(m0x2.data(), m0x2.size() * 4);
+            c.rnd_lo = (const uint32_t *)arena.put(rlo.data(), rlo.size() * 4);
+            c.rnd_hi = (const uint32_t *)arena.put(rhi.data(), rhi.size() * 4);
+            c.shift = (const uint32_t *)arena.put(sh.data(), sh.size() * 4);
+            c.ktab = flat ? (const uint32_t *)~(uintptr_t)0 : (const uint32_t *)arena.put(ktab.data(), ktab.size() * 4);
+            c.H = ti.H; c.W = ti.W; c.Cin_p = cin_p; c.Ho = to.H; c.Wo = to.W; c.Cout_p = cout_p;
+            c.stride = o.stride; c.pad = o.pad; c.Kp = Kp; c.Mp = Mp;
+            c.zp_in = ti.zp; c.zp_out = to.zp; c.relu = o.relu; c.c4 = c4 ? 1 : 0;
+            break; }
+        case OP_ADD: {
+            AddParams &a = d.add;
+            a.za = pm.tensors[o.a].zp; a.zb = pm.tensors[o.b].zp; a.zo = pm.tensors[o.out].zp;
+            a.Ma = o.Ma; a.Mb = o.Mb; a.sh = o.sh; a.relu = o.relu;
+            break; }
+        case OP_MAXPOOL: {
+            const TensorDesc &ti = pm.tensors[o.a], &to = pm.tensors[o.out];
+            PoolParams &p = d.pool;
+            p.H = ti.H; p.W = ti.W; p.Cp = ti.Cp; p.Ho = to.H; p.Wo = to.W; p.k = o.k; p.stride = o.stride; p.pad = o.pad;
+            break; }
+        case OP_GAP: {
+            const TensorDesc &ti = pm.tensors[o.a], &to = pm.tensors[o.out];
+            GapParams &g = d.gap;
+            g.HW = ti.H * ti.W; g.Cp = ti.Cp; g.zp_in = ti.zp; g.zp_out = to.zp; g.M0 = o.Ma; g.sh = o.sh;
+            break; }
+        case OP_FC: {
+            const TensorDesc &ti = pm.tensors[o.a];
+            const int hw = ti.H * ti.W, Kp = hw * ti.Cp, classes = pm.classes;
+            std::vector<int8_t> w((size_t)classes * Kp, 0);
+            std::vector<int32_t> bias(classes, 0);
+            for (int c = 0; c < classes; ++c) {
+                int64_t wsum = 0;
+                for (int ch = 0; ch < ti.C; ++ch)
+                    for (int s = 0; s < hw; ++s) {
+                        int8_t v = o.w[(size_t)c * ti.C * hw + (size_t)ch * hw + s];
+                        w[(size_t)c * Kp + (size_t)s * ti.Cp + ch] = v;
+                        wsum += v;
+                    }
+                int64_t b = (int64_t)o.bias[c] - (int64_t)ti.zp * wsum;
+                if (b < INT32_MIN || b > INT32_MAX) return ISR_ERR_UNSUPPORTED;
+                bias[c] = (int32_t)b;
+            }
+            FcParams &f = d.fc;
+            f.w = (const int8_t *)arena.put(w.data(), w.size());
+            f.bias = (const int32_t *)arena.put(bias.data(), bias.size() * 4);
+            f.Kp = Kp; f.classes = classes;
+            break; }
+        }
+        m->ops.push_back(d);
+    }
+    return ISR_OK;
+}
+
+template <typename T>
+void rebase(const T *&p, const uint8_t *base) {
+    if ((uintptr_t)p == ~(uintptr_t)0) { p = nullptr; return; }
+    p = (const T *)(base + (uintptr_t)p);
+}
+
+int get_table(isr_model *m, uint32_t sigma, const DeviceNoiseTable **out) {
+    for (int i = 0; i < TABLE_SLOTS; ++i)
+        if (m->table_sigma[i] == sigma) { *out = m->dtables + i; return ISR_OK; }
+    int slot = m->table_next;
+    m->table_next = (slot + 1) % TABLE_SLOTS;
+    // the staging slot may still be in flight from an earlier call on this stream
+    HIP_TRY(hipStreamSynchronize(m->stream));
+    if (!build_device_table(sigma, m->htables[slot])) return ISR_ERR_ARG;
+    HIP_TRY(hipMemcpyAsync(m->dtables + slot, m->htables + slot, sizeof(DeviceNoiseTable), hipMemcpyHostToDevice, m->stream));
+    m->table_sigma[slot] = sigma;
+    *out = m->dtables + slot;
+    return ISR_OK;
+}
+
+// Enqueues the Monte-Carlo loop for sample indices [begin, begin+count) of one
+// phase.  Optional outputs: per-sample logits / argmax (device buffers inside
+// the workspace, copied to the host pointers chunk by chunk) and the device
+// vote counters.  stop_tensor >= 0 ends each forward right after that tensor.
+int run_range(isr_model *m, const uint8_t *x, const DeviceNoiseTable *table, uint64_t seed, uint32_t image,
+              uint32_t phase, uint32_t begin, uint32_t count, int32_t *logits_host, int32_t *argmax_host,
+              uint32_t *dcounts, int stop_tensor) {
+    const ParsedModel &pm = m->pm;
+    uint8_t *ws = m->ws;
+    for (uint32_t done = 0; done < count;) {
+        const uint32_t cnt = std::min(m->chunk, count - done);
+        NoiseParams np;
+        np.x = x; np.table = table; np.out = (int8_t *)(ws + m->toff[0]);
+        np.C = pm.C; np.H = pm.H; np.W = pm.W;
+        np.key0 = (uint32_t)seed; np.key1 = (uint32_t)(seed >> 32);
+        np.image = image; np.phase = phase; np.sample_begin = begin + done; np.count = cnt;
+        HIP_TRY(launch_noise(np, m->stream));
+        if (stop_tensor != 0) {
+            for (const DevOp &d : m->ops) {
+                switch (d.type) {
+                case OP_CONV: {
+                    ConvParams c = d.conv;
+                    c.in = (const int8_t *)(ws + m->toff[d.a]);
+                    c.out = (int8_t *)(ws + m->toff[d.out]);
+                    c.npix = (int32_t)(cnt * c.Ho * c.Wo);
+                    HIP_TRY(launch_conv(c, m->stream));
+                    break; }
+                case OP_ADD: {
+                    AddParams a = d.add;
+                    const TensorDesc &t = pm.tensors[d.out];
+                    a.a = (const int8_t *)(ws + m->toff[d.a]);
+                    a.b = (const int8_t *)(ws + m->toff[d.b]);
+                    a.out = (int8_t *)(ws + m->toff[d.out]);
+                    a.n16 = (int64_t)cnt * t.H * t.W * t.Cp / 16;
+                    HIP_TRY(launch_add(a, m->stream));
+                    break; }
+                case OP_MAXPOOL: {
+                    PoolParams p = d.pool;
+                    p.in = (const int8_t *)(ws + m->toff[d.a]);
+                    p.out = (int8_t *)(ws + m->toff[d.out]);
+                    p.B = (int32_t)cnt;
+                    HIP_TRY(launch_maxpool(p, m->stream));
+                    break; }
+                case OP_GAP: {
+                    GapParams g = d.gap;
+                    g.in = (const int8_t *)(ws + m->toff[d.a]);
+                    g.out = (int8_t *)(ws + m->toff[d.out]);
+                    g.B = (int32_t)cnt;
+                    HIP_TRY(launch_gap(g, m->stream));
+                    break; }
+                case OP_FC: {
+                    FcParams f = d.fc;
+                    f.in = (const int8_t *)(ws + m->toff[d.a]);
+                    f.B = (int32_t)cnt;
+                    f.logits = logits_host ? (int32_t *)(ws + m->logits_off) : nullptr;
+                    f.argmax = argmax_host ? (int32_t *)(ws + m->argmax_off) : nullptr;
+                    f.counts = dcounts;
+                    HIP_TRY(launch_fc(f, m->stream));
+                    break; }
+                }
+                if (stop_tensor > 0 && d.out == stop_tensor) break;
+            }
+        }
+        if (logits_host) {
+            HIP_TRY(hipMemcpyAsync(logits_host + (size_t)done * pm.classes, ws + m->logits_off,
+                                   (size_t)cnt * pm.classes * 4, hipMemcpyDeviceToHost, m->stream));
+        }
+        if (argmax_host) {
+            HIP_TRY(hipMemcpyAsync(argmax_host + done, ws + m->argmax_off, (size_t)cnt * 4,
+                                   hipMemcpyDeviceToHost, m->stream));
+        }
+        if (logits_host || argmax_host) HIP_TRY(hipStreamSynchronize(m->stream));
+        done += cnt;
+    }
+    return ISR_OK;
+}
+
+int check_call(const isr_model *m, const void *x, uint32_t sigma, double alpha, bool need_alpha) {
+    if (!m || !x) return ISR_ERR_ARG;
+    if (sigma < 1 || sigma > 1024) return ISR_ERR_ARG;
+    if (need_alpha && !(alpha > 0.0 && alpha < 1.0)) return ISR_ERR_ARG;
+    if (!m->ws || m->chunk == 0) return ISR_ERR_WORKSPACE;
+    return ISR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int isr_load_model(const void *blob_host, size_t bytes, isr_model **out) {
+    if (!blob_host || !out) return ISR_ERR_ARG;
+    *out = nullptr;
+    isr_model *m = new (std::nothrow) isr_model();
+    if (!m) return ISR_ERR_ARG;
+    std::string why;
+    int rc = parse_model(blob_host, bytes, m->pm, why);
+    if (rc != ISR_OK) { delete m; return rc; }
+    ConstArena arena;
+    arena.put(nullptr, 256);  // offset 0 is never a valid table
+    rc = build_device_ops(m, arena);
+    if (rc != ISR_OK) { delete m; return rc; }
+    auto cleanup = [&](int code) { isr_free_model(m); return code; };
+    hipError_t e = hipMalloc((void **)&m->dconst, arena.host.size());
+    if (e == hipSuccess) e = hipMemcpy(m->dconst, arena.host.data(), arena.host.size(), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMalloc((void **)&m->dtables, sizeof(DeviceNoiseTable) * TABLE_SLOTS);
+    if (e == hipSuccess) e = hipHostMalloc((void **)&m->htables, sizeof(DeviceNoiseTable) * TABLE_SLOTS, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipMalloc((void **)&m->dcounts, sizeof(uint32_t) * 2 * m->pm.classes);
+    if (e == hipSuccess) e = hipHostMalloc((void **)&m->hcounts, sizeof(uint32_t) * 2 * m->pm.classes, hipHostMallocDefault);
+    if (e != hipSuccess) { g_last_hip_error = (int)e; return cleanup(ISR_ERR_DEVICE); }
+    for (DevOp &d : m->ops) {
+        if (d.type == OP_CONV) {
+            rebase(d.conv.w, m->dconst); rebase(d.conv.bias, m->dconst); rebase(d.conv.m0x2, m->dconst);
+            rebase(d.conv.rnd_lo, m->dconst); rebase(d.conv.rnd_hi, m->dconst); rebase(d.conv.shift, m->dconst);
+            rebase(d.conv.ktab, m->dconst);
+        } else if (d.type == OP_FC) {
+            rebase(d.fc.w, m->dconst); rebase(d.fc.bias, m->dconst);
+        }
+    }
+    *out = m;
+    return ISR_OK;
+}
+
+int isr_free_model(isr_model *m) {
+    if (!m) return ISR_OK;
+    if (m->dconst) (void)hipFree(m->dconst);
+    if (m->dtables) (void)hipFree(m->dtables);
+    if (m->htables) (void)hipHostFree(m->htables);
+    if (m->dcounts) (void)hipFree(m->dcounts);
+    if (m->hcounts) (void)hipHostFree(m->hcounts);
+    delete m;
+    return ISR_OK;
+}
+
+int isr_model_info(const isr_model *m, int *C, int *H, int *W, int *num_classes) {
+    if (!m) return ISR_ERR_ARG;
+    if (C) *C = m->pm.C;
+    if (H) *H = m->pm.H;
+    if (W) *W = m->pm.W;
+    if (num_classes) *num_classes = m->pm.classes;
+    return ISR_OK;
+}
+
+size_t isr_workspace_bytes(const isr_model *m, uint32_t chunk_samples) {
+    if (!m || chunk_samples == 0) return 0;
+    std::vector<size_t> toff;
+    size_t lo, ao;
+    return plan_workspace(m->pm, chunk_samples, toff, lo, ao);
+}
+
+int isr_set_workspace(isr_model *m, void *workspace_device, size_t bytes, uint32_t chunk_samples, void *hip_stream) {
+    if (!m || !workspace_device || chunk_samples == 0) return ISR_ERR_ARG;
+    if ((uintptr_t)workspace_device % 256 != 0) return ISR_ERR_ARG;
+    // pixel counts of a chunk are kept in 32 bits inside the kernels
+    for (const TensorDesc &t : m->pm.tensors)
+        if ((uint64_t)chunk_samples * t.H * t.W * std::max(t.Cp, 16) >= (1ull << 31)) return ISR_ERR_ARG;
+    std::vector<size_t> toff;
+    size_t lo, ao;
+    size_t need = plan_workspace(m->pm, chunk_samples, toff, lo, ao);
+    if (bytes < need) return ISR_ERR_WORKSPACE;
+    m->ws = (uint8_t *)workspace_device;
+    m->ws_bytes = bytes;
+    m->chunk = chunk_samples;
+    m->stream = (hipStream_t)hip_stream;
+    m->toff = toff;
+    m->logits_off = lo;
+    m->argmax_off = ao;
+    m->plan_bytes = need;
+    return ISR_OK;
+}
+
+int isr_certify(isr_model *m, const uint8_t *x_device, uint32_t sigma, uint32_t n0, uint32_t n, double alpha,
+                uint64_t seed, uint32_t image_id, isr_result *out, uint32_t *counts0_host, uint32_t *counts1_host) {
+    int rc = check_call(m, x_device, sigma, alpha, true);
+    if (rc != ISR_OK) return rc;
+    if (!out || n0 == 0 || n == 0) return ISR_ERR_ARG;
+    const uint32_t C = (uint32_t)m->pm.classes;
+    const DeviceNoiseTable *table = nullptr;
+    if ((rc = get_table(m, sigma, &table)) != ISR_OK) return rc;
+    HIP_TRY(launch_fill_u32(m->dcounts, 0, 2 * C, m->stream));
+    if ((rc = run_range(m, x_device, table, seed, image_id, 0, 0, n0, nullptr, nullptr, m->dcounts, -1)) != ISR_OK) return rc;
+    if ((rc = run_range(m, x_device, table, seed, image_id, 1, 0, n, nullptr, nullptr, m->dcounts + C, -1)) != ISR_OK) return rc;
+    HIP_TRY(hipMemcpyAsync(m->hcounts, m->dcounts, sizeof(uint32_t) * 2 * C, hipMemcpyDeviceToHost, m->stream));
+    HIP_TRY(hipStreamSynchronize(m->stream));
+    if (counts0_host) std::memcpy(counts0_host, m->hcounts, sizeof(uint32_t) * C);
+    if (counts1_host) std::memcpy(counts1_host, m->hcounts + C, sizeof(uint32_t) * C);
+    return isr_decide_certify(m->hcounts, m->hcounts + C, C, (double)sigma, n, alpha, out);
+}
+
+int isr_predict(isr_model *m, const uint8_t *x_device, uint32_t sigma, uint32_t n, double alpha, uint64_t seed,
+                uint32_t image_id, isr_result *out, uint32_t *counts_host) {
+    int rc = check_call(m, x_device, sigma, alpha, true);
+    if (rc != ISR_OK) return rc;
+    if (!out || n == 0) return ISR_ERR_ARG;
+    const uint32_t C = (uint32_t)m->pm.classes;
+    const DeviceNoiseTable *table = nullptr;
+    if ((rc = get_table(m, sigma, &table)) != ISR_OK) return rc;
+    HIP_TRY(launch_fill_u32(m->dcounts, 0, C, m->stream));
+    if ((rc = run_range(m, x_device, table, seed, image_id, 0, 0, n, nullptr, nullptr, m->dcounts, -1)) != ISR_OK) return rc;
+    HIP_TRY(hipMemcpyAsync(m->hcounts, m->dcounts, sizeof(uint32_t) * C, hipMemcpyDeviceToHost, m->stream));
+    HIP_TRY(hipStreamSynchronize(m->stream));
+    if (counts_host) std::memcpy(counts_host, m->hcounts, sizeof(uint32_t) * C);
+    return isr_decide_predict(m->hcounts, C, alpha, out);
+}
+
+int isr_debug_noisy(isr_model *m, const uint8_t *x_device, uint32_t sigma, uint64_t seed, uint32_t image_id,
+                    uint32_t phase, uint32_t sample_begin, uint32_t count, int8_t *out_host) {
+    int rc = check_call(m, x_device, sigma, 0.5, false);
+    if (rc != ISR_OK) return rc;
+    if (!out_host || count == 0 || count > m->chunk || phase > 1) return ISR_ERR_ARG;
+    const DeviceNoiseTable *table = nullptr;
+    if ((rc = get_table(m, sigma, &table)) != ISR_OK) return rc;
+    if ((rc = run_range(m, x_device, table, seed, image_id, phase, sample_begin, count, nullptr, nullptr, nullptr, 0)) != ISR_OK) return rc;
+    const ParsedModel &pm = m->pm;
+    const size_t hw = (size_t)pm.H * pm.W;
+    std::vector<int8_t> tmp(count * hw * 4);
+    HIP_TRY(hipMemcpyAsync(tmp.data(), m->ws + m->toff[0], tmp.size(), hipMemcpyDeviceToHost, m->stream));
+    HIP_TRY(hipStreamSynchronize(m->stream));
+    for (uint32_t s = 0; s < count; ++s)
+        for (int c = 0; c < pm.C; ++c)
+            for (size_t i = 0; i < hw; ++i) out_host[((size_t)s * pm.C + c) * hw + i] = tmp[((size_t)s * hw + i) * 4 + c];
+    return ISR_OK;
+}
+
+int isr_debug_forward(isr_model *m, const uint8_t *x_device, uint32_t sigma, uint64_t seed, uint32_t image_id,
+                      uint32_t phase, uint32_t sample_begin, uint32_t count, int32_t *logits_host,
+                      int32_t *argmax_host, uint32_t *counts_host) {
+    int rc = check_call(m, x_device, sigma, 0.5, false);
+    if (rc != ISR_OK) return rc;
+    if (count == 0 || phase > 1) return ISR_ERR_ARG;
+    const uint32_t C = (uint32_t)m->pm.classes;
+    const DeviceNoiseTable *table = nullptr;
+    if ((rc = get_table(m, sigma, &table)) != ISR_OK) return rc;
+    if (counts_host) HIP_TRY(launch_fill_u32(m->dcounts, 0, C, m->stream));
+    rc = run_range(m, x_device, table, seed, image_id, phase, sample_begin, count, logits_host, argmax_host,
+                   counts_host ? m->dcounts : nullptr, -1);
+    if (rc != ISR_OK) return rc;
+    if (counts_host) {
+        HIP_TRY(hipMemcpyAsync(m->hcounts, m->dcounts, sizeof(uint32_t) * C, hipMemcpyDeviceToHost, m->stream));
+        HIP_TRY(hipStreamSynchronize(m->stream));
+        for (uint32_t i = 0; i < C; ++i) counts_host[i] += m->hcounts[i];
+    } else {
+        HIP_TRY(hipStreamSynchronize(m->stream));
+    }
+    return ISR_OK;
+}
+
+int isr_debug_tensor(isr_model *m, const uint8_t *x_device, uint32_t sigma, uint64_t seed, uint32_t image_id,
+                     uint32_t phase, uint32_t sample, int32_t tensor_id, int8_t *out_host) {
+    int rc = check_call(m, x_device, sigma, 0.5, false);
+    if (rc != ISR_OK) return rc;
+    const ParsedModel &pm = m->pm;
+    if (!out_host || phase > 1 || tensor_id < 0 || tensor_id >= (int)pm.tensors.size() || tensor_id == pm.ops.back().out)
+        return ISR_ERR_ARG;
+    const DeviceNoiseTable *table = nullptr;
+    if ((rc = get_table(m, sigma, &table)) != ISR_OK) return rc;
+    if ((rc = run_range(m, x_device, table, seed, image_id, phase, sample, 1, nullptr, nullptr, nullptr, tensor_id)) != ISR_OK) return rc;
+    const TensorDesc &t = pm.tensors[tensor_id];
+    const size_t hw = (size_t)t.H * t.W;
+    std::vector<int8_t> tmp(hw * t.Cp);
+    HIP_TRY(hipMemcpyAsync(tmp.data(), m->ws + m->toff[tensor_id], tmp.size(), hipMemcpyDeviceToHost, m->stream));
+    HIP_TRY(hipStreamSynchronize(m->stream));
+    for (int c = 0; c < t.C; ++c)
+        for (size_t i = 0; i < hw; ++i) out_host[(size_t)c * hw + i] = tmp[i * t.Cp + c];
+    return ISR_OK;
+}
+
+const char *isr_strerror(int status) {
+    switch (status) {
+    case ISR_OK: return "ok";
+    case ISR_ERR_ARG: return "invalid argument";
+    case ISR_ERR_FORMAT: return "malformed model blob";
+    case ISR_ERR_UNSUPPORTED: return "model uses a shape or op the kernels do not cover";
+    case ISR_ERR_WORKSPACE: return "workspace missing or too small";
+    case ISR_ERR_DEVICE: return "HIP call failed";
+    default: return "unknown status";
+    }
+}
+
+int isr_last_device_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,269 @@
+// int8 implicit-GEMM convolution on CDNA4 MFMA with the requantisation epilogue.
+//
+// GEMM view of one convolution layer over a chunk of noisy copies:
+//   rows    M = output channels            (A operand: weights, [Mp][Kp], K contiguous)
+//   columns N = B*Ho*Wo output pixels      (B operand: activations gathered on the fly)
+//   depth   K = taps x input channels      (channel-contiguous NHWC, so a 16-byte
+//                                           K chunk is 16 channels of one tap)
+// acc (int32) starts at bias - z_in * sum(w) so that the kernel can multiply raw
+// int8 activations; out-of-image taps are filled with z_in and so contribute 0.
+// Epilogue: q = clamp(z_out + RHA(acc * M0, 31 + shift), relu ? z_out : -128, 127),
+// one rounding, half away from zero, written as int8 NHWC.
+//
+// Tile: 256 threads = 4 waves; a BM x BN block of the output, K consumed in
+// 64-byte steps staged through LDS (double buffered, register prefetch).
+// MT = 32 uses v_mfma_i32_32x32x32_i8, MT = 16 uses v_mfma_i32_16x16x64_i8.
+#include "isr_internal.h"
+
+namespace isr {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+// 16-byte chunk swizzle inside a 64-byte LDS row: spreads equal chunk indices of
+// neighbouring rows over different banks for the 128-bit fragment reads.
+__device__ __forceinline__ int swz(int row) { return ((row >> 1) ^ (row >> 3)) & 3; }
+
+// RHA(acc * M0, 31 + shift) on magnitude and sign, 32x32->64 multiply-add:
+//   |acc| * (M0 << 1) + 2^(31+shift) = 2 * (|acc| * M0 + 2^(30+shift)),
+// so the rounded quotient is the high word shifted right by `shift`.
+__device__ __forceinline__ int requant(int acc, uint32_t m0x2, uint32_t rnd_lo, uint32_t rnd_hi, uint32_t sh) {
+    uint32_t mag = (uint32_t)(acc < 0 ? -acc : acc);
+    uint64_t prod = (uint64_t)mag * (uint64_t)m0x2 + (((uint64_t)rnd_hi << 32) | rnd_lo);
+    int r = (int)((uint32_t)(prod >> 32) >> sh);
+    return acc < 0 ? -r : r;
+}
+
+__device__ __forceinline__ uint32_t pack4(int a, int b, int c, int d) {
+    return (uint32_t)(a & 0xFF) | ((uint32_t)(b & 0xFF) << 8) | ((uint32_t)(c & 0xFF) << 16) | ((uint32_t)d << 24);
+}
+
+template <int MT, int BM, int BN, int WGM>
+__global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
+    constexpr int WGN = 4 / WGM;
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int FM = WM / MT, FN = WN / MT;
+    constexpr int NA = (BM * 4 + 255) / 256, NB = BN * 4 / 256;
+    constexpr int ACC = MT == 32 ? 16 : 4;
+    static_assert(WM % MT == 0 && WN % MT == 0 && BN % 64 == 0, "tile shape");
+
+    __shared__ __attribute__((aligned(16))) int8_t As[2][BM * 64];
+    __shared__ __attribute__((aligned(16))) int8_t Bs[2][BN * 64];
+    __shared__ uint32_t ktab_s[1024];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WGM, wn = wave / WGM;
+    const int m0 = blockIdx.y * BM;
+    const long n0 = (long)blockIdx.x * BN;
+    const int nk = p.Kp >> 6;
+    const int col = tid & 3, row0 = tid >> 2;
+    const bool flat = p.ktab == nullptr;   // 1x1, stride 1, no padding: pixel n reads input pixel n
+
+    if (!flat)
+        for (int i = tid; i < nk * 4; i += 256) ktab_s[i] = p.ktab[i];
+
+    // per-thread gather state for its NB activation rows
+    long base[NB];
+    int iy0[NB], ix0[NB];
+    bool rvalid[NB];
+    const int HoWo = p.Ho * p.Wo;
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        long n = n0 + row0 + 64 * j;
+        rvalid[j] = n < p.npix;
+        if (flat) {
+            base[j] = n * p.Cin_p;
+            iy0[j] = ix0[j] = 0;
+        } else {
+            long nn = rvalid[j] ? n : 0;
+            int b = (int)(nn / HoWo);
+            int rem = (int)(nn - (long)b * HoWo);
+            int oy = rem / p.Wo, ox = rem - oy * p.Wo;
+            base[j] = (long)b * p.H * p.W * p.Cin_p;
+            iy0[j] = oy * p.stride - p.pad;
+            ix0[j] = ox * p.stride - p.pad;
+        }
+    }
+    const uint32_t zb = (uint32_t)(p.zp_in & 0xFF) * 0x01010101u;
+    const v4i zfill = {(int)zb, (int)zb, (int)zb, (int)zb};
+    const int8_t *wrow[NA];
+#pragma unroll
+    for (int j = 0; j < NA; ++j) wrow[j] = p.w + (long)(m0 + row0 + 64 * j) * p.Kp + col * 16;
+
+    v4i ra[NA], rb[NB];
+
+    auto load_global = [&](int ks) {
+#pragma unroll
+        for (int j = 0; j < NA; ++j)
+            if (BM * 4 >= 256 || row0 + 64 * j < BM) ra[j] = *(const v4i *)(wrow[j] + (long)ks * 64);
+        if (flat) {
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+                rb[j] = rvalid[j] ? *(const v4i *)(p.in + base[j] + ks * 64 + col * 16) : zfill;
+        } else if (!p.c4) {
+            uint32_t e = ktab_s[ks * 4 + col];
+            int ky = e & 0xFF, kx = (e >> 8) & 0xFF, ic = e >> 16;
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                int iy = iy0[j] + ky, ix = ix0[j] + kx;
+                bool ok = rvalid[j] && e != 0xFFFFFFFFu && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
+                rb[j] = ok ? *(const v4i *)(p.in + base[j] + ((long)iy * p.W + ix) * p.Cin_p + ic) : zfill;
+            }
+        } else {
+            uint32_t e = ktab_s[ks * 4 + col];
+            int ky = e & 0xFF, kx = (e >> 8) & 0xFF;
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                int iy = iy0[j] + ky;
+                bool rowok = rvalid[j] && e != 0xFFFFFFFFu && (unsigned)iy < (unsigned)p.H;
+                const int8_t *src = p.in + base[j] + (long)iy * p.W * 4;
+                v4i v;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    int ix = ix0[j] + kx + t;
+                    bool ok = rowok && (unsigned)ix < (unsigned)p.W;
+                    v[t] = ok ? *(const int *)(src + ix * 4) : (int)zb;
+                }
+                rb[j] = v;
+            }
+        }
+    };
+    auto store_lds = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < NA; ++j) {
+            int r = row0 + 64 * j;
+            if (BM * 4 >= 256 || r < BM) *(v4i *)(&As[buf][r * 64 + ((col ^ swz(r)) << 4)]) = ra[j];
+        }
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            int r = row0 + 64 * j;
+            *(v4i *)(&Bs[buf][r * 64 + ((col ^ swz(r)) << 4)]) = rb[j];
+        }
+    };
+
+    // accumulators start at the folded bias
+    typedef int acc_t __attribute__((ext_vector_type(ACC)));
+    acc_t acc[FM][FN];
+#pragma unroll
+    for (int fm = 0; fm < FM; ++fm) {
+        acc_t init;
+        if constexpr (MT == 32) {
+            const int *bp = p.bias + m0 + wm * WM + fm * 32 + 16 * (lane >> 5);
+#pragma unroll
+            for (int i = 0; i < ACC; ++i) init[i] = bp[i];
+        } else {
+            const int *bp = p.bias + m0 + wm * WM + fm * 16 + 4 * (lane >> 4);
+#pragma unroll
+            for (int i = 0; i < ACC; ++i) init[i] = bp[i];
+        }
+#pragma unroll
+        for (int fn = 0; fn < FN; ++fn) acc[fm][fn] = init;
+    }
+
+    __syncthreads();   // ktab_s visible
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+
+    for (int ks = 0; ks < nk; ++ks) {
+        const int buf = ks & 1;
+        if (ks + 1 < nk) load_global(ks + 1);
+        if constexpr (MT == 32) {
+#pragma unroll
+            for (int ksub = 0; ksub < 2; ++ksub) {
+                const int c = ksub * 2 + (lane >> 5);
+                v4i fa[FM], fb[FN];
+#pragma unroll
+                for (int fm = 0; fm < FM; ++fm) {
+                    int r = wm * WM + fm * 32 + (lane & 31);
+                    fa[fm] = *(const v4i *)(&As[buf][r * 64 + ((c ^ swz(r)) << 4)]);
+                }
+#pragma unroll
+                for (int fn = 0; fn < FN; ++fn) {
+                    int r = wn * WN + fn * 32 + (lane & 31);
+                    fb[fn] = *(const v4i *)(&Bs[buf][r * 64 + ((c ^ swz(r)) << 4)]);
+                }
+#pragma unroll
+                for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+                    for (int fn = 0; fn < FN; ++fn)
+                        acc[fm][fn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[fm], fb[fn], acc[fm][fn], 0, 0, 0);
+            }
+        } else {
+            const int c = lane >> 4;
+            v4i fa[FM], fb[FN];
+#pragma unroll
+            for (int fm = 0; fm < FM; ++fm) {
+                int r = wm * WM + fm * 16 + (lane & 15);
+                fa[fm] = *(const v4i *)(&As[buf][r * 64 + ((c ^ swz(r)) << 4)]);
+            }
+#pragma unroll
+            for (int fn = 0; fn < FN; ++fn) {
+                int r = wn * WN + fn * 16 + (lane & 15);
+                fb[fn] = *(const v4i *)(&Bs[buf][r * 64 + ((c ^ swz(r)) << 4)]);
+            }
+#pragma unroll
+            for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+                for (int fn = 0; fn < FN; ++fn)
+                    acc[fm][fn] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[fm], fb[fn], acc[fm][fn], 0, 0, 0);
+        }
+        if (ks + 1 < nk) store_lds(buf ^ 1);
+        __syncthreads();
+    }
+
+    // epilogue: requantise, clamp, pack, store (NHWC)
+    const int lo = p.relu ? p.zp_out : -128;
+#pragma unroll
+    for (int fm = 0; fm < FM; ++fm) {
+        const int oc = m0 + wm * WM + fm * MT + (MT == 32 ? 16 * (lane >> 5) : 4 * (lane >> 4));
+        if (oc >= p.Cout_p) continue;
+        uint32_t mm[ACC], rl[ACC], rh[ACC], ss[ACC];
+#pragma unroll
+        for (int i = 0; i < ACC; ++i) {
+            mm[i] = p.m0x2[oc + i]; rl[i] = p.rnd_lo[oc + i]; rh[i] = p.rnd_hi[oc + i]; ss[i] = p.shift[oc + i];
+        }
+#pragma unroll
+        for (int fn = 0; fn < FN; ++fn) {
+            long n = n0 + wn * WN + fn * MT + (lane & (MT - 1));
+            if (n >= p.npix) continue;
+            int q[ACC];
+#pragma unroll
+            for (int i = 0; i < ACC; ++i) {
+                int r = p.zp_out + requant(acc[fm][fn][i], mm[i], rl[i], rh[i], ss[i]);
+                q[i] = r < lo ? lo : (r > 127 ? 127 : r);
+            }
+            int8_t *dst = p.out + n * p.Cout_p + oc;
+            if constexpr (MT == 32) {
+                v4i v = {(int)pack4(q[0], q[1], q[2], q[3]), (int)pack4(q[4], q[5], q[6], q[7]),
+                         (int)pack4(q[8], q[9], q[10], q[11]), (int)pack4(q[12], q[13], q[14], q[15])};
+                *(v4i *)dst = v;
+            } else {
+                *(uint32_t *)dst = pack4(q[0], q[1], q[2], q[3]);
+            }
+        }
+    }
+}
+
+int conv_tile_m(int cout_p) { return cout_p <= 16 ? 16 : (cout_p <= 32 ? 32 : (cout_p <= 64 ? 64 : 128)); }
+
+template <int MT, int BM, int BN, int WGM>
+static hipError_t launch_one(const ConvParams &p, hipStream_t st) {
+    dim3 grid((unsigned)((p.npix + BN - 1) / BN), (unsigned)((p.Cout_p + BM - 1) / BM));
+    hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM>), grid, dim3(256), 0, st, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_conv(const ConvParams &p, hipStream_t st) {
+    if (p.npix <= 0) return hipSuccess;
+    if (p.Kp % 64 != 0 || p.Kp > 16384 || p.Cout_p % 16 != 0 || p.Mp % 128 != 0 || p.Mp < p.Cout_p)
+        return hipErrorInvalidValue;
+    switch (conv_tile_m(p.Cout_p)) {
+    case 16: return launch_one<16, 16, 256, 1>(p, st);
+    case 32: return launch_one<32, 32, 256, 1>(p, st);
+    case 64: return launch_one<32, 64, 256, 1>(p, st);
+    default: return launch_one<32, 128, 256, 2>(p, st);
+    }
+}
+
+}  // namespace isr

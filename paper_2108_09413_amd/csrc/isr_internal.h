@@ -1,0 +1,127 @@
+// Internal declarations shared by the host code and the kernel launchers.
+#ifndef ISR_INTERNAL_H
+#define ISR_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+
+#include <cstddef>
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "isr.h"
+
+namespace isr {
+
+// ---- noise table -----------------------------------------------------------
+constexpr uint32_t NOISE_TABLE_MAX = 512;   // >= 510 thresholds between -255 and 255
+constexpr uint32_t NOISE_GUIDE_BITS = 10;
+constexpr uint32_t NOISE_GUIDE_SIZE = 1u << NOISE_GUIDE_BITS;
+
+struct DeviceNoiseTable {
+    uint32_t hi[NOISE_TABLE_MAX];
+    uint32_t lo[NOISE_TABLE_MAX];
+    uint16_t guide[NOISE_GUIDE_SIZE + 2];
+    uint32_t n;      // thresholds in use
+    int32_t dmin;    // delta = dmin + #{j < n : T[j] <= u}
+};
+
+bool build_noise_table(uint32_t sigma, std::vector<uint64_t> &T, uint32_t &R);
+bool build_device_table(uint32_t sigma, DeviceNoiseTable &out);
+
+// ---- parsed model (host) ---------------------------------------------------
+enum OpType : int32_t { OP_CONV = 1, OP_ADD = 2, OP_MAXPOOL = 3, OP_GAP = 4, OP_FC = 5 };
+
+struct TensorDesc {
+    int32_t C, H, W, zp;
+    int32_t Cp;          // channels as stored on the device (multiple of 16; 4 for the input)
+};
+
+struct HostOp {
+    OpType type;
+    int32_t a = -1, b = -1, out = -1;
+    int32_t k = 0, stride = 1, pad = 0, relu = 0;
+    int32_t Ma = 0, Mb = 0, sh = 0;
+    std::vector<int8_t> w;                  // CONV: OIHW, FC: [Cout][Cin]
+    std::vector<int32_t> bias, M0, shift;
+};
+
+struct ParsedModel {
+    int32_t C = 0, H = 0, W = 0, classes = 0;
+    std::vector<TensorDesc> tensors;
+    std::vector<HostOp> ops;
+};
+
+// Returns ISR_OK / ISR_ERR_FORMAT / ISR_ERR_UNSUPPORTED; `why` gets a short reason.
+int parse_model(const void *blob, size_t bytes, ParsedModel &out, std::string &why);
+
+// ---- device-side op descriptors -------------------------------------------
+struct ConvParams {
+    const int8_t *in;        // [B][H][W][Cin_p]
+    int8_t *out;             // [B][Ho][Wo][Cout_p]
+    const int8_t *w;         // [Mp][Kp] rows in MFMA row order, K = (tap, channel)
+    const int32_t *bias;     // [Mp] bias - z_in * sum(w)
+    const uint32_t *m0x2;    // [Mp] M0 << 1
+    const uint32_t *rnd_lo;  // [Mp] low / high word of 2^(31 + shift)
+    const uint32_t *rnd_hi;
+    const uint32_t *shift;   // [Mp]
+    const uint32_t *ktab;    // [Kp/16] packed (ky | kx<<8 | ic<<16), 0xFFFFFFFF = no tap
+    int32_t H, W, Cin_p, Ho, Wo, Cout_p;
+    int32_t stride, pad, Kp, Mp;
+    int32_t zp_in, zp_out, relu;
+    int32_t npix;            // B * Ho * Wo
+    int32_t c4;              // 1: input is NHWC4 and a K chunk is 4 horizontal taps
+};
+
+struct AddParams {
+    const int8_t *a, *b;
+    int8_t *out;
+    int32_t za, zb, zo, Ma, Mb, sh, relu;
+    int64_t n16;             // number of 16-byte groups
+};
+
+struct PoolParams {
+    const int8_t *in;
+    int8_t *out;
+    int32_t H, W, Cp, Ho, Wo, k, stride, pad;
+    int32_t B;
+};
+
+struct GapParams {
+    const int8_t *in;        // [B][HW][Cp]
+    int8_t *out;             // [B][Cp]
+    int32_t HW, Cp, zp_in, zp_out, M0, sh, B;
+};
+
+struct FcParams {
+    const int8_t *in;        // [B][Kp]
+    const int8_t *w;         // [classes][Kp]
+    const int32_t *bias;     // [classes], bias - z_in * sum(w)
+    int32_t Kp, classes, B;
+    int32_t *logits;         // [B][classes] or null
+    int32_t *argmax;         // [B] or null
+    uint32_t *counts;        // [classes] (accumulated) or null
+};
+
+struct NoiseParams {
+    const uint8_t *x;        // [C][H][W] clean image
+    const DeviceNoiseTable *table;
+    int8_t *out;             // [B][H][W][4]
+    int32_t C, H, W;
+    uint32_t key0, key1, image, phase, sample_begin, count;
+};
+
+// Kernel launchers (kernels.hip / conv_igemm.hip).  All asynchronous on `st`.
+hipError_t launch_noise(const NoiseParams &p, hipStream_t st);
+hipError_t launch_conv(const ConvParams &p, hipStream_t st);
+hipError_t launch_add(const AddParams &p, hipStream_t st);
+hipError_t launch_maxpool(const PoolParams &p, hipStream_t st);
+hipError_t launch_gap(const GapParams &p, hipStream_t st);
+hipError_t launch_fc(const FcParams &p, hipStream_t st);
+hipError_t launch_fill_u32(uint32_t *p, uint32_t value, size_t n, hipStream_t st);
+// Tile geometry of the convolution kernel chosen for (Cout_p): rows per M tile.
+int conv_tile_m(int cout_p);
+
+}  // namespace isr
+
+#endif

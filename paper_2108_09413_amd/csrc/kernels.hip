@@ -1,0 +1,305 @@
+// Memory-bound stages of the Monte-Carlo loop: noise injection, residual add,
+// pooling, the FC + argmax + vote tally.
+#include "isr_internal.h"
+
+namespace isr {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------
+// Noise: x + delta, delta ~ discrete Gaussian (Def. 3.3), saturated to [0,255],
+// recentred to int8, written as NHWC4 (4th channel 0).
+//
+// Randomness: Philox4x32-10 keyed by the seed; counter (p >> 2, sample, image,
+// 2*phase + half) with p the logical [C][H][W] pixel index; word p & 3; half 0
+// supplies the high 32 bits of the uniform 64-bit u, half 1 the low 32 bits.
+// The low half is generated only when the high word ties with a threshold.
+
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t out[4]) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        uint32_t h0 = __umulhi(0xD2511F53u, c0), l0 = 0xD2511F53u * c0;
+        uint32_t h1 = __umulhi(0xCD9E8D57u, c2), l1 = 0xCD9E8D57u * c2;
+        c0 = h1 ^ c1 ^ k0;
+        c1 = l1;
+        c2 = h0 ^ c3 ^ k1;
+        c3 = l0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+struct NoiseLds {
+    uint32_t hi[NOISE_TABLE_MAX];
+    uint32_t lo[NOISE_TABLE_MAX];
+    uint16_t guide[NOISE_GUIDE_SIZE + 2];
+};
+
+// #{j < n : T[j] <= u} for u = (uhi, ulo); the low word is produced on demand.
+template <typename LowWord>
+__device__ __forceinline__ int threshold_count(const NoiseLds &t, int n, uint32_t uhi, LowWord low_word) {
+    int c = t.guide[uhi >> (32 - NOISE_GUIDE_BITS)];
+    while (c < n && t.hi[c] < uhi) ++c;
+    if (c < n && t.hi[c] == uhi) {
+        uint32_t ulo = low_word();
+        while (c < n && t.hi[c] == uhi && t.lo[c] <= ulo) ++c;
+    }
+    return c;
+}
+
+__global__ __launch_bounds__(256) void noise_kernel(const NoiseParams p) {
+    __shared__ NoiseLds t;
+    for (int i = threadIdx.x; i < (int)NOISE_TABLE_MAX; i += 256) {
+        t.hi[i] = p.table->hi[i];
+        t.lo[i] = p.table->lo[i];
+    }
+    for (int i = threadIdx.x; i < (int)NOISE_GUIDE_SIZE + 2; i += 256) t.guide[i] = p.table->guide[i];
+    const int n = (int)p.table->n;
+    const int dmin = p.table->dmin;
+    __syncthreads();
+
+    const int W4 = p.W >> 2;
+    const long groups_per_sample = (long)p.H * W4;
+    const long total = groups_per_sample * p.count;
+    for (long g = (long)blockIdx.x * 256 + threadIdx.x; g < total; g += (long)gridDim.x * 256) {
+        const uint32_t s_local = (uint32_t)(g / groups_per_sample);
+        const int rem = (int)(g - (long)s_local * groups_per_sample);
+        const int y = rem / W4, x4 = rem - y * W4;
+        const uint32_t sample = p.sample_begin + s_local;
+        int val[3][4];
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            if (c < p.C) {
+                const uint32_t pix = (uint32_t)((c * p.H + y) * p.W + x4 * 4);   // multiple of 4
+                const uint32_t grp = pix >> 2;
+                uint32_t hi[4];
+                philox4x32_10(grp, sample, p.image, p.phase * 2u, p.key0, p.key1, hi);
+                const uint32_t px4 = *(const uint32_t *)(p.x + pix);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    int cnt = threshold_count(t, n, hi[j], [&]() {
+                        uint32_t lo[4];
+                        philox4x32_10(grp, sample, p.image, p.phase * 2u + 1u, p.key0, p.key1, lo);
+                        return lo[j];
+                    });
+                    int v = (int)((px4 >> (8 * j)) & 0xFF) + dmin + cnt;
+                    v = v < 0 ? 0 : (v > 255 ? 255 : v);
+                    val[c][j] = v - 128;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) val[c][j] = 0;
+            }
+        }
+        v4i o;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            o[j] = (int)((uint32_t)(val[0][j] & 0xFF) | ((uint32_t)(val[1][j] & 0xFF) << 8) |
+                         ((uint32_t)(val[2][j] & 0xFF) << 16));
+        *(v4i *)(p.out + ((long)s_local * groups_per_sample + rem) * 16) = o;
+    }
+}
+
+hipError_t launch_noise(const NoiseParams &p, hipStream_t st) {
+    if (p.count == 0) return hipSuccess;
+    if (p.C < 1 || p.C > 3 || (p.W & 3) != 0) return hipErrorInvalidValue;
+    long total = (long)p.H * (p.W >> 2) * p.count;
+    long blocks = (total + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    hipLaunchKernelGGL(noise_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Residual add of two int8 tensors with requantisation:
+//   out = clamp(z_o + RHA((qa - za) Ma + (qb - zb) Mb, shift), relu ? z_o : -128, 127)
+
+__device__ __forceinline__ int rha64(long v, int s) {
+    if (s == 0) return (int)v;
+    long half = 1L << (s - 1);
+    return (int)(v >= 0 ? (v + half) >> s : -((-v + half) >> s));
+}
+
+__global__ __launch_bounds__(256) void add_kernel(const AddParams p) {
+    const int lo = p.relu ? p.zo : -128;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < p.n16; i += (long)gridDim.x * 256) {
+        v4i va = *(const v4i *)(p.a + i * 16), vb = *(const v4i *)(p.b + i * 16), vo;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            uint32_t packed = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                int qa = (int)(int8_t)((uint32_t)va[d] >> (8 * e));
+                int qb = (int)(int8_t)((uint32_t)vb[d] >> (8 * e));
+                long v = (long)(qa - p.za) * p.Ma + (long)(qb - p.zb) * p.Mb;
+                int r = p.zo + rha64(v, p.sh);
+                r = r < lo ? lo : (r > 127 ? 127 : r);
+                packed |= (uint32_t)(r & 0xFF) << (8 * e);
+            }
+            vo[d] = (int)packed;
+        }
+        *(v4i *)(p.out + i * 16) = vo;
+    }
+}
+
+hipError_t launch_add(const AddParams &p, hipStream_t st) {
+    if (p.n16 <= 0) return hipSuccess;
+    long blocks = (p.n16 + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(add_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Max pooling over in-bounds taps, NHWC, 16 channels per thread.
+
+__global__ __launch_bounds__(256) void maxpool_kernel(const PoolParams p) {
+    const int c16 = p.Cp >> 4;
+    const long total = (long)p.B * p.Ho * p.Wo * c16;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+        int cg = (int)(i % c16);
+        long pix = i / c16;
+        int ox = (int)(pix % p.Wo);
+        long t = pix / p.Wo;
+        int oy = (int)(t % p.Ho);
+        long b = t / p.Ho;
+        int best[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) best[e] = -128;
+        for (int ky = 0; ky < p.k; ++ky) {
+            int iy = oy * p.stride - p.pad + ky;
+            if ((unsigned)iy >= (unsigned)p.H) continue;
+            for (int kx = 0; kx < p.k; ++kx) {
+                int ix = ox * p.stride - p.pad + kx;
+                if ((unsigned)ix >= (unsigned)p.W) continue;
+                v4i v = *(const v4i *)(p.in + ((b * p.H + iy) * p.W + ix) * p.Cp + cg * 16);
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    int q = (int)(int8_t)((uint32_t)v[e >> 2] >> (8 * (e & 3)));
+                    best[e] = q > best[e] ? q : best[e];
+                }
+            }
+        }
+        v4i o;
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+            o[d] = (int)((uint32_t)(best[4 * d] & 0xFF) | ((uint32_t)(best[4 * d + 1] & 0xFF) << 8) |
+                         ((uint32_t)(best[4 * d + 2] & 0xFF) << 16) | ((uint32_t)best[4 * d + 3] << 24));
+        *(v4i *)(p.out + pix * p.Cp + cg * 16) = o;
+    }
+}
+
+hipError_t launch_maxpool(const PoolParams &p, hipStream_t st) {
+    long total = (long)p.B * p.Ho * p.Wo * (p.Cp >> 4);
+    if (total <= 0) return hipSuccess;
+    long blocks = (total + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(maxpool_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Global average pooling: S = sum over H*W of (q - z_in), requantised like a
+// convolution output with a scalar (M0, shift); 4 channels per thread.
+
+__global__ __launch_bounds__(256) void gap_kernel(const GapParams p) {
+    const int c4 = p.Cp >> 2;
+    const long total = (long)p.B * c4;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+        int cg = (int)(i % c4);
+        long b = i / c4;
+        const int8_t *src = p.in + b * p.HW * p.Cp + cg * 4;
+        int s[4] = {0, 0, 0, 0};
+        for (int t = 0; t < p.HW; ++t) {
+            uint32_t v = *(const uint32_t *)(src + (long)t * p.Cp);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s[e] += (int)(int8_t)(v >> (8 * e));
+        }
+        uint32_t packed = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            long v = (long)(s[e] - p.HW * p.zp_in) * p.M0;
+            int r = p.zp_out + rha64(v, 31 + p.sh);
+            r = r < -128 ? -128 : (r > 127 ? 127 : r);
+            packed |= (uint32_t)(r & 0xFF) << (8 * e);
+        }
+        *(uint32_t *)(p.out + b * p.Cp + cg * 4) = packed;
+    }
+}
+
+hipError_t launch_gap(const GapParams &p, hipStream_t st) {
+    long total = (long)p.B * (p.Cp >> 2);
+    if (total <= 0) return hipSuccess;
+    long blocks = (total + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(gap_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// FC logits (int32, no requantisation), wavefront argmax (lowest index among
+// maxima) and vote histogram: one wave per sample, LDS histogram per block,
+// one global atomic per class per block.
+
+constexpr int FC_MAX_CLASSES = 1024;
+
+__global__ __launch_bounds__(256) void fc_vote_kernel(const FcParams p) {
+    __shared__ uint32_t hist[FC_MAX_CLASSES];
+    for (int i = threadIdx.x; i < p.classes; i += 256) hist[i] = 0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (long s = (long)blockIdx.x * 4 + wave; s < p.B; s += (long)gridDim.x * 4) {
+        const int8_t *a = p.in + s * p.Kp;
+        int best = INT32_MIN, best_idx = 0x7FFFFFFF;
+        for (int c = lane; c < p.classes; c += 64) {
+            const int8_t *w = p.w + (long)c * p.Kp;
+            int acc = p.bias[c];
+            for (int k = 0; k < p.Kp; k += 16) {
+                v4i va = *(const v4i *)(a + k), vw = *(const v4i *)(w + k);
+#pragma unroll
+                for (int d = 0; d < 4; ++d) acc = __builtin_amdgcn_sdot4(va[d], vw[d], acc, false);
+            }
+            if (p.logits) p.logits[s * p.classes + c] = acc;
+            if (acc > best) { best = acc; best_idx = c; }   // ascending c keeps the lowest index
+        }
+        // wave reduction: larger logit wins, then the lower class index
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            int ob = __shfl_xor(best, off, 64), oi = __shfl_xor(best_idx, off, 64);
+            if (ob > best || (ob == best && oi < best_idx)) { best = ob; best_idx = oi; }
+        }
+        if (lane == 0) {
+            if (p.argmax) p.argmax[s] = best_idx;
+            if (p.counts) atomicAdd(&hist[best_idx], 1u);
+        }
+    }
+    __syncthreads();
+    if (p.counts)
+        for (int i = threadIdx.x; i < p.classes; i += 256)
+            if (hist[i]) atomicAdd(&p.counts[i], hist[i]);
+}
+
+hipError_t launch_fc(const FcParams &p, hipStream_t st) {
+    if (p.B <= 0) return hipSuccess;
+    if (p.classes < 1 || p.classes > FC_MAX_CLASSES || p.Kp % 16 != 0) return hipErrorInvalidValue;
+    long blocks = ((long)p.B + 3) / 4;
+    if (blocks > 256 * 8) blocks = 256 * 8;
+    hipLaunchKernelGGL(fc_vote_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p);
+    return hipGetLastError();
+}
+
+__global__ void fill_u32_kernel(uint32_t *p, uint32_t v, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = v;
+}
+
+hipError_t launch_fill_u32(uint32_t *p, uint32_t value, size_t n, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p, value, n);
+    return hipGetLastError();
+}
+
+}  // namespace isr

@@ -137,7 +137,7 @@ class NetBuilder:
                 sh += 1
             m0 = (1 << (31 + sh)) // hw
             if m0 == (1 << 31):
-                m0, sh = 1 << 30, sh - 1
+                m0, sh = ((1 << 30), sh - 1) if sh > 0 else ((1 << 31) - 1, 0)
             assert (1 << 30) <= m0 < (1 << 31)
         tout = self.tensor(ti.C, 1, 1, ti.zp, ti.rms)
         self.ops.append((OP_GAP, struct.pack("<4i", tin, tout, m0, sh)))

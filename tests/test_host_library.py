@@ -1,0 +1,133 @@
+"""CPU-side checks of the C-ABI library: it loads, exports what include/isr.h
+declares, and its host-only pieces (noise table, statistics, blob validation)
+agree with the oracle and the golden values.  No compute call needs a GPU."""
+import os
+import re
+import struct
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2108_09413_amd as isr
+import synth
+from oracle import stats as ostats
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ALPHA = 0.001
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "isr.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(isr_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(isr.EXPORTS)
+    L = isr.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+@pytest.mark.parametrize("sigma", [1, 2, 15, 32, 64, 128, 256, 1024])
+def test_noise_table_identical_to_oracle(sigma):
+    T, R = isr.isr_noise_table(sigma)
+    To, Ro = oracle.noise_table(sigma)
+    assert R == Ro and np.array_equal(T, To)
+
+
+def test_noise_table_argument_domain():
+    for bad in (0, 1025):
+        with pytest.raises(isr.IsrError) as e:
+            isr.isr_noise_table(bad)
+        assert e.value.status == isr.ISR_ERR_ARG
+
+
+def test_cp_and_radius_against_golden_values(golden_dir):
+    for l in open(os.path.join(golden_dir, "cp_radius_values.txt")):
+        if l.startswith("#") or not l.strip():
+            continue
+        n, k, p_txt, r_txt = l.split()
+        n, k = int(n), int(k)
+        p = isr.isr_cp_lower(k, n, ALPHA)
+        assert p == pytest.approx(float(p_txt), rel=2e-15, abs=1e-16)
+        c1 = [n - k, k, 0]
+        res = isr.isr_decide_certify([0, 5, 1], c1, 64.0, n, ALPHA)
+        assert res.n_top == k and res.p_lower == p
+        if r_txt == "abstain":
+            assert res.cls == isr.ABSTAIN and res.radius == 0.0
+        else:
+            tol = max(1e-12, 4e-16 / abs(float(p_txt) - 0.5))
+            assert res.cls == 1 and res.radius / 64.0 == pytest.approx(float(r_txt), rel=tol)
+
+
+def test_statistics_agree_with_oracle_on_random_counts():
+    rng = np.random.default_rng(3)
+    for _ in range(300):
+        n = int(rng.choice([100, 1000, 10000, 100000]))
+        k = int(rng.integers(0, n + 1))
+        alpha = float(rng.choice([0.001, 0.01, 0.05, 0.3]))
+        a, b = isr.isr_cp_lower(k, n, alpha), ostats.cp_lower(k, n, alpha)
+        assert a == pytest.approx(b, rel=1e-12, abs=1e-15)
+        C = int(rng.integers(2, 12))
+        c0 = rng.multinomial(100, rng.dirichlet(np.ones(C))).astype(np.uint32)
+        c1 = rng.multinomial(n, rng.dirichlet(np.ones(C) * 0.3)).astype(np.uint32)
+        sigma = float(rng.choice([32, 64, 128, 256]))
+        res = isr.isr_decide_certify(c0, c1, sigma, n, alpha)
+        cls, rad, pl, ntop = ostats.certify_decision(c0, c1, sigma, n, alpha)
+        assert res.cls == cls and res.n_top == ntop
+        assert res.p_lower == pytest.approx(pl, rel=1e-12, abs=1e-15)
+        if cls != ostats.ABSTAIN:
+            assert res.radius == pytest.approx(rad, rel=max(1e-9, 1e-15 / abs(pl - 0.5)))
+        cp = rng.multinomial(int(rng.choice([10, 100, 1000, 100000])), rng.dirichlet(np.ones(C) * 0.5)).astype(np.uint32)
+        rp = isr.isr_decide_predict(cp, alpha)
+        pc, pv, na, nb = ostats.predict_decision(cp, alpha)
+        assert (rp.cls, rp.n_top, rp.n_second) == (pc, na, nb)
+        assert rp.p_lower == pytest.approx(pv, rel=1e-10, abs=1e-300)
+
+
+def test_normal_quantile_and_pvalue_special_values():
+    import mpmath as mp
+    mp.mp.dps = 80
+    for p in (1e-30, 1e-12, 0.001, 0.3, 0.5, 0.5000000001, 0.9, 0.99993092483300939, 1 - 1e-15):
+        want = float(mp.sqrt(2) * mp.erfinv(2 * mp.mpf(p) - 1))
+        assert isr.isr_normal_quantile(p) == pytest.approx(want, rel=1e-13, abs=1e-16)
+    for bad in (0.0, 1.0, -0.1, float("nan")):
+        with pytest.raises(isr.IsrError):
+            isr.isr_normal_quantile(bad)
+    assert isr.isr_binom_pvalue(0, 0) == 1.0
+    assert isr.isr_binom_pvalue(5, 5) == 1.0
+    assert isr.isr_binom_pvalue(11, 0) == pytest.approx(2.0 ** -10, rel=1e-14)
+    assert isr.isr_binom_pvalue(60, 40) == pytest.approx(0.056887933640980784, rel=1e-12)
+    with pytest.raises(isr.IsrError):
+        isr.isr_cp_lower(5, 4, ALPHA)
+    with pytest.raises(isr.IsrError):
+        isr.isr_cp_lower(1, 4, 1.5)
+
+
+def test_validate_model_accepts_workloads_and_rejects_damage():
+    for cfg, size in ((0, None), (1, None), (3, 32)):
+        assert isr.isr_validate_model(synth.build_model(cfg, size=size)) == isr.ISR_OK
+    blob = bytearray(synth.build_model(0))
+    assert isr.isr_validate_model(bytes(blob[:-4])) == isr.ISR_ERR_FORMAT          # truncated
+    assert isr.isr_validate_model(bytes(blob) + b"\0\0\0\0") == isr.ISR_ERR_FORMAT  # trailing bytes
+    bad = bytearray(blob); bad[0] ^= 1
+    assert isr.isr_validate_model(bytes(bad)) == isr.ISR_ERR_FORMAT                # magic
+    bad = bytearray(blob); struct.pack_into("<I", bad, 4, 2)
+    assert isr.isr_validate_model(bytes(bad)) == isr.ISR_ERR_FORMAT                # version
+    assert isr.isr_validate_model(b"") == isr.ISR_ERR_FORMAT
+    # a weight of -128 is outside the symmetric range
+    off = 32 + 5 * 16 + 8 + 24
+    bad = bytearray(blob); bad[off] = 0x80
+    assert isr.isr_validate_model(bytes(bad)) == isr.ISR_ERR_FORMAT
+    # multiplier below 2^30
+    from synth.models import NetBuilder
+    b = NetBuilder(rng=np.random.default_rng(0), in_shape=(3, 8, 8), num_classes=3)
+    t = b.tensor(3, 8, 8, 0, 50.0)
+    u = b.conv(t, 4, 3, 1, 1, True, m0=(1 << 30) - 1)
+    b.fc(b.gap(u), 3)
+    assert isr.isr_validate_model(b.blob()) == isr.ISR_ERR_FORMAT
+    # unsupported but well-formed: input width not a multiple of 4
+    b = NetBuilder(rng=np.random.default_rng(0), in_shape=(3, 6, 6), num_classes=3)
+    t = b.tensor(3, 6, 6, 0, 50.0)
+    u = b.conv(t, 4, 3, 1, 1, True)
+    b.fc(b.gap(u), 3)
+    assert isr.isr_validate_model(b.blob()) == isr.ISR_ERR_UNSUPPORTED
