@@ -142,6 +142,25 @@ int isr_decide_certify(const uint32_t *counts0, const uint32_t *counts1, uint32_
                        double sigma, uint32_t n, double alpha, isr_result *out);
 int isr_decide_predict(const uint32_t *counts, uint32_t classes, double alpha, isr_result *out);
 
+/* ---- per-kernel timing (HIP events on the model's stream) ------------------ */
+
+typedef struct isr_kernel_stat {
+    char name[32];        /* "noise", "conv_m16/32/64/128", "add", "maxpool", "gap", "fc_vote" */
+    uint64_t launches;    /* launches timed so far */
+    double total_ms;      /* sum of their durations */
+    double alg_ops;       /* algorithmic integer ops of those launches (2 per multiply-accumulate,
+                             real channel counts, no padding); 0 for the memory-bound kernels */
+    double alg_bytes;     /* algorithmic bytes read + written by those launches */
+} isr_kernel_stat;
+
+/* every_chunks > 0: bracket every kernel launch of each every_chunks-th chunk
+ * with HIP events and accumulate per kernel class (the chunk is followed by a
+ * stream synchronisation); 0 switches timing off.  Either call resets the
+ * accumulators. */
+int isr_profile(isr_model *m, uint32_t every_chunks);
+/* Copies up to cap accumulated entries to out_host and their number to n_out. */
+int isr_profile_read(const isr_model *m, isr_kernel_stat *out_host, uint32_t cap, uint32_t *n_out);
+
 const char *isr_strerror(int status);
 int isr_last_device_error(void); /* hipError_t of the last failing HIP call on this thread */
 

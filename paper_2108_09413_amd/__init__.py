@@ -22,7 +22,8 @@ EXPORTS = [
     "isr_load_model", "isr_free_model", "isr_validate_model", "isr_model_info", "isr_workspace_bytes",
     "isr_set_workspace", "isr_certify", "isr_predict", "isr_debug_noisy", "isr_debug_forward",
     "isr_debug_tensor", "isr_noise_table", "isr_cp_lower", "isr_normal_quantile", "isr_binom_pvalue",
-    "isr_decide_certify", "isr_decide_predict", "isr_strerror", "isr_last_device_error",
+    "isr_decide_certify", "isr_decide_predict", "isr_profile", "isr_profile_read", "isr_strerror",
+    "isr_last_device_error",
 ]
 
 
@@ -42,6 +43,11 @@ class Result(C.Structure):
     def __repr__(self):
         return (f"Result(cls={self.cls}, radius={self.radius!r}, p_lower={self.p_lower!r}, "
                 f"n_top={self.n_top}, n_second={self.n_second})")
+
+
+class KernelStat(C.Structure):
+    _fields_ = [("name", C.c_char * 32), ("launches", C.c_uint64), ("total_ms", C.c_double),
+                ("alg_ops", C.c_double), ("alg_bytes", C.c_double)]
 
 
 _lib = None
@@ -74,6 +80,8 @@ def lib():
         L.isr_binom_pvalue.argtypes = [u32, u32, C.POINTER(dbl)]
         L.isr_decide_certify.argtypes = [vp, vp, u32, dbl, u32, dbl, C.POINTER(Result)]
         L.isr_decide_predict.argtypes = [vp, u32, dbl, C.POINTER(Result)]
+        L.isr_profile.argtypes = [vp, u32]
+        L.isr_profile_read.argtypes = [vp, C.POINTER(KernelStat), u32, C.POINTER(u32)]
         L.isr_strerror.argtypes = [C.c_int]
         L.isr_strerror.restype = C.c_char_p
         L.isr_last_device_error.argtypes = []
@@ -253,3 +261,16 @@ def isr_debug_tensor(model: Model, x, sigma: int, seed: int, image_id: int, phas
     _check(lib().isr_debug_tensor(model.handle, C.c_void_p(x.data_ptr()), sigma, C.c_uint64(seed), image_id, phase,
                                   sample, tensor_id, _np_ptr(out)), "isr_debug_tensor")
     return out
+
+
+def isr_profile(model: Model, every_chunks: int):
+    _check(lib().isr_profile(model.handle, every_chunks), "isr_profile")
+
+
+def isr_profile_read(model: Model):
+    """List of dicts: name, launches, total_ms, alg_ops, alg_bytes per kernel class."""
+    arr = (KernelStat * 16)()
+    n = C.c_uint32(0)
+    _check(lib().isr_profile_read(model.handle, arr, 16, C.byref(n)), "isr_profile_read")
+    return [dict(name=arr[i].name.decode(), launches=int(arr[i].launches), total_ms=arr[i].total_ms,
+                 alg_ops=arr[i].alg_ops, alg_bytes=arr[i].alg_bytes) for i in range(min(n.value, 16))]

@@ -24,9 +24,15 @@ thread_local int g_last_hip_error = 0;
 
 constexpr int TABLE_SLOTS = 8;
 
+enum KernelClass { KC_NOISE, KC_CONV16, KC_CONV32, KC_CONV64, KC_CONV128, KC_ADD, KC_POOL, KC_GAP, KC_FC, KC_COUNT };
+const char *const KC_NAMES[KC_COUNT] = {"noise", "conv_m16", "conv_m32", "conv_m64", "conv_m128",
+                                        "add", "maxpool", "gap", "fc_vote"};
+
 struct DevOp {
     OpType type;
     int a = -1, b = -1, out = -1;
+    int kclass = 0;
+    double ops_per_sample = 0.0, bytes_per_sample = 0.0;   // algorithmic, for the timing report
     ConvParams conv{};
     AddParams add{};
     PoolParams pool{};
@@ -63,6 +69,11 @@ struct isr_model {
     hipStream_t stream = nullptr;
     std::vector<size_t> toff;           // per tensor offset inside the workspace
     size_t logits_off = 0, argmax_off = 0, plan_bytes = 0;
+    // per-kernel timing
+    uint32_t profile_every = 0;
+    uint64_t chunk_counter = 0;
+    std::vector<hipEvent_t> events;
+    isr_kernel_stat stats[KC_COUNT] = {};
 };
 
 namespace {
@@ -191,21 +202,31 @@ int build_device_ops(isr_model *m, ConstArena &arena) {
             c.H = ti.H; c.W = ti.W; c.Cin_p = cin_p; c.Ho = to.H; c.Wo = to.W; c.Cout_p = cout_p;
             c.stride = o.stride; c.pad = o.pad; c.Kp = Kp; c.Mp = Mp;
             c.zp_in = ti.zp; c.zp_out = to.zp; c.relu = o.relu; c.c4 = c4 ? 1 : 0;
+            int tm = conv_tile_m(cout_p);
+            d.kclass = tm == 16 ? KC_CONV16 : tm == 32 ? KC_CONV32 : tm == 64 ? KC_CONV64 : KC_CONV128;
+            d.ops_per_sample = 2.0 * to.C * to.H * to.W * ti.C * k * k;
+            d.bytes_per_sample = (double)ti.C * ti.H * ti.W + (double)to.C * to.H * to.W;
             break; }
         case OP_ADD: {
             AddParams &a = d.add;
             a.za = pm.tensors[o.a].zp; a.zb = pm.tensors[o.b].zp; a.zo = pm.tensors[o.out].zp;
             a.Ma = o.Ma; a.Mb = o.Mb; a.sh = o.sh; a.relu = o.relu;
+            d.kclass = KC_ADD;
+            d.bytes_per_sample = 3.0 * pm.tensors[o.out].C * pm.tensors[o.out].H * pm.tensors[o.out].W;
             break; }
         case OP_MAXPOOL: {
             const TensorDesc &ti = pm.tensors[o.a], &to = pm.tensors[o.out];
             PoolParams &p = d.pool;
             p.H = ti.H; p.W = ti.W; p.Cp = ti.Cp; p.Ho = to.H; p.Wo = to.W; p.k = o.k; p.stride = o.stride; p.pad = o.pad;
+            d.kclass = KC_POOL;
+            d.bytes_per_sample = (double)ti.C * ti.H * ti.W + (double)to.C * to.H * to.W;
             break; }
         case OP_GAP: {
             const TensorDesc &ti = pm.tensors[o.a], &to = pm.tensors[o.out];
             GapParams &g = d.gap;
             g.HW = ti.H * ti.W; g.Cp = ti.Cp; g.zp_in = ti.zp; g.zp_out = to.zp; g.M0 = o.Ma; g.sh = o.sh;
+            d.kclass = KC_GAP;
+            d.bytes_per_sample = (double)ti.C * ti.H * ti.W + (double)to.C;
             break; }
         case OP_FC: {
             const TensorDesc &ti = pm.tensors[o.a];
@@ -228,6 +249,9 @@ int build_device_ops(isr_model *m, ConstArena &arena) {
             f.w = (const int8_t *)arena.put(w.data(), w.size());
             f.bias = (const int32_t *)arena.put(bias.data(), bias.size() * 4);
             f.Kp = Kp; f.classes = classes;
+            d.kclass = KC_FC;
+            d.ops_per_sample = 2.0 * classes * ti.C * hw;
+            d.bytes_per_sample = (double)ti.C * hw;
             break; }
         }
         m->ops.push_back(d);
@@ -266,14 +290,34 @@ int run_range(isr_model *m, const uint8_t *x, const DeviceNoiseTable *table, uin
     uint8_t *ws = m->ws;
     for (uint32_t done = 0; done < count;) {
         const uint32_t cnt = std::min(m->chunk, count - done);
+        const bool timed = m->profile_every && (m->chunk_counter++ % m->profile_every) == 0;
+        size_t ev = 0;
+        std::vector<int> ev_class;
+        auto mark = [&](int kclass) -> int {   // event before a launch (kclass >= 0) / after the last one
+            if (!timed) return ISR_OK;
+            if (ev == m->events.size()) {
+                hipEvent_t e;
+                HIP_TRY(hipEventCreate(&e));
+                m->events.push_back(e);
+            }
+            HIP_TRY(hipEventRecord(m->events[ev++], m->stream));
+            if (kclass >= 0) ev_class.push_back(kclass);
+            return ISR_OK;
+        };
+        std::vector<std::pair<double, double>> ev_work;   // (ops, bytes) per timed launch
+        int prc;
         NoiseParams np;
         np.x = x; np.table = table; np.out = (int8_t *)(ws + m->toff[0]);
         np.C = pm.C; np.H = pm.H; np.W = pm.W;
         np.key0 = (uint32_t)seed; np.key1 = (uint32_t)(seed >> 32);
         np.image = image; np.phase = phase; np.sample_begin = begin + done; np.count = cnt;
+        if ((prc = mark(KC_NOISE)) != ISR_OK) return prc;
+        ev_work.push_back({0.0, (double)cnt * pm.H * pm.W * 4});
         HIP_TRY(launch_noise(np, m->stream));
         if (stop_tensor != 0) {
             for (const DevOp &d : m->ops) {
+                if ((prc = mark(d.kclass)) != ISR_OK) return prc;
+                ev_work.push_back({d.ops_per_sample * cnt, d.bytes_per_sample * cnt});
                 switch (d.type) {
                 case OP_CONV: {
                     ConvParams c = d.conv;
@@ -316,6 +360,19 @@ int run_range(isr_model *m, const uint8_t *x, const DeviceNoiseTable *table, uin
                     break; }
                 }
                 if (stop_tensor > 0 && d.out == stop_tensor) break;
+            }
+        }
+        if (timed) {
+            if ((prc = mark(-1)) != ISR_OK) return prc;
+            HIP_TRY(hipStreamSynchronize(m->stream));
+            for (size_t i = 0; i + 1 < ev; ++i) {
+                float ms = 0.f;
+                HIP_TRY(hipEventElapsedTime(&ms, m->events[i], m->events[i + 1]));
+                isr_kernel_stat &st = m->stats[ev_class[i]];
+                st.launches += 1;
+                st.total_ms += ms;
+                st.alg_ops += ev_work[i].first;
+                st.alg_bytes += ev_work[i].second;
             }
         }
         if (logits_host) {
@@ -377,8 +434,32 @@ int isr_load_model(const void *blob_host, size_t bytes, isr_model **out) {
     return ISR_OK;
 }
 
+int isr_profile(isr_model *m, uint32_t every_chunks) {
+    if (!m) return ISR_ERR_ARG;
+    m->profile_every = every_chunks;
+    m->chunk_counter = 0;
+    for (int i = 0; i < KC_COUNT; ++i) {
+        m->stats[i] = isr_kernel_stat{};
+        std::strncpy(m->stats[i].name, KC_NAMES[i], sizeof(m->stats[i].name) - 1);
+    }
+    return ISR_OK;
+}
+
+int isr_profile_read(const isr_model *m, isr_kernel_stat *out_host, uint32_t cap, uint32_t *n_out) {
+    if (!m || !n_out || (cap && !out_host)) return ISR_ERR_ARG;
+    uint32_t n = 0;
+    for (int i = 0; i < KC_COUNT; ++i)
+        if (m->stats[i].launches) {
+            if (n < cap) out_host[n] = m->stats[i];
+            ++n;
+        }
+    *n_out = n;
+    return ISR_OK;
+}
+
 int isr_free_model(isr_model *m) {
     if (!m) return ISR_OK;
+    for (hipEvent_t e : m->events) (void)hipEventDestroy(e);
     if (m->dconst) (void)hipFree(m->dconst);
     if (m->dtables) (void)hipFree(m->dtables);
     if (m->htables) (void)hipHostFree(m->htables);
