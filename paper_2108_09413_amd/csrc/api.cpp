@@ -162,6 +162,8 @@ int build_device_ops(isr_model *m, ConstArena &arena) {
             std::vector<int8_t> w((size_t)Mp * Kp, 0);
             std::vector<int32_t> bias(Mp, 0);
             std::vector<uint32_t> m0x2(Mp, 0x80000000u), rlo(Mp, 0), rhi(Mp, 1), sh(Mp, 1);
+            std::vector<int32_t> m0s(Mp, 1 << 30), chi(Mp, 1 + 2 * to.zp), shm1(Mp, 1);
+            bool fast = true;
             for (int oc = 0; oc < to.C; ++oc) {
                 int row = perm ? (oc & ~31) + mfma32_row_of_channel(oc & 31) : oc;
                 int64_t wsum = 0;
@@ -179,6 +181,13 @@ int build_device_ops(isr_model *m, ConstArena &arena) {
                 m0x2[oc] = (uint32_t)o.M0[oc] << 1;
                 uint64_t rnd = 1ull << (31 + o.shift[oc]);
                 rlo[oc] = (uint32_t)rnd; rhi[oc] = (uint32_t)(rnd >> 32); sh[oc] = (uint32_t)o.shift[oc];
+                if (o.shift[oc] >= 2 && o.shift[oc] <= 22) {
+                    m0s[oc] = o.M0[oc];
+                    chi[oc] = (1 << (o.shift[oc] - 2)) + to.zp * (1 << (o.shift[oc] - 1));
+                    shm1[oc] = o.shift[oc] - 1;
+                } else {
+                    fast = false;
+                }
             }
             const bool flat = !c4 && k == 1 && o.stride == 1 && o.pad == 0 && cin_p % 64 == 0;
             std::vector<uint32_t> ktab(Kp / 16, 0xFFFFFFFFu);
@@ -198,6 +207,10 @@ int build_device_ops(isr_model *m, ConstArena &arena) {
             c.rnd_lo = (const uint32_t *)arena.put(rlo.data(), rlo.size() * 4);
             c.rnd_hi = (const uint32_t *)arena.put(rhi.data(), rhi.size() * 4);
             c.shift = (const uint32_t *)arena.put(sh.data(), sh.size() * 4);
+            c.m0s = (const int32_t *)arena.put(m0s.data(), m0s.size() * 4);
+            c.chi = (const int32_t *)arena.put(chi.data(), chi.size() * 4);
+            c.shm1 = (const int32_t *)arena.put(shm1.data(), shm1.size() * 4);
+            c.fast_requant = fast ? 1 : 0;
             c.ktab = flat ? (const uint32_t *)~(uintptr_t)0 : (const uint32_t *)arena.put(ktab.data(), ktab.size() * 4);
             c.H = ti.H; c.W = ti.W; c.Cin_p = cin_p; c.Ho = to.H; c.Wo = to.W; c.Cout_p = cout_p;
             c.stride = o.stride; c.pad = o.pad; c.Kp = Kp; c.Mp = Mp;
@@ -426,6 +439,7 @@ int isr_load_model(const void *blob_host, size_t bytes, isr_model **out) {
             rebase(d.conv.w, m->dconst); rebase(d.conv.bias, m->dconst); rebase(d.conv.m0x2, m->dconst);
             rebase(d.conv.rnd_lo, m->dconst); rebase(d.conv.rnd_hi, m->dconst); rebase(d.conv.shift, m->dconst);
             rebase(d.conv.ktab, m->dconst);
+            rebase(d.conv.m0s, m->dconst); rebase(d.conv.chi, m->dconst); rebase(d.conv.shm1, m->dconst);
         } else if (d.type == OP_FC) {
             rebase(d.fc.w, m->dconst); rebase(d.fc.bias, m->dconst);
         }

@@ -34,12 +34,30 @@ __device__ __forceinline__ int requant(int acc, uint32_t m0x2, uint32_t rnd_lo, 
     return acc < 0 ? -r : r;
 }
 
+// Same result from one signed 32x32+64 multiply-add when 2 <= shift <= 22:
+//   z_out + RHA(v, s) = floor((v + 2^(s-1) - [v<0] + z_out 2^s) / 2^s),  v = acc M0, s = 31 + shift.
+// 2^(s-1) + z_out 2^s is a multiple of 2^32 (chi holds its high word), and
+// subtracting [v<0] turns the 64-bit addend into (chi + m : m) with m = acc >> 31.
+__device__ __forceinline__ int requant_fast(int acc, int m0, int chi, int shm1) {
+    int m = acc >> 31;
+    long addend = (long)(((unsigned long)(uint32_t)(chi + m) << 32) | (uint32_t)m);
+    long w = (long)acc * (long)m0 + addend;
+    return (int)(w >> 32) >> shm1;
+}
+
+// clamp(v, lo, hi) for lo <= hi in one instruction
+__device__ __forceinline__ int clamp3(int v, int lo, int hi) {
+    int r;
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "v"(lo), "v"(hi));
+    return r;
+}
+
 __device__ __forceinline__ uint32_t pack4(int a, int b, int c, int d) {
     return (uint32_t)(a & 0xFF) | ((uint32_t)(b & 0xFF) << 8) | ((uint32_t)(c & 0xFF) << 16) | ((uint32_t)d << 24);
 }
 
-template <int MT, int BM, int BN, int WGM>
-__global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
+template <int MT, int BM, int BN, int WGM, bool FAST, int MINW>
+__global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams p) {
     constexpr int WGN = 4 / WGM;
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int FM = WM / MT, FN = WN / MT;
@@ -53,8 +71,14 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WGM, wn = wave / WGM;
-    const int m0 = blockIdx.y * BM;
-    const long n0 = (long)blockIdx.x * BN;
+    // Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a contiguous
+    // range of logical tiles, M tile fastest, so that the workgroups sharing an
+    // activation tile run on the same XCD (same L2) close together in time.
+    const int nblk = gridDim.x, mt = (p.Cout_p + BM - 1) / BM;
+    const int xcd = blockIdx.x & 7, per = nblk >> 3, extra = nblk & 7;
+    const int logical = xcd * per + (xcd < extra ? xcd : extra) + (blockIdx.x >> 3);
+    const int m0 = (logical % mt) * BM;
+    const long n0 = (long)(logical / mt) * BN;
     const int nk = p.Kp >> 6;
     const int col = tid & 3, row0 = tid >> 2;
     const bool flat = p.ktab == nullptr;   // 1x1, stride 1, no padding: pixel n reads input pixel n
@@ -72,7 +96,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
         long n = n0 + row0 + 64 * j;
         rvalid[j] = n < p.npix;
         if (flat) {
-            base[j] = n * p.Cin_p;
+            base[j] = (rvalid[j] ? n : (long)p.npix - 1) * p.Cin_p;
             iy0[j] = ix0[j] = 0;
         } else {
             long nn = rvalid[j] ? n : 0;
@@ -97,9 +121,9 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
         for (int j = 0; j < NA; ++j)
             if (BM * 4 >= 256 || row0 + 64 * j < BM) ra[j] = *(const v4i *)(wrow[j] + (long)ks * 64);
         if (flat) {
+            // rows past the end re-read the last pixel; their results are never stored
 #pragma unroll
-            for (int j = 0; j < NB; ++j)
-                rb[j] = rvalid[j] ? *(const v4i *)(p.in + base[j] + ks * 64 + col * 16) : zfill;
+            for (int j = 0; j < NB; ++j) rb[j] = *(const v4i *)(p.in + base[j] + ks * 64 + col * 16);
         } else if (!p.c4) {
             uint32_t e = ktab_s[ks * 4 + col];
             int ky = e & 0xFF, kx = (e >> 8) & 0xFF, ic = e >> 16;
@@ -107,7 +131,9 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
             for (int j = 0; j < NB; ++j) {
                 int iy = iy0[j] + ky, ix = ix0[j] + kx;
                 bool ok = rvalid[j] && e != 0xFFFFFFFFu && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
-                rb[j] = ok ? *(const v4i *)(p.in + base[j] + ((long)iy * p.W + ix) * p.Cin_p + ic) : zfill;
+                long off = ok ? base[j] + ((long)iy * p.W + ix) * p.Cin_p + ic : 0;   // offset 0 is always readable
+                v4i v = *(const v4i *)(p.in + off);
+                rb[j] = ok ? v : zfill;
             }
         } else {
             uint32_t e = ktab_s[ks * 4 + col];
@@ -218,28 +244,52 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
     for (int fm = 0; fm < FM; ++fm) {
         const int oc = m0 + wm * WM + fm * MT + (MT == 32 ? 16 * (lane >> 5) : 4 * (lane >> 4));
         if (oc >= p.Cout_p) continue;
-        uint32_t mm[ACC], rl[ACC], rh[ACC], ss[ACC];
+        if constexpr (FAST) {
+            int mm[ACC], ch[ACC], ss[ACC];
 #pragma unroll
-        for (int i = 0; i < ACC; ++i) {
-            mm[i] = p.m0x2[oc + i]; rl[i] = p.rnd_lo[oc + i]; rh[i] = p.rnd_hi[oc + i]; ss[i] = p.shift[oc + i];
-        }
+            for (int i = 0; i < ACC; ++i) { mm[i] = p.m0s[oc + i]; ch[i] = p.chi[oc + i]; ss[i] = p.shm1[oc + i]; }
 #pragma unroll
-        for (int fn = 0; fn < FN; ++fn) {
-            long n = n0 + wn * WN + fn * MT + (lane & (MT - 1));
-            if (n >= p.npix) continue;
-            int q[ACC];
+            for (int fn = 0; fn < FN; ++fn) {
+                long n = n0 + wn * WN + fn * MT + (lane & (MT - 1));
+                if (n >= p.npix) continue;
+                int q[ACC];
+#pragma unroll
+                for (int i = 0; i < ACC; ++i) {
+                    q[i] = clamp3(requant_fast(acc[fm][fn][i], mm[i], ch[i], ss[i]), lo, 127);
+                }
+                int8_t *dst = p.out + n * p.Cout_p + oc;
+                if constexpr (MT == 32) {
+                    v4i v = {(int)pack4(q[0], q[1], q[2], q[3]), (int)pack4(q[4], q[5], q[6], q[7]),
+                             (int)pack4(q[8], q[9], q[10], q[11]), (int)pack4(q[12], q[13], q[14], q[15])};
+                    *(v4i *)dst = v;
+                } else {
+                    *(uint32_t *)dst = pack4(q[0], q[1], q[2], q[3]);
+                }
+            }
+        } else {
+            uint32_t mm[ACC], rl[ACC], rh[ACC], ss[ACC];
 #pragma unroll
             for (int i = 0; i < ACC; ++i) {
-                int r = p.zp_out + requant(acc[fm][fn][i], mm[i], rl[i], rh[i], ss[i]);
-                q[i] = r < lo ? lo : (r > 127 ? 127 : r);
+                mm[i] = p.m0x2[oc + i]; rl[i] = p.rnd_lo[oc + i]; rh[i] = p.rnd_hi[oc + i]; ss[i] = p.shift[oc + i];
             }
-            int8_t *dst = p.out + n * p.Cout_p + oc;
-            if constexpr (MT == 32) {
-                v4i v = {(int)pack4(q[0], q[1], q[2], q[3]), (int)pack4(q[4], q[5], q[6], q[7]),
-                         (int)pack4(q[8], q[9], q[10], q[11]), (int)pack4(q[12], q[13], q[14], q[15])};
-                *(v4i *)dst = v;
-            } else {
-                *(uint32_t *)dst = pack4(q[0], q[1], q[2], q[3]);
+#pragma unroll
+            for (int fn = 0; fn < FN; ++fn) {
+                long n = n0 + wn * WN + fn * MT + (lane & (MT - 1));
+                if (n >= p.npix) continue;
+                int q[ACC];
+#pragma unroll
+                for (int i = 0; i < ACC; ++i) {
+                    int r = p.zp_out + requant(acc[fm][fn][i], mm[i], rl[i], rh[i], ss[i]);
+                    q[i] = r < lo ? lo : (r > 127 ? 127 : r);
+                }
+                int8_t *dst = p.out + n * p.Cout_p + oc;
+                if constexpr (MT == 32) {
+                    v4i v = {(int)pack4(q[0], q[1], q[2], q[3]), (int)pack4(q[4], q[5], q[6], q[7]),
+                             (int)pack4(q[8], q[9], q[10], q[11]), (int)pack4(q[12], q[13], q[14], q[15])};
+                    *(v4i *)dst = v;
+                } else {
+                    *(uint32_t *)dst = pack4(q[0], q[1], q[2], q[3]);
+                }
             }
         }
     }
@@ -247,10 +297,13 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
 
 int conv_tile_m(int cout_p) { return cout_p <= 16 ? 16 : (cout_p <= 32 ? 32 : (cout_p <= 64 ? 64 : 128)); }
 
-template <int MT, int BM, int BN, int WGM>
+template <int MT, int BM, int BN, int WGM, int MINW>
 static hipError_t launch_one(const ConvParams &p, hipStream_t st) {
-    dim3 grid((unsigned)((p.npix + BN - 1) / BN), (unsigned)((p.Cout_p + BM - 1) / BM));
-    hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM>), grid, dim3(256), 0, st, p);
+    dim3 grid((unsigned)(((p.npix + BN - 1) / BN) * ((p.Cout_p + BM - 1) / BM)));
+    if (p.fast_requant)
+        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, true, MINW>), grid, dim3(256), 0, st, p);
+    else
+        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, false, 2>), grid, dim3(256), 0, st, p);
     return hipGetLastError();
 }
 
@@ -259,10 +312,10 @@ hipError_t launch_conv(const ConvParams &p, hipStream_t st) {
     if (p.Kp % 64 != 0 || p.Kp > 16384 || p.Cout_p % 16 != 0 || p.Mp % 128 != 0 || p.Mp < p.Cout_p)
         return hipErrorInvalidValue;
     switch (conv_tile_m(p.Cout_p)) {
-    case 16: return launch_one<16, 16, 256, 1>(p, st);
-    case 32: return launch_one<32, 32, 256, 1>(p, st);
-    case 64: return launch_one<32, 64, 256, 1>(p, st);
-    default: return launch_one<32, 128, 256, 2>(p, st);
+    case 16: return launch_one<16, 16, 256, 1, 4>(p, st);
+    case 32: return launch_one<32, 32, 256, 1, 4>(p, st);
+    case 64: return launch_one<32, 64, 256, 1, 3>(p, st);
+    default: return launch_one<32, 128, 128, 2, 4>(p, st);
     }
 }
 

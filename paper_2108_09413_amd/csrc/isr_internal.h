@@ -65,6 +65,10 @@ struct ConvParams {
     const uint32_t *rnd_lo;  // [Mp] low / high word of 2^(31 + shift)
     const uint32_t *rnd_hi;
     const uint32_t *shift;   // [Mp]
+    const int32_t *m0s;      // [Mp] M0                                  } single-multiply path,
+    const int32_t *chi;      // [Mp] 2^(shift-2) + z_out * 2^(shift-1)   } valid when every
+    const int32_t *shm1;     // [Mp] shift - 1                           } shift is in [2, 22]
+    int32_t fast_requant;
     const uint32_t *ktab;    // [Kp/16] packed (ky | kx<<8 | ic<<16), 0xFFFFFFFF = no tap
     int32_t H, W, Cin_p, Ho, Wo, Cout_p;
     int32_t stride, pad, Kp, Mp;
