@@ -142,6 +142,11 @@ int isr_decide_certify(const uint32_t *counts0, const uint32_t *counts1, uint32_
                        double sigma, uint32_t n, double alpha, isr_result *out);
 int isr_decide_predict(const uint32_t *counts, uint32_t classes, double alpha, isr_result *out);
 
+/* Kernel-variant switch for parity checks: enable != 0 (the default) folds each
+ * residual add into the epilogue of the convolution before it; 0 runs every op
+ * of the blob as its own kernel.  Results are identical either way. */
+int isr_set_fusion(isr_model *m, int enable);
+
 /* ---- per-kernel timing (HIP events on the model's stream) ------------------ */
 
 typedef struct isr_kernel_stat {

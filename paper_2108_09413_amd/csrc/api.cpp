@@ -52,9 +52,19 @@ int mfma32_row_of_channel(int oc_local) {
 
 }  // namespace
 
+// An executable op list plus where each tensor lives in the workspace.
+struct Plan {
+    std::vector<DevOp> ops;
+    std::vector<size_t> toff;           // per tensor offset inside the workspace
+    std::vector<char> has;              // tensor is produced by this plan
+    size_t logits_off = 0, argmax_off = 0, bytes = 0;
+};
+
 struct isr_model {
     ParsedModel pm;
-    std::vector<DevOp> ops;
+    std::vector<DevOp> ops;             // one descriptor per op of the blob
+    Plan plan[2];                       // [0] op by op, [1] residual adds fused into the preceding conv
+    int use_fused = 1;
     uint8_t *dconst = nullptr;          // weights and per-channel tables
     DeviceNoiseTable *dtables = nullptr;  // TABLE_SLOTS entries
     DeviceNoiseTable *htables = nullptr;  // pinned staging, TABLE_SLOTS entries
@@ -67,8 +77,6 @@ struct isr_model {
     size_t ws_bytes = 0;
     uint32_t chunk = 0;
     hipStream_t stream = nullptr;
-    std::vector<size_t> toff;           // per tensor offset inside the workspace
-    size_t logits_off = 0, argmax_off = 0, plan_bytes = 0;
     // per-kernel timing
     uint32_t profile_every = 0;
     uint64_t chunk_counter = 0;
@@ -80,12 +88,11 @@ namespace {
 
 // Offsets of every tensor for a chunk of B samples; buffers are reused once the
 // last op reading a tensor has been issued (stream order makes that safe).
-size_t plan_workspace(const ParsedModel &pm, uint32_t B, std::vector<size_t> &toff, size_t &logits_off,
-                      size_t &argmax_off) {
+void plan_workspace(const ParsedModel &pm, uint32_t B, Plan &pl) {
     const int nt = (int)pm.tensors.size();
     std::vector<int> last_use(nt, -1);
-    for (int i = 0; i < (int)pm.ops.size(); ++i) {
-        const HostOp &o = pm.ops[i];
+    for (int i = 0; i < (int)pl.ops.size(); ++i) {
+        const DevOp &o = pl.ops[i];
         if (o.a >= 0) last_use[o.a] = i;
         if (o.b >= 0) last_use[o.b] = i;
     }
@@ -120,17 +127,63 @@ size_t plan_workspace(const ParsedModel &pm, uint32_t B, std::vector<size_t> &to
                 ++i;
             }
     };
-    toff.assign(nt, 0);
-    toff[0] = alloc(tbytes(0));
-    for (int i = 0; i < (int)pm.ops.size(); ++i) {
-        const HostOp &o = pm.ops[i];
-        if (o.type != OP_FC) toff[o.out] = alloc(tbytes(o.out));
+    pl.toff.assign(nt, 0);
+    pl.has.assign(nt, 0);
+    pl.toff[0] = alloc(tbytes(0));
+    pl.has[0] = 1;
+    for (int i = 0; i < (int)pl.ops.size(); ++i) {
+        const DevOp &o = pl.ops[i];
+        if (o.type != OP_FC) { pl.toff[o.out] = alloc(tbytes(o.out)); pl.has[o.out] = 1; }
         for (int t : {o.a, o.b})
-            if (t >= 0 && last_use[t] == i && !(t == o.b && o.a == o.b)) release(toff[t], tbytes(t));
+            if (t >= 0 && last_use[t] == i && !(t == o.b && o.a == o.b)) release(pl.toff[t], tbytes(t));
     }
-    logits_off = round_up(top, 256);
-    argmax_off = logits_off + round_up((size_t)B * pm.classes * 4, 256);
-    return argmax_off + round_up((size_t)B * 4, 256);
+    pl.logits_off = round_up(top, 256);
+    pl.argmax_off = pl.logits_off + round_up((size_t)B * pm.classes * 4, 256);
+    pl.bytes = pl.argmax_off + round_up((size_t)B * 4, 256);
+}
+
+// Folds each residual ADD into the convolution issued right before it when that
+// convolution produces one of the add's inputs for the add alone and the sum
+// fits 32 bits: the convolution then reads the other input in its epilogue and
+// writes the add's output (the two roundings are kept).
+void fuse_adds(const ParsedModel &pm, const std::vector<DevOp> &plain, std::vector<DevOp> &fused) {
+    std::vector<int> uses(pm.tensors.size(), 0);
+    for (const DevOp &d : plain) {
+        if (d.a >= 0) uses[d.a]++;
+        if (d.b >= 0) uses[d.b]++;
+    }
+    fused.clear();
+    for (size_t i = 0; i < plain.size(); ++i) {
+        const DevOp &d = plain[i];
+        if (d.type == OP_ADD && !fused.empty() && fused.back().type == OP_CONV && !fused.back().conv.fuse_add &&
+            fused.back().conv.fast_requant && d.a != d.b &&
+            (fused.back().out == d.a || fused.back().out == d.b) && uses[fused.back().out] == 1) {
+            DevOp &c = fused.back();
+            const bool conv_is_a = c.out == d.a;
+            const int res = conv_is_a ? d.b : d.a;
+            const AddParams &a = d.add;
+            const int64_t m_self = conv_is_a ? a.Ma : a.Mb, m_res = conv_is_a ? a.Mb : a.Ma;
+            const int64_t z_self = conv_is_a ? a.za : a.zb, z_res = conv_is_a ? a.zb : a.za;
+            const int64_t c0 = -z_self * m_self - z_res * m_res;
+            const int64_t k = (a.sh >= 1 ? (1ll << (a.sh - 1)) : 0) + (int64_t)a.zo * (1ll << a.sh);
+            auto mag = [](int64_t v) { return v < 0 ? -v : v; };
+            const int64_t bound = 255 * (mag(m_self) + mag(m_res)) + mag(k) + 1;
+            if (a.sh >= 1 && a.sh <= 30 && mag(m_self) < (1 << 23) && mag(m_res) < (1 << 23) && bound < (1ll << 31)) {
+                c.conv.fuse_add = 1;
+                c.conv.add_mul_self = (int32_t)m_self;
+                c.conv.add_mul_res = (int32_t)m_res;
+                c.conv.add_c0 = (int32_t)c0;
+                c.conv.add_k = (int32_t)k;
+                c.conv.add_sh = a.sh;
+                c.conv.add_lo = a.relu ? a.zo : -128;
+                c.b = res;
+                c.out = d.out;
+                c.bytes_per_sample += d.bytes_per_sample / 3.0;   // the residual read
+                continue;
+            }
+        }
+        fused.push_back(d);
+    }
 }
 
 struct ConstArena {
@@ -296,9 +349,9 @@ int get_table(isr_model *m, uint32_t sigma, const DeviceNoiseTable **out) {
 // phase.  Optional outputs: per-sample logits / argmax (device buffers inside
 // the workspace, copied to the host pointers chunk by chunk) and the device
 // vote counters.  stop_tensor >= 0 ends each forward right after that tensor.
-int run_range(isr_model *m, const uint8_t *x, const DeviceNoiseTable *table, uint64_t seed, uint32_t image,
-              uint32_t phase, uint32_t begin, uint32_t count, int32_t *logits_host, int32_t *argmax_host,
-              uint32_t *dcounts, int stop_tensor) {
+int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseTable *table, uint64_t seed,
+              uint32_t image, uint32_t phase, uint32_t begin, uint32_t count, int32_t *logits_host,
+              int32_t *argmax_host, uint32_t *dcounts, int stop_tensor) {
     const ParsedModel &pm = m->pm;
     uint8_t *ws = m->ws;
     for (uint32_t done = 0; done < count;) {
@@ -320,7 +373,7 @@ int run_range(isr_model *m, const uint8_t *x, const DeviceNoiseTable *table, uin
         std::vector<std::pair<double, double>> ev_work;   // (ops, bytes) per timed launch
         int prc;
         NoiseParams np;
-        np.x = x; np.table = table; np.out = (int8_t *)(ws + m->toff[0]);
+        np.x = x; np.table = table; np.out = (int8_t *)(ws + pl.toff[0]);
         np.C = pm.C; np.H = pm.H; np.W = pm.W;
         np.key0 = (uint32_t)seed; np.key1 = (uint32_t)(seed >> 32);
         np.image = image; np.phase = phase; np.sample_begin = begin + done; np.count = cnt;
@@ -328,46 +381,47 @@ int run_range(isr_model *m, const uint8_t *x, const DeviceNoiseTable *table, uin
         ev_work.push_back({0.0, (double)cnt * pm.H * pm.W * 4});
         HIP_TRY(launch_noise(np, m->stream));
         if (stop_tensor != 0) {
-            for (const DevOp &d : m->ops) {
+            for (const DevOp &d : pl.ops) {
                 if ((prc = mark(d.kclass)) != ISR_OK) return prc;
                 ev_work.push_back({d.ops_per_sample * cnt, d.bytes_per_sample * cnt});
                 switch (d.type) {
                 case OP_CONV: {
                     ConvParams c = d.conv;
-                    c.in = (const int8_t *)(ws + m->toff[d.a]);
-                    c.out = (int8_t *)(ws + m->toff[d.out]);
+                    c.in = (const int8_t *)(ws + pl.toff[d.a]);
+                    c.out = (int8_t *)(ws + pl.toff[d.out]);
+                    c.res = c.fuse_add ? (const int8_t *)(ws + pl.toff[d.b]) : nullptr;
                     c.npix = (int32_t)(cnt * c.Ho * c.Wo);
                     HIP_TRY(launch_conv(c, m->stream));
                     break; }
                 case OP_ADD: {
                     AddParams a = d.add;
                     const TensorDesc &t = pm.tensors[d.out];
-                    a.a = (const int8_t *)(ws + m->toff[d.a]);
-                    a.b = (const int8_t *)(ws + m->toff[d.b]);
-                    a.out = (int8_t *)(ws + m->toff[d.out]);
+                    a.a = (const int8_t *)(ws + pl.toff[d.a]);
+                    a.b = (const int8_t *)(ws + pl.toff[d.b]);
+                    a.out = (int8_t *)(ws + pl.toff[d.out]);
                     a.n16 = (int64_t)cnt * t.H * t.W * t.Cp / 16;
                     HIP_TRY(launch_add(a, m->stream));
                     break; }
                 case OP_MAXPOOL: {
                     PoolParams p = d.pool;
-                    p.in = (const int8_t *)(ws + m->toff[d.a]);
-                    p.out = (int8_t *)(ws + m->toff[d.out]);
+                    p.in = (const int8_t *)(ws + pl.toff[d.a]);
+                    p.out = (int8_t *)(ws + pl.toff[d.out]);
                     p.B = (int32_t)cnt;
                     HIP_TRY(launch_maxpool(p, m->stream));
                     break; }
                 case OP_GAP: {
                     GapParams g = d.gap;
-                    g.in = (const int8_t *)(ws + m->toff[d.a]);
-                    g.out = (int8_t *)(ws + m->toff[d.out]);
+                    g.in = (const int8_t *)(ws + pl.toff[d.a]);
+                    g.out = (int8_t *)(ws + pl.toff[d.out]);
                     g.B = (int32_t)cnt;
                     HIP_TRY(launch_gap(g, m->stream));
                     break; }
                 case OP_FC: {
                     FcParams f = d.fc;
-                    f.in = (const int8_t *)(ws + m->toff[d.a]);
+                    f.in = (const int8_t *)(ws + pl.toff[d.a]);
                     f.B = (int32_t)cnt;
-                    f.logits = logits_host ? (int32_t *)(ws + m->logits_off) : nullptr;
-                    f.argmax = argmax_host ? (int32_t *)(ws + m->argmax_off) : nullptr;
+                    f.logits = logits_host ? (int32_t *)(ws + pl.logits_off) : nullptr;
+                    f.argmax = argmax_host ? (int32_t *)(ws + pl.argmax_off) : nullptr;
                     f.counts = dcounts;
                     HIP_TRY(launch_fc(f, m->stream));
                     break; }
@@ -389,11 +443,11 @@ int run_range(isr_model *m, const uint8_t *x, const DeviceNoiseTable *table, uin
             }
         }
         if (logits_host) {
-            HIP_TRY(hipMemcpyAsync(logits_host + (size_t)done * pm.classes, ws + m->logits_off,
+            HIP_TRY(hipMemcpyAsync(logits_host + (size_t)done * pm.classes, ws + pl.logits_off,
                                    (size_t)cnt * pm.classes * 4, hipMemcpyDeviceToHost, m->stream));
         }
         if (argmax_host) {
-            HIP_TRY(hipMemcpyAsync(argmax_host + done, ws + m->argmax_off, (size_t)cnt * 4,
+            HIP_TRY(hipMemcpyAsync(argmax_host + done, ws + pl.argmax_off, (size_t)cnt * 4,
                                    hipMemcpyDeviceToHost, m->stream));
         }
         if (logits_host || argmax_host) HIP_TRY(hipStreamSynchronize(m->stream));
@@ -444,7 +498,15 @@ int isr_load_model(const void *blob_host, size_t bytes, isr_model **out) {
             rebase(d.fc.w, m->dconst); rebase(d.fc.bias, m->dconst);
         }
     }
+    m->plan[0].ops = m->ops;
+    fuse_adds(m->pm, m->ops, m->plan[1].ops);
     *out = m;
+    return ISR_OK;
+}
+
+int isr_set_fusion(isr_model *m, int enable) {
+    if (!m) return ISR_ERR_ARG;
+    m->use_fused = enable ? 1 : 0;
     return ISR_OK;
 }
 
@@ -494,9 +556,14 @@ int isr_model_info(const isr_model *m, int *C, int *H, int *W, int *num_classes)
 
 size_t isr_workspace_bytes(const isr_model *m, uint32_t chunk_samples) {
     if (!m || chunk_samples == 0) return 0;
-    std::vector<size_t> toff;
-    size_t lo, ao;
-    return plan_workspace(m->pm, chunk_samples, toff, lo, ao);
+    size_t need = 0;
+    for (int i = 0; i < 2; ++i) {
+        Plan pl;
+        pl.ops = m->plan[i].ops;
+        plan_workspace(m->pm, chunk_samples, pl);
+        need = std::max(need, pl.bytes);
+    }
+    return need;
 }
 
 int isr_set_workspace(isr_model *m, void *workspace_device, size_t bytes, uint32_t chunk_samples, void *hip_stream) {
@@ -505,18 +572,12 @@ int isr_set_workspace(isr_model *m, void *workspace_device, size_t bytes, uint32
     // pixel counts of a chunk are kept in 32 bits inside the kernels
     for (const TensorDesc &t : m->pm.tensors)
         if ((uint64_t)chunk_samples * t.H * t.W * std::max(t.Cp, 16) >= (1ull << 31)) return ISR_ERR_ARG;
-    std::vector<size_t> toff;
-    size_t lo, ao;
-    size_t need = plan_workspace(m->pm, chunk_samples, toff, lo, ao);
-    if (bytes < need) return ISR_ERR_WORKSPACE;
+    if (bytes < isr_workspace_bytes(m, chunk_samples)) return ISR_ERR_WORKSPACE;
+    for (int i = 0; i < 2; ++i) plan_workspace(m->pm, chunk_samples, m->plan[i]);
     m->ws = (uint8_t *)workspace_device;
     m->ws_bytes = bytes;
     m->chunk = chunk_samples;
     m->stream = (hipStream_t)hip_stream;
-    m->toff = toff;
-    m->logits_off = lo;
-    m->argmax_off = ao;
-    m->plan_bytes = need;
     return ISR_OK;
 }
 
@@ -529,8 +590,8 @@ int isr_certify(isr_model *m, const uint8_t *x_device, uint32_t sigma, uint32_t 
     const DeviceNoiseTable *table = nullptr;
     if ((rc = get_table(m, sigma, &table)) != ISR_OK) return rc;
     HIP_TRY(launch_fill_u32(m->dcounts, 0, 2 * C, m->stream));
-    if ((rc = run_range(m, x_device, table, seed, image_id, 0, 0, n0, nullptr, nullptr, m->dcounts, -1)) != ISR_OK) return rc;
-    if ((rc = run_range(m, x_device, table, seed, image_id, 1, 0, n, nullptr, nullptr, m->dcounts + C, -1)) != ISR_OK) return rc;
+    if ((rc = run_range(m, m->plan[m->use_fused], x_device, table, seed, image_id, 0, 0, n0, nullptr, nullptr, m->dcounts, -1)) != ISR_OK) return rc;
+    if ((rc = run_range(m, m->plan[m->use_fused], x_device, table, seed, image_id, 1, 0, n, nullptr, nullptr, m->dcounts + C, -1)) != ISR_OK) return rc;
     HIP_TRY(hipMemcpyAsync(m->hcounts, m->dcounts, sizeof(uint32_t) * 2 * C, hipMemcpyDeviceToHost, m->stream));
     HIP_TRY(hipStreamSynchronize(m->stream));
     if (counts0_host) std::memcpy(counts0_host, m->hcounts, sizeof(uint32_t) * C);
@@ -547,7 +608,7 @@ int isr_predict(isr_model *m, const uint8_t *x_device, uint32_t sigma, uint32_t 
     const DeviceNoiseTable *table = nullptr;
     if ((rc = get_table(m, sigma, &table)) != ISR_OK) return rc;
     HIP_TRY(launch_fill_u32(m->dcounts, 0, C, m->stream));
-    if ((rc = run_range(m, x_device, table, seed, image_id, 0, 0, n, nullptr, nullptr, m->dcounts, -1)) != ISR_OK) return rc;
+    if ((rc = run_range(m, m->plan[m->use_fused], x_device, table, seed, image_id, 0, 0, n, nullptr, nullptr, m->dcounts, -1)) != ISR_OK) return rc;
     HIP_TRY(hipMemcpyAsync(m->hcounts, m->dcounts, sizeof(uint32_t) * C, hipMemcpyDeviceToHost, m->stream));
     HIP_TRY(hipStreamSynchronize(m->stream));
     if (counts_host) std::memcpy(counts_host, m->hcounts, sizeof(uint32_t) * C);
@@ -561,11 +622,11 @@ int isr_debug_noisy(isr_model *m, const uint8_t *x_device, uint32_t sigma, uint6
     if (!out_host || count == 0 || count > m->chunk || phase > 1) return ISR_ERR_ARG;
     const DeviceNoiseTable *table = nullptr;
     if ((rc = get_table(m, sigma, &table)) != ISR_OK) return rc;
-    if ((rc = run_range(m, x_device, table, seed, image_id, phase, sample_begin, count, nullptr, nullptr, nullptr, 0)) != ISR_OK) return rc;
+    if ((rc = run_range(m, m->plan[m->use_fused], x_device, table, seed, image_id, phase, sample_begin, count, nullptr, nullptr, nullptr, 0)) != ISR_OK) return rc;
     const ParsedModel &pm = m->pm;
     const size_t hw = (size_t)pm.H * pm.W;
     std::vector<int8_t> tmp(count * hw * 4);
-    HIP_TRY(hipMemcpyAsync(tmp.data(), m->ws + m->toff[0], tmp.size(), hipMemcpyDeviceToHost, m->stream));
+    HIP_TRY(hipMemcpyAsync(tmp.data(), m->ws + m->plan[m->use_fused].toff[0], tmp.size(), hipMemcpyDeviceToHost, m->stream));
     HIP_TRY(hipStreamSynchronize(m->stream));
     for (uint32_t s = 0; s < count; ++s)
         for (int c = 0; c < pm.C; ++c)
@@ -583,7 +644,7 @@ int isr_debug_forward(isr_model *m, const uint8_t *x_device, uint32_t sigma, uin
     const DeviceNoiseTable *table = nullptr;
     if ((rc = get_table(m, sigma, &table)) != ISR_OK) return rc;
     if (counts_host) HIP_TRY(launch_fill_u32(m->dcounts, 0, C, m->stream));
-    rc = run_range(m, x_device, table, seed, image_id, phase, sample_begin, count, logits_host, argmax_host,
+    rc = run_range(m, m->plan[m->use_fused], x_device, table, seed, image_id, phase, sample_begin, count, logits_host, argmax_host,
                    counts_host ? m->dcounts : nullptr, -1);
     if (rc != ISR_OK) return rc;
     if (counts_host) {
@@ -605,11 +666,13 @@ int isr_debug_tensor(isr_model *m, const uint8_t *x_device, uint32_t sigma, uint
         return ISR_ERR_ARG;
     const DeviceNoiseTable *table = nullptr;
     if ((rc = get_table(m, sigma, &table)) != ISR_OK) return rc;
-    if ((rc = run_range(m, x_device, table, seed, image_id, phase, sample, 1, nullptr, nullptr, nullptr, tensor_id)) != ISR_OK) return rc;
+    // tensors that the fused plan never materialises come from the op-by-op plan
+    const Plan &pl = (m->use_fused && m->plan[1].has[tensor_id]) ? m->plan[1] : m->plan[0];
+    if ((rc = run_range(m, pl, x_device, table, seed, image_id, phase, sample, 1, nullptr, nullptr, nullptr, tensor_id)) != ISR_OK) return rc;
     const TensorDesc &t = pm.tensors[tensor_id];
     const size_t hw = (size_t)t.H * t.W;
     std::vector<int8_t> tmp(hw * t.Cp);
-    HIP_TRY(hipMemcpyAsync(tmp.data(), m->ws + m->toff[tensor_id], tmp.size(), hipMemcpyDeviceToHost, m->stream));
+    HIP_TRY(hipMemcpyAsync(tmp.data(), m->ws + pl.toff[tensor_id], tmp.size(), hipMemcpyDeviceToHost, m->stream));
     HIP_TRY(hipStreamSynchronize(m->stream));
     for (int c = 0; c < t.C; ++c)
         for (size_t i = 0; i < hw; ++i) out_host[(size_t)c * hw + i] = tmp[i * t.Cp + c];

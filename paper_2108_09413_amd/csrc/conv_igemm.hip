@@ -56,7 +56,7 @@ __device__ __forceinline__ uint32_t pack4(int a, int b, int c, int d) {
     return (uint32_t)(a & 0xFF) | ((uint32_t)(b & 0xFF) << 8) | ((uint32_t)(c & 0xFF) << 16) | ((uint32_t)d << 24);
 }
 
-template <int MT, int BM, int BN, int WGM, bool FAST, int MINW>
+template <int MT, int BM, int BN, int WGM, bool FAST, int MINW, bool FUSE>
 __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams p) {
     constexpr int WGN = 4 / WGM;
     constexpr int WM = BM / WGM, WN = BN / WGN;
@@ -257,6 +257,23 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
                 for (int i = 0; i < ACC; ++i) {
                     q[i] = clamp3(requant_fast(acc[fm][fn][i], mm[i], ch[i], ss[i]), lo, 127);
                 }
+                if constexpr (FUSE) {
+                    // second requantisation: the residual add on the int8 result
+                    int rr[ACC / 4];
+                    if constexpr (MT == 32) {
+                        v4i rv = *(const v4i *)(p.res + n * p.Cout_p + oc);
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) rr[d] = rv[d];
+                    } else {
+                        rr[0] = *(const int *)(p.res + n * p.Cout_p + oc);
+                    }
+#pragma unroll
+                    for (int i = 0; i < ACC; ++i) {
+                        int r8 = (int)(int8_t)((uint32_t)rr[i >> 2] >> (8 * (i & 3)));
+                        int v = q[i] * p.add_mul_self + p.add_c0 + r8 * p.add_mul_res;
+                        q[i] = clamp3((v + p.add_k + (v >> 31)) >> p.add_sh, p.add_lo, 127);
+                    }
+                }
                 int8_t *dst = p.out + n * p.Cout_p + oc;
                 if constexpr (MT == 32) {
                     v4i v = {(int)pack4(q[0], q[1], q[2], q[3]), (int)pack4(q[4], q[5], q[6], q[7]),
@@ -300,10 +317,13 @@ int conv_tile_m(int cout_p) { return cout_p <= 16 ? 16 : (cout_p <= 32 ? 32 : (c
 template <int MT, int BM, int BN, int WGM, int MINW>
 static hipError_t launch_one(const ConvParams &p, hipStream_t st) {
     dim3 grid((unsigned)(((p.npix + BN - 1) / BN) * ((p.Cout_p + BM - 1) / BM)));
-    if (p.fast_requant)
-        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, true, MINW>), grid, dim3(256), 0, st, p);
+    if (p.fuse_add && !p.fast_requant) return hipErrorInvalidValue;
+    if (p.fuse_add)
+        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, true, MINW, true>), grid, dim3(256), 0, st, p);
+    else if (p.fast_requant)
+        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, true, MINW, false>), grid, dim3(256), 0, st, p);
     else
-        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, false, 2>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, false, 2, false>), grid, dim3(256), 0, st, p);
     return hipGetLastError();
 }
 

@@ -69,6 +69,11 @@ struct ConvParams {
     const int32_t *chi;      // [Mp] 2^(shift-2) + z_out * 2^(shift-1)   } valid when every
     const int32_t *shm1;     // [Mp] shift - 1                           } shift is in [2, 22]
     int32_t fast_requant;
+    // residual add folded into the epilogue (fuse_add != 0): with q the int8 result above,
+    //   v = q * add_mul_self + res * add_mul_res + add_c0            (= (q-z)Ms + (res-zr)Mr)
+    //   out = clamp((v + add_k + (v >> 31)) >> add_sh, add_lo, 127)  (add_k = 2^(sh-1) + z_o 2^sh)
+    const int8_t *res;       // [B][Ho][Wo][Cout_p] other input of the add
+    int32_t fuse_add, add_mul_self, add_mul_res, add_c0, add_k, add_sh, add_lo;
     const uint32_t *ktab;    // [Kp/16] packed (ky | kx<<8 | ic<<16), 0xFFFFFFFF = no tap
     int32_t H, W, Cin_p, Ho, Wo, Cout_p;
     int32_t stride, pad, Kp, Mp;

@@ -169,6 +169,26 @@ def test_votes_invariant_to_chunk_size_and_ragged_tail(isr):
         m.close()
 
 
+def test_fused_and_unfused_kernels_agree(isr):
+    """Residual adds folded into the convolution epilogue vs one kernel per op:
+    identical logits, and both equal the oracle."""
+    _say("fusion on/off")
+    for cfg, size, sigma in ((1, None, 64), (3, 64, 128)):
+        blob = synth.build_model(cfg, size=size)
+        shape = (3, size, size) if size else None
+        x = synth.make_image(cfg, 2, shape=shape)
+        m = _load(isr, blob, 16)
+        a = isr.isr_debug_forward(m, x, sigma, 8, 2, 1, 40, 24)
+        isr.isr_set_fusion(m, False)
+        b = isr.isr_debug_forward(m, x, sigma, 8, 2, 1, 40, 24)
+        isr.isr_set_fusion(m, True)
+        assert all(np.array_equal(u, v) for u, v in zip(a, b))
+        om = oracle.Model(blob)
+        olg, oam, ocnt = om.mc(x, sigma, 8, 2, 1, 40, 24)
+        assert np.array_equal(a[0], olg) and np.array_equal(a[1], oam) and np.array_equal(a[2], ocnt)
+        m.close()
+
+
 def test_resnet20_logits_and_votes(isr):
     _say("resnet20 logits parity")
     blob = synth.build_model(1)
