@@ -52,8 +52,11 @@ __device__ __forceinline__ int clamp3(int v, int lo, int hi) {
     return r;
 }
 
+// low bytes of four registers -> one dword (3 byte-permutes)
 __device__ __forceinline__ uint32_t pack4(int a, int b, int c, int d) {
-    return (uint32_t)(a & 0xFF) | ((uint32_t)(b & 0xFF) << 8) | ((uint32_t)(c & 0xFF) << 16) | ((uint32_t)d << 24);
+    uint32_t lo = __builtin_amdgcn_perm((uint32_t)b, (uint32_t)a, 0x0c0c0400u);
+    uint32_t hi = __builtin_amdgcn_perm((uint32_t)d, (uint32_t)c, 0x0c0c0400u);
+    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
 }
 
 template <int MT, int BM, int BN, int WGM, bool FAST, int MINW, bool FUSE>
@@ -270,7 +273,8 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
 #pragma unroll
                     for (int i = 0; i < ACC; ++i) {
                         int r8 = (int)(int8_t)((uint32_t)rr[i >> 2] >> (8 * (i & 3)));
-                        int v = q[i] * p.add_mul_self + p.add_c0 + r8 * p.add_mul_res;
+                        // 24-bit multiplies (full rate): |q|, |r8| < 2^8 and |multipliers| < 2^23
+                        int v = __mul24(q[i], p.add_mul_self) + p.add_c0 + __mul24(r8, p.add_mul_res);
                         q[i] = clamp3((v + p.add_k + (v >> 31)) >> p.add_sh, p.add_lo, 127);
                     }
                 }

@@ -15,7 +15,7 @@ namespace isr {
 
 // ---- noise table -----------------------------------------------------------
 constexpr uint32_t NOISE_TABLE_MAX = 512;   // >= 510 thresholds between -255 and 255
-constexpr uint32_t NOISE_GUIDE_BITS = 10;
+constexpr uint32_t NOISE_GUIDE_BITS = 12;
 constexpr uint32_t NOISE_GUIDE_SIZE = 1u << NOISE_GUIDE_BITS;
 
 struct DeviceNoiseTable {

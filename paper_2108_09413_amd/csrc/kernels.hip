@@ -19,12 +19,12 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
                                               uint32_t k0, uint32_t k1, uint32_t out[4]) {
 #pragma unroll
     for (int r = 0; r < 10; ++r) {
-        uint32_t h0 = __umulhi(0xD2511F53u, c0), l0 = 0xD2511F53u * c0;
-        uint32_t h1 = __umulhi(0xCD9E8D57u, c2), l1 = 0xCD9E8D57u * c2;
-        c0 = h1 ^ c1 ^ k0;
-        c1 = l1;
-        c2 = h0 ^ c3 ^ k1;
-        c3 = l0;
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;   // one 32x32->64 multiply gives both halves
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        c0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        c1 = (uint32_t)p1;
+        c2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c3 = (uint32_t)p0;
         k0 += 0x9E3779B9u;
         k1 += 0xBB67AE85u;
     }
@@ -32,18 +32,28 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 }
 
 struct NoiseLds {
-    uint32_t hi[NOISE_TABLE_MAX];
+    uint32_t hi[NOISE_TABLE_MAX + 2];   // entries >= n hold 0xFFFFFFFF
     uint32_t lo[NOISE_TABLE_MAX];
     uint16_t guide[NOISE_GUIDE_SIZE + 2];
 };
 
-// #{j < n : T[j] <= u} for u = (uhi, ulo); the low word is produced on demand.
-template <typename LowWord>
-__device__ __forceinline__ int threshold_count(const NoiseLds &t, int n, uint32_t uhi, LowWord low_word) {
-    int c = t.guide[uhi >> (32 - NOISE_GUIDE_BITS)];
-    while (c < n && t.hi[c] < uhi) ++c;
+// #{j < n : T[j] <= u} when the guide bucket holds more than one candidate or the
+// high word ties with a threshold: binary search inside the bucket, then the
+// 64-bit comparison for the (rare) equal high words.
+__device__ __noinline__ int threshold_count_slow(const NoiseLds &t, int n, uint32_t uhi, uint32_t grp,
+                                                 uint32_t sample, uint32_t image, uint32_t phase, uint32_t key0,
+                                                 uint32_t key1, int word) {
+    const uint32_t b = uhi >> (32 - NOISE_GUIDE_BITS);
+    int lo = t.guide[b], hi = t.guide[b + 1];    // every threshold with high word < uhi lies below guide[b+1]
+    while (lo < hi) {                             // first index whose high word is >= uhi
+        int mid = (lo + hi) >> 1;
+        if (t.hi[mid] < uhi) lo = mid + 1; else hi = mid;
+    }
+    int c = lo;
     if (c < n && t.hi[c] == uhi) {
-        uint32_t ulo = low_word();
+        uint32_t lo4[4];
+        philox4x32_10(grp, sample, image, phase * 2u + 1u, key0, key1, lo4);
+        const uint32_t ulo = lo4[word & 3];
         while (c < n && t.hi[c] == uhi && t.lo[c] <= ulo) ++c;
     }
     return c;
@@ -55,7 +65,9 @@ __global__ __launch_bounds__(256) void noise_kernel(const NoiseParams p) {
         t.hi[i] = p.table->hi[i];
         t.lo[i] = p.table->lo[i];
     }
-    for (int i = threadIdx.x; i < (int)NOISE_GUIDE_SIZE + 2; i += 256) t.guide[i] = p.table->guide[i];
+    if (threadIdx.x < 2) t.hi[NOISE_TABLE_MAX + threadIdx.x] = 0xFFFFFFFFu;
+    for (int i = threadIdx.x; i < (int)(NOISE_GUIDE_SIZE + 2) / 2; i += 256)   // two 16-bit entries per word
+        ((uint32_t *)t.guide)[i] = ((const uint32_t *)p.table->guide)[i];
     const int n = (int)p.table->n;
     const int dmin = p.table->dmin;
     __syncthreads();
@@ -68,7 +80,7 @@ __global__ __launch_bounds__(256) void noise_kernel(const NoiseParams p) {
         const int rem = (int)(g - (long)s_local * groups_per_sample);
         const int y = rem / W4, x4 = rem - y * W4;
         const uint32_t sample = p.sample_begin + s_local;
-        int val[3][4];
+        uint32_t packed[4] = {0, 0, 0, 0};
 #pragma unroll
         for (int c = 0; c < 3; ++c) {
             if (c < p.C) {
@@ -79,25 +91,20 @@ __global__ __launch_bounds__(256) void noise_kernel(const NoiseParams p) {
                 const uint32_t px4 = *(const uint32_t *)(p.x + pix);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    int cnt = threshold_count(t, n, hi[j], [&]() {
-                        uint32_t lo[4];
-                        philox4x32_10(grp, sample, p.image, p.phase * 2u + 1u, p.key0, p.key1, lo);
-                        return lo[j];
-                    });
+                    const uint32_t u = hi[j];
+                    int cnt = t.guide[u >> (32 - NOISE_GUIDE_BITS)];
+                    const uint32_t t0 = t.hi[cnt], t1 = t.hi[cnt + 1];
+                    cnt += t0 < u;
+                    // common case: at most one threshold below u in the bucket and no tie
+                    if ((t0 < u ? t1 : t0) <= u)
+                        cnt = threshold_count_slow(t, n, u, grp, sample, p.image, p.phase, p.key0, p.key1, j);
                     int v = (int)((px4 >> (8 * j)) & 0xFF) + dmin + cnt;
-                    v = v < 0 ? 0 : (v > 255 ? 255 : v);
-                    val[c][j] = v - 128;
+                    v = (v < 0 ? 0 : (v > 255 ? 255 : v)) - 128;
+                    packed[j] |= (uint32_t)(v & 0xFF) << (8 * c);
                 }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) val[c][j] = 0;
             }
         }
-        v4i o;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            o[j] = (int)((uint32_t)(val[0][j] & 0xFF) | ((uint32_t)(val[1][j] & 0xFF) << 8) |
-                         ((uint32_t)(val[2][j] & 0xFF) << 16));
+        v4i o = {(int)packed[0], (int)packed[1], (int)packed[2], (int)packed[3]};
         *(v4i *)(p.out + ((long)s_local * groups_per_sample + rem) * 16) = o;
     }
 }
@@ -107,7 +114,7 @@ hipError_t launch_noise(const NoiseParams &p, hipStream_t st) {
     if (p.C < 1 || p.C > 3 || (p.W & 3) != 0) return hipErrorInvalidValue;
     long total = (long)p.H * (p.W >> 2) * p.count;
     long blocks = (total + 255) / 256;
-    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (blocks > 256 * 4) blocks = 256 * 4;   // the table is staged into LDS once per workgroup
     hipLaunchKernelGGL(noise_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p);
     return hipGetLastError();
 }
