@@ -71,6 +71,7 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
     __shared__ __attribute__((aligned(16))) int8_t As[2][BM * 64];
     __shared__ __attribute__((aligned(16))) int8_t Bs[2][BN * 64];
     __shared__ uint32_t ktab_s[1024];
+    __shared__ __attribute__((aligned(16))) int prm_s[4][BM];   // bias, M0, chi, shift-1 of this M tile
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WGM, wn = wave / WGM;
@@ -88,6 +89,10 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
 
     if (!flat)
         for (int i = tid; i < nk * 4; i += 256) ktab_s[i] = p.ktab[i];
+    for (int i = tid; i < BM; i += 256) {
+        prm_s[0][i] = p.bias[m0 + i];
+        if constexpr (FAST) { prm_s[1][i] = p.m0s[m0 + i]; prm_s[2][i] = p.chi[m0 + i]; prm_s[3][i] = p.shm1[m0 + i]; }
+    }
 
     // per-thread gather state for its NB activation rows
     long base[NB];
@@ -170,26 +175,43 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
         }
     };
 
-    // accumulators start at the folded bias
     typedef int acc_t __attribute__((ext_vector_type(ACC)));
     acc_t acc[FM][FN];
+    // first channel (within the M tile) held by this lane for fragment fm
+    auto lane_oc = [&](int fm) { return wm * WM + fm * MT + (MT == 32 ? 16 * (lane >> 5) : 4 * (lane >> 4)); };
+
+    // residual operand of a fused add: fetched up front, consumed in the epilogue
+    int rres[FUSE ? FM : 1][FUSE ? FN : 1][ACC / 4];
+    if constexpr (FUSE) {
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+            for (int fn = 0; fn < FN; ++fn) {
+                long n = n0 + wn * WN + fn * MT + (lane & (MT - 1));
+                if (n >= p.npix) n = p.npix - 1;
+                int occ = m0 + lane_oc(fm);
+                if (occ >= p.Cout_p) occ = 0;
+                const int8_t *src = p.res + n * p.Cout_p + occ;
+                if constexpr (MT == 32) {
+                    v4i rv = *(const v4i *)src;
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) rres[fm][fn][d] = rv[d];
+                } else {
+                    rres[fm][fn][0] = *(const int *)src;
+                }
+            }
+    }
+
+    __syncthreads();   // ktab_s, prm_s visible
+    // accumulators start at the folded bias
 #pragma unroll
     for (int fm = 0; fm < FM; ++fm) {
         acc_t init;
-        if constexpr (MT == 32) {
-            const int *bp = p.bias + m0 + wm * WM + fm * 32 + 16 * (lane >> 5);
 #pragma unroll
-            for (int i = 0; i < ACC; ++i) init[i] = bp[i];
-        } else {
-            const int *bp = p.bias + m0 + wm * WM + fm * 16 + 4 * (lane >> 4);
-#pragma unroll
-            for (int i = 0; i < ACC; ++i) init[i] = bp[i];
-        }
+        for (int i = 0; i < ACC; ++i) init[i] = prm_s[0][lane_oc(fm) + i];
 #pragma unroll
         for (int fn = 0; fn < FN; ++fn) acc[fm][fn] = init;
     }
-
-    __syncthreads();   // ktab_s visible
     load_global(0);
     store_lds(0);
     __syncthreads();
@@ -250,7 +272,9 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
         if constexpr (FAST) {
             int mm[ACC], ch[ACC], ss[ACC];
 #pragma unroll
-            for (int i = 0; i < ACC; ++i) { mm[i] = p.m0s[oc + i]; ch[i] = p.chi[oc + i]; ss[i] = p.shm1[oc + i]; }
+            for (int i = 0; i < ACC; ++i) {
+                mm[i] = prm_s[1][oc - m0 + i]; ch[i] = prm_s[2][oc - m0 + i]; ss[i] = prm_s[3][oc - m0 + i];
+            }
 #pragma unroll
             for (int fn = 0; fn < FN; ++fn) {
                 long n = n0 + wn * WN + fn * MT + (lane & (MT - 1));
@@ -262,17 +286,9 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
                 }
                 if constexpr (FUSE) {
                     // second requantisation: the residual add on the int8 result
-                    int rr[ACC / 4];
-                    if constexpr (MT == 32) {
-                        v4i rv = *(const v4i *)(p.res + n * p.Cout_p + oc);
-#pragma unroll
-                        for (int d = 0; d < 4; ++d) rr[d] = rv[d];
-                    } else {
-                        rr[0] = *(const int *)(p.res + n * p.Cout_p + oc);
-                    }
 #pragma unroll
                     for (int i = 0; i < ACC; ++i) {
-                        int r8 = (int)(int8_t)((uint32_t)rr[i >> 2] >> (8 * (i & 3)));
+                        int r8 = (int)(int8_t)((uint32_t)rres[fm][fn][i >> 2] >> (8 * (i & 3)));
                         // 24-bit multiplies (full rate): |q|, |r8| < 2^8 and |multipliers| < 2^23
                         int v = __mul24(q[i], p.add_mul_self) + p.add_c0 + __mul24(r8, p.add_mul_res);
                         q[i] = clamp3((v + p.add_k + (v >> 31)) >> p.add_sh, p.add_lo, 127);
@@ -318,12 +334,12 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
 
 int conv_tile_m(int cout_p) { return cout_p <= 16 ? 16 : (cout_p <= 32 ? 32 : (cout_p <= 64 ? 64 : 128)); }
 
-template <int MT, int BM, int BN, int WGM, int MINW>
+template <int MT, int BM, int BN, int WGM, int MINW, int MINW_FUSED>
 static hipError_t launch_one(const ConvParams &p, hipStream_t st) {
     dim3 grid((unsigned)(((p.npix + BN - 1) / BN) * ((p.Cout_p + BM - 1) / BM)));
     if (p.fuse_add && !p.fast_requant) return hipErrorInvalidValue;
     if (p.fuse_add)
-        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, true, MINW, true>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, true, MINW_FUSED, true>), grid, dim3(256), 0, st, p);
     else if (p.fast_requant)
         hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, true, MINW, false>), grid, dim3(256), 0, st, p);
     else
@@ -336,10 +352,10 @@ hipError_t launch_conv(const ConvParams &p, hipStream_t st) {
     if (p.Kp % 64 != 0 || p.Kp > 16384 || p.Cout_p % 16 != 0 || p.Mp % 128 != 0 || p.Mp < p.Cout_p)
         return hipErrorInvalidValue;
     switch (conv_tile_m(p.Cout_p)) {
-    case 16: return launch_one<16, 16, 256, 1, 4>(p, st);
-    case 32: return launch_one<32, 32, 256, 1, 4>(p, st);
-    case 64: return launch_one<32, 64, 256, 1, 3>(p, st);
-    default: return launch_one<32, 128, 128, 2, 4>(p, st);
+    case 16: return launch_one<16, 16, 256, 1, 4, 4>(p, st);
+    case 32: return launch_one<32, 32, 256, 1, 3, 3>(p, st);
+    case 64: return launch_one<32, 64, 256, 1, 3, 3>(p, st);
+    default: return launch_one<32, 128, 128, 2, 4, 3>(p, st);
     }
 }
 
