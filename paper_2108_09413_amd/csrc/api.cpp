@@ -244,13 +244,17 @@ int build_device_ops(isr_model *m, ConstArena &arena) {
             }
             const bool flat = !c4 && k == 1 && o.stride == 1 && o.pad == 0 && cin_p % 64 == 0;
             std::vector<uint32_t> ktab(Kp / 16, 0xFFFFFFFFu);
+            std::vector<int32_t> ktoff(Kp / 16, 0);
             for (int j = 0; j < Kp / 16; ++j) {
                 if (c4) {
                     int per_row = kwp / 4, ky = j / per_row, kx0 = (j % per_row) * 4;
-                    if (ky < k) ktab[j] = (uint32_t)ky | ((uint32_t)kx0 << 8);
+                    if (ky < k) { ktab[j] = (uint32_t)ky | ((uint32_t)kx0 << 8); ktoff[j] = (ky * ti.W + kx0) * 4; }
                 } else {
                     int k0 = j * 16, tap = k0 / cin_p, ic = k0 % cin_p;
-                    if (tap < k * k) ktab[j] = (uint32_t)(tap / k) | ((uint32_t)(tap % k) << 8) | ((uint32_t)ic << 16);
+                    if (tap < k * k) {
+                        ktab[j] = (uint32_t)(tap / k) | ((uint32_t)(tap % k) << 8);
+                        ktoff[j] = ((tap / k) * ti.W + (tap % k)) * cin_p + ic;
+                    }
                 }
             }
             ConvParams &c = d.conv;
@@ -265,6 +269,7 @@ int build_device_ops(isr_model *m, ConstArena &arena) {
             c.shm1 = (const int32_t *)arena.put(shm1.data(), shm1.size() * 4);
             c.fast_requant = fast ? 1 : 0;
             c.ktab = flat ? (const uint32_t *)~(uintptr_t)0 : (const uint32_t *)arena.put(ktab.data(), ktab.size() * 4);
+            c.ktoff = flat ? (const int32_t *)~(uintptr_t)0 : (const int32_t *)arena.put(ktoff.data(), ktoff.size() * 4);
             c.H = ti.H; c.W = ti.W; c.Cin_p = cin_p; c.Ho = to.H; c.Wo = to.W; c.Cout_p = cout_p;
             c.stride = o.stride; c.pad = o.pad; c.Kp = Kp; c.Mp = Mp;
             c.zp_in = ti.zp; c.zp_out = to.zp; c.relu = o.relu; c.c4 = c4 ? 1 : 0;
@@ -492,7 +497,7 @@ int isr_load_model(const void *blob_host, size_t bytes, isr_model **out) {
         if (d.type == OP_CONV) {
             rebase(d.conv.w, m->dconst); rebase(d.conv.bias, m->dconst); rebase(d.conv.m0x2, m->dconst);
             rebase(d.conv.rnd_lo, m->dconst); rebase(d.conv.rnd_hi, m->dconst); rebase(d.conv.shift, m->dconst);
-            rebase(d.conv.ktab, m->dconst);
+            rebase(d.conv.ktab, m->dconst); rebase(d.conv.ktoff, m->dconst);
             rebase(d.conv.m0s, m->dconst); rebase(d.conv.chi, m->dconst); rebase(d.conv.shm1, m->dconst);
         } else if (d.type == OP_FC) {
             rebase(d.fc.w, m->dconst); rebase(d.fc.bias, m->dconst);

@@ -70,7 +70,8 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
 
     __shared__ __attribute__((aligned(16))) int8_t As[2][BM * 64];
     __shared__ __attribute__((aligned(16))) int8_t Bs[2][BN * 64];
-    __shared__ uint32_t ktab_s[1024];
+    __shared__ uint32_t ktg_s[512];   // per 16-byte K chunk: ky | kx << 8, 0xFFFFFFFF = padding chunk
+    __shared__ int kto_s[512];        // per 16-byte K chunk: byte offset of its tap and channel from the window origin
     __shared__ __attribute__((aligned(16))) int prm_s[4][BM];   // bias, M0, chi, shift-1 of this M tile
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -88,14 +89,15 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
     const bool flat = p.ktab == nullptr;   // 1x1, stride 1, no padding: pixel n reads input pixel n
 
     if (!flat)
-        for (int i = tid; i < nk * 4; i += 256) ktab_s[i] = p.ktab[i];
+        for (int i = tid; i < nk * 4; i += 256) { ktg_s[i] = p.ktab[i]; kto_s[i] = p.ktoff[i]; }
     for (int i = tid; i < BM; i += 256) {
         prm_s[0][i] = p.bias[m0 + i];
         if constexpr (FAST) { prm_s[1][i] = p.m0s[m0 + i]; prm_s[2][i] = p.chi[m0 + i]; prm_s[3][i] = p.shm1[m0 + i]; }
     }
 
-    // per-thread gather state for its NB activation rows
-    long base[NB];
+    // per-thread gather state for its NB activation rows: byte offset of the window
+    // origin (may be negative inside the padding; a chunk's tensor is below 2 GiB)
+    int pixoff[NB];
     int iy0[NB], ix0[NB];
     bool rvalid[NB];
     const int HoWo = p.Ho * p.Wo;
@@ -104,16 +106,17 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
         long n = n0 + row0 + 64 * j;
         rvalid[j] = n < p.npix;
         if (flat) {
-            base[j] = (rvalid[j] ? n : (long)p.npix - 1) * p.Cin_p;
+            // rows past the end re-read the last pixel; their results are never stored
+            pixoff[j] = (int)((rvalid[j] ? n : (long)p.npix - 1) * p.Cin_p) + col * 16;
             iy0[j] = ix0[j] = 0;
         } else {
-            long nn = rvalid[j] ? n : 0;
-            int b = (int)(nn / HoWo);
-            int rem = (int)(nn - (long)b * HoWo);
+            int nn = rvalid[j] ? (int)n : 0;
+            int b = nn / HoWo;
+            int rem = nn - b * HoWo;
             int oy = rem / p.Wo, ox = rem - oy * p.Wo;
-            base[j] = (long)b * p.H * p.W * p.Cin_p;
             iy0[j] = oy * p.stride - p.pad;
             ix0[j] = ox * p.stride - p.pad;
+            pixoff[j] = ((b * p.H + iy0[j]) * p.W + ix0[j]) * p.Cin_p;
         }
     }
     const uint32_t zb = (uint32_t)(p.zp_in & 0xFF) * 0x01010101u;
@@ -129,34 +132,36 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
         for (int j = 0; j < NA; ++j)
             if (BM * 4 >= 256 || row0 + 64 * j < BM) ra[j] = *(const v4i *)(wrow[j] + (long)ks * 64);
         if (flat) {
-            // rows past the end re-read the last pixel; their results are never stored
 #pragma unroll
-            for (int j = 0; j < NB; ++j) rb[j] = *(const v4i *)(p.in + base[j] + ks * 64 + col * 16);
+            for (int j = 0; j < NB; ++j) rb[j] = *(const v4i *)(p.in + (uint32_t)(pixoff[j] + ks * 64));
         } else if (!p.c4) {
-            uint32_t e = ktab_s[ks * 4 + col];
-            int ky = e & 0xFF, kx = (e >> 8) & 0xFF, ic = e >> 16;
+            const uint32_t g = ktg_s[ks * 4 + col];
+            const int toff = kto_s[ks * 4 + col];
+            const int ky = g & 0xFF, kx = (g >> 8) & 0xFF;
 #pragma unroll
             for (int j = 0; j < NB; ++j) {
                 int iy = iy0[j] + ky, ix = ix0[j] + kx;
-                bool ok = rvalid[j] && e != 0xFFFFFFFFu && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
-                long off = ok ? base[j] + ((long)iy * p.W + ix) * p.Cin_p + ic : 0;   // offset 0 is always readable
+                bool ok = rvalid[j] && g != 0xFFFFFFFFu && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
+                uint32_t off = ok ? (uint32_t)(pixoff[j] + toff) : 0u;   // offset 0 is always readable
                 v4i v = *(const v4i *)(p.in + off);
                 rb[j] = ok ? v : zfill;
             }
         } else {
-            uint32_t e = ktab_s[ks * 4 + col];
-            int ky = e & 0xFF, kx = (e >> 8) & 0xFF;
+            const uint32_t g = ktg_s[ks * 4 + col];
+            const int toff = kto_s[ks * 4 + col];
+            const int ky = g & 0xFF, kx = (g >> 8) & 0xFF;
 #pragma unroll
             for (int j = 0; j < NB; ++j) {
                 int iy = iy0[j] + ky;
-                bool rowok = rvalid[j] && e != 0xFFFFFFFFu && (unsigned)iy < (unsigned)p.H;
-                const int8_t *src = p.in + base[j] + (long)iy * p.W * 4;
+                bool rowok = rvalid[j] && g != 0xFFFFFFFFu && (unsigned)iy < (unsigned)p.H;
                 v4i v;
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     int ix = ix0[j] + kx + t;
                     bool ok = rowok && (unsigned)ix < (unsigned)p.W;
-                    v[t] = ok ? *(const int *)(src + ix * 4) : (int)zb;
+                    uint32_t off = ok ? (uint32_t)(pixoff[j] + toff + 4 * t) : 0u;
+                    int w = *(const int *)(p.in + off);
+                    v[t] = ok ? w : (int)zb;
                 }
                 rb[j] = v;
             }
@@ -349,7 +354,7 @@ static hipError_t launch_one(const ConvParams &p, hipStream_t st) {
 
 hipError_t launch_conv(const ConvParams &p, hipStream_t st) {
     if (p.npix <= 0) return hipSuccess;
-    if (p.Kp % 64 != 0 || p.Kp > 16384 || p.Cout_p % 16 != 0 || p.Mp % 128 != 0 || p.Mp < p.Cout_p)
+    if (p.Kp % 64 != 0 || p.Kp > 8192 || p.Cout_p % 16 != 0 || p.Mp % 128 != 0 || p.Mp < p.Cout_p)
         return hipErrorInvalidValue;
     switch (conv_tile_m(p.Cout_p)) {
     case 16: return launch_one<16, 16, 256, 1, 4, 4>(p, st);

@@ -74,7 +74,8 @@ struct ConvParams {
     //   out = clamp((v + add_k + (v >> 31)) >> add_sh, add_lo, 127)  (add_k = 2^(sh-1) + z_o 2^sh)
     const int8_t *res;       // [B][Ho][Wo][Cout_p] other input of the add
     int32_t fuse_add, add_mul_self, add_mul_res, add_c0, add_k, add_sh, add_lo;
-    const uint32_t *ktab;    // [Kp/16] packed (ky | kx<<8 | ic<<16), 0xFFFFFFFF = no tap
+    const uint32_t *ktab;    // [Kp/16] per 16-byte K chunk: ky | kx<<8, 0xFFFFFFFF = padding chunk; null = plain GEMM
+    const int32_t *ktoff;    // [Kp/16] byte offset (ky*W + kx)*Cin_p + channel of the chunk
     int32_t H, W, Cin_p, Ho, Wo, Cout_p;
     int32_t stride, pad, Kp, Mp;
     int32_t zp_in, zp_out, relu;

@@ -164,7 +164,7 @@ int parse_model(const void *blob, size_t bytes, ParsedModel &m, std::string &why
             const TensorDesc &ti = m.tensors[o.a];
             if (o.a == 0 && o.k > 8) return fail(ISR_ERR_UNSUPPORTED, "first-layer kernel wider than 8");
             int64_t kp = o.a == 0 ? (int64_t)o.k * ((o.k + 3) & ~3) * 4 : (int64_t)o.k * o.k * ti.Cp;
-            if (kp > 16384) return fail(ISR_ERR_UNSUPPORTED, "convolution depth above 16384");
+            if (kp > 8192) return fail(ISR_ERR_UNSUPPORTED, "convolution depth above 8192");
         } else if (o.a == 0 || o.b == 0) {
             return fail(ISR_ERR_UNSUPPORTED, "the input tensor must feed a convolution");
         }
