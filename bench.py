@@ -44,6 +44,8 @@ def main():
     ap.add_argument("--chunk", type=int, default=0, help="noisy copies per device chunk (0 = default)")
     ap.add_argument("--n", type=int, default=0, help="override estimation samples per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (reference for HBM byte counters)")
     ap.add_argument("--profile-every", type=int, default=16,
                     help="time every kernel of each k-th chunk with HIP events (0 = off)")
     args = ap.parse_args()
@@ -79,6 +81,12 @@ def main():
         i, s = pairs[k % len(pairs)]
         return isr.isr_certify(model, images[i], s, n0, n, alpha, seed=0, image_id=i + 1, want_counts=False)[0]
 
+    if args.copy_calibration_mib:
+        src = torch.zeros(args.copy_calibration_mib << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for k in range(args.warmup):
         step(k)
     isr.isr_profile(model, args.profile_every)
@@ -115,6 +123,20 @@ def main():
                  "GB/s": round(s["alg_bytes"] / (s["total_ms"] * 1e-3) / 1e9, 1),
                  "time_share": round(s["total_ms"] / all_ms, 4)} for s in stats],
         }
+
+    # HBM bytes per conv launch from the committed rocprofv3 counter summary (measured offline,
+    # per noisy inference; scaled to the launches of one chunk)
+    if roofline is not None and args.workload == "resnet50":
+        try:
+            import re
+            txt = open(os.path.join(ROOT, "profiles", "resnet50_certify_hbm_traffic.md")).read()
+            mt = re.search(r"conv_hbm_bytes_per_inference: fetch=(\d+) write=(\d+)", txt)
+            launches_per_inference = conv_launches / max(sum(s["launches"] for s in stats if s["name"] == "noise"), 1) / chunk
+            roofline["traffic"] = round((int(mt.group(1)) + int(mt.group(2))) / launches_per_inference)
+            roofline["traffic_note"] = "HBM bytes per conv launch: rocprofv3 FETCH_SIZE+WRITE_SIZE per inference x inferences per launch"
+            roofline["alg_bytes_per_launch"] = round(sum(s["alg_bytes"] for s in conv) / max(conv_launches, 1))
+        except Exception:
+            pass
 
     cpu = None
     if not args.no_cpu_baseline:
