@@ -210,13 +210,15 @@ int build_device_ops(isr_model *m, ConstArena &arena) {
             const int cin_p = ti.Cp, cout_p = to.Cp, k = o.k;
             const int kwp = (k + 3) & ~3;
             const int kreal = c4 ? k * kwp * 4 : k * k * cin_p;
-            const int Kp = (int)round_up((size_t)kreal, 64), Mp = (int)round_up((size_t)cout_p, 128);
+            bool fast = true;
+            for (int oc = 0; oc < to.C; ++oc) fast = fast && o.shift[oc] >= 2 && o.shift[oc] <= 22;
+            const int kb = conv_k_step(kreal, c4 ? 0 : cin_p, cout_p, fast ? 1 : 0);
+            const int Kp = (int)round_up((size_t)kreal, (size_t)kb), Mp = (int)round_up((size_t)cout_p, 128);
             const bool perm = conv_tile_m(cout_p) != 16;
             std::vector<int8_t> w((size_t)Mp * Kp, 0);
             std::vector<int32_t> bias(Mp, 0);
             std::vector<uint32_t> m0x2(Mp, 0x80000000u), rlo(Mp, 0), rhi(Mp, 1), sh(Mp, 1);
             std::vector<int32_t> m0s(Mp, 1 << 30), chi(Mp, 1 + 2 * to.zp), shm1(Mp, 1);
-            bool fast = true;
             for (int oc = 0; oc < to.C; ++oc) {
                 int row = perm ? (oc & ~31) + mfma32_row_of_channel(oc & 31) : oc;
                 int64_t wsum = 0;
@@ -238,8 +240,6 @@ int build_device_ops(isr_model *m, ConstArena &arena) {
                     m0s[oc] = o.M0[oc];
                     chi[oc] = (1 << (o.shift[oc] - 2)) + to.zp * (1 << (o.shift[oc] - 1));
                     shm1[oc] = o.shift[oc] - 1;
-                } else {
-                    fast = false;
                 }
             }
             const bool flat = !c4 && k == 1 && o.stride == 1 && o.pad == 0 && cin_p % 64 == 0;
@@ -271,7 +271,7 @@ int build_device_ops(isr_model *m, ConstArena &arena) {
             c.ktab = flat ? (const uint32_t *)~(uintptr_t)0 : (const uint32_t *)arena.put(ktab.data(), ktab.size() * 4);
             c.ktoff = flat ? (const int32_t *)~(uintptr_t)0 : (const int32_t *)arena.put(ktoff.data(), ktoff.size() * 4);
             c.H = ti.H; c.W = ti.W; c.Cin_p = cin_p; c.Ho = to.H; c.Wo = to.W; c.Cout_p = cout_p;
-            c.stride = o.stride; c.pad = o.pad; c.Kp = Kp; c.Mp = Mp;
+            c.stride = o.stride; c.pad = o.pad; c.Kp = Kp; c.Mp = Mp; c.kb = kb;
             c.zp_in = ti.zp; c.zp_out = to.zp; c.relu = o.relu; c.c4 = c4 ? 1 : 0;
             int tm = conv_tile_m(cout_p);
             d.kclass = tm == 16 ? KC_CONV16 : tm == 32 ? KC_CONV32 : tm == 64 ? KC_CONV64 : KC_CONV128;

@@ -10,8 +10,11 @@
 // Epilogue: q = clamp(z_out + RHA(acc * M0, 31 + shift), relu ? z_out : -128, 127),
 // one rounding, half away from zero, written as int8 NHWC.
 //
-// Tile: 256 threads = 4 waves; a BM x BN block of the output, K consumed in
-// 64-byte steps staged through LDS (double buffered, register prefetch).
+// Tile: 256 threads = 4 waves; a BM x BN block of the output, K consumed in steps
+// of KB bytes staged through LDS with register prefetch.  KB = 64: two LDS
+// buffers, one barrier per step.  KB = 128: every activation row read is a full
+// 128-byte line (64-byte row segments only reach about half of the L1 rate on
+// this chip), one LDS buffer, two barriers per step.
 // MT = 32 uses v_mfma_i32_32x32x32_i8, MT = 16 uses v_mfma_i32_16x16x64_i8.
 #include "isr_internal.h"
 
@@ -20,9 +23,11 @@ namespace isr {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-// 16-byte chunk swizzle inside a 64-byte LDS row: spreads equal chunk indices of
-// neighbouring rows over different banks for the 128-bit fragment reads.
-__device__ __forceinline__ int swz(int row) { return ((row >> 1) ^ (row >> 3)) & 3; }
+// 16-byte chunk swizzle inside an LDS row of CPR chunks: spreads equal chunk
+// indices of neighbouring rows over different banks for the 128-bit fragment reads
+// (8 consecutive rows must cover all 32 banks).
+template <int CPR>
+__device__ __forceinline__ int swz(int row) { return CPR == 4 ? (((row >> 1) ^ (row >> 3)) & 3) : (row & 7); }
 
 // RHA(acc * M0, 31 + shift) on magnitude and sign, 32x32->64 multiply-add:
 //   |acc| * (M0 << 1) + 2^(31+shift) = 2 * (|acc| * M0 + 2^(30+shift)),
@@ -59,17 +64,20 @@ __device__ __forceinline__ uint32_t pack4(int a, int b, int c, int d) {
     return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
 }
 
-template <int MT, int BM, int BN, int WGM, bool FAST, int MINW, bool FUSE>
+template <int MT, int BM, int BN, int WGM, bool FAST, int MINW, bool FUSE, int KB>
 __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams p) {
     constexpr int WGN = 4 / WGM;
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int FM = WM / MT, FN = WN / MT;
-    constexpr int NA = (BM * 4 + 255) / 256, NB = BN * 4 / 256;
+    constexpr int CPR = KB / 16;            // 16-byte chunks per tile row
+    constexpr int RPP = 256 / CPR;          // rows covered by one pass of the 256 threads
+    constexpr int NBUF = KB == 64 ? 2 : 1;
+    constexpr int NA = (BM * CPR + 255) / 256, NB = BN * CPR / 256;
     constexpr int ACC = MT == 32 ? 16 : 4;
-    static_assert(WM % MT == 0 && WN % MT == 0 && BN % 64 == 0, "tile shape");
+    static_assert(WM % MT == 0 && WN % MT == 0 && BN % 64 == 0 && (KB == 64 || KB == 128), "tile shape");
 
-    __shared__ __attribute__((aligned(16))) int8_t As[2][BM * 64];
-    __shared__ __attribute__((aligned(16))) int8_t Bs[2][BN * 64];
+    __shared__ __attribute__((aligned(16))) int8_t As[NBUF][BM * KB];
+    __shared__ __attribute__((aligned(16))) int8_t Bs[NBUF][BN * KB];
     __shared__ uint32_t ktg_s[512];   // per 16-byte K chunk: ky | kx << 8, 0xFFFFFFFF = padding chunk
     __shared__ int kto_s[512];        // per 16-byte K chunk: byte offset of its tap and channel from the window origin
     __shared__ __attribute__((aligned(16))) int prm_s[4][BM];   // bias, M0, chi, shift-1 of this M tile
@@ -84,12 +92,12 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
     const int logical = xcd * per + (xcd < extra ? xcd : extra) + (blockIdx.x >> 3);
     const int m0 = (logical % mt) * BM;
     const long n0 = (long)(logical / mt) * BN;
-    const int nk = p.Kp >> 6;
-    const int col = tid & 3, row0 = tid >> 2;
+    const int nk = p.Kp / KB;
+    const int col = tid % CPR, row0 = tid / CPR;
     const bool flat = p.ktab == nullptr;   // 1x1, stride 1, no padding: pixel n reads input pixel n
 
     if (!flat)
-        for (int i = tid; i < nk * 4; i += 256) { ktg_s[i] = p.ktab[i]; kto_s[i] = p.ktoff[i]; }
+        for (int i = tid; i < nk * CPR; i += 256) { ktg_s[i] = p.ktab[i]; kto_s[i] = p.ktoff[i]; }
     for (int i = tid; i < BM; i += 256) {
         prm_s[0][i] = p.bias[m0 + i];
         if constexpr (FAST) { prm_s[1][i] = p.m0s[m0 + i]; prm_s[2][i] = p.chi[m0 + i]; prm_s[3][i] = p.shm1[m0 + i]; }
@@ -103,7 +111,7 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
     const int HoWo = p.Ho * p.Wo;
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
-        long n = n0 + row0 + 64 * j;
+        long n = n0 + row0 + RPP * j;
         rvalid[j] = n < p.npix;
         if (flat) {
             // rows past the end re-read the last pixel; their results are never stored
@@ -123,20 +131,20 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
     const v4i zfill = {(int)zb, (int)zb, (int)zb, (int)zb};
     const int8_t *wrow[NA];
 #pragma unroll
-    for (int j = 0; j < NA; ++j) wrow[j] = p.w + (long)(m0 + row0 + 64 * j) * p.Kp + col * 16;
+    for (int j = 0; j < NA; ++j) wrow[j] = p.w + (long)(m0 + row0 + RPP * j) * p.Kp + col * 16;
 
-    v4i ra[NA], rb[NB];
+    v4i ra[NA], rb[NB];   // the next K step, in flight while the current one is computed
 
     auto load_global = [&](int ks) {
 #pragma unroll
         for (int j = 0; j < NA; ++j)
-            if (BM * 4 >= 256 || row0 + 64 * j < BM) ra[j] = *(const v4i *)(wrow[j] + (long)ks * 64);
+            if (BM * CPR >= 256 || row0 + RPP * j < BM) ra[j] = *(const v4i *)(wrow[j] + (long)ks * KB);
         if (flat) {
 #pragma unroll
-            for (int j = 0; j < NB; ++j) rb[j] = *(const v4i *)(p.in + (uint32_t)(pixoff[j] + ks * 64));
+            for (int j = 0; j < NB; ++j) rb[j] = *(const v4i *)(p.in + (uint32_t)(pixoff[j] + ks * KB));
         } else if (!p.c4) {
-            const uint32_t g = ktg_s[ks * 4 + col];
-            const int toff = kto_s[ks * 4 + col];
+            const uint32_t g = ktg_s[ks * CPR + col];
+            const int toff = kto_s[ks * CPR + col];
             const int ky = g & 0xFF, kx = (g >> 8) & 0xFF;
 #pragma unroll
             for (int j = 0; j < NB; ++j) {
@@ -147,8 +155,8 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
                 rb[j] = ok ? v : zfill;
             }
         } else {
-            const uint32_t g = ktg_s[ks * 4 + col];
-            const int toff = kto_s[ks * 4 + col];
+            const uint32_t g = ktg_s[ks * CPR + col];
+            const int toff = kto_s[ks * CPR + col];
             const int ky = g & 0xFF, kx = (g >> 8) & 0xFF;
 #pragma unroll
             for (int j = 0; j < NB; ++j) {
@@ -170,13 +178,13 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
     auto store_lds = [&](int buf) {
 #pragma unroll
         for (int j = 0; j < NA; ++j) {
-            int r = row0 + 64 * j;
-            if (BM * 4 >= 256 || r < BM) *(v4i *)(&As[buf][r * 64 + ((col ^ swz(r)) << 4)]) = ra[j];
+            int r = row0 + RPP * j;
+            if (BM * CPR >= 256 || r < BM) *(v4i *)(&As[buf][r * KB + ((col ^ swz<CPR>(r)) << 4)]) = ra[j];
         }
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
-            int r = row0 + 64 * j;
-            *(v4i *)(&Bs[buf][r * 64 + ((col ^ swz(r)) << 4)]) = rb[j];
+            int r = row0 + RPP * j;
+            *(v4i *)(&Bs[buf][r * KB + ((col ^ swz<CPR>(r)) << 4)]) = rb[j];
         }
     };
 
@@ -218,26 +226,33 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
         for (int fn = 0; fn < FN; ++fn) acc[fm][fn] = init;
     }
     load_global(0);
-    store_lds(0);
-    __syncthreads();
+    if constexpr (NBUF == 2) {
+        store_lds(0);
+        __syncthreads();
+    }
 
     for (int ks = 0; ks < nk; ++ks) {
-        const int buf = ks & 1;
+        const int buf = NBUF == 2 ? (ks & 1) : 0;
+        if constexpr (NBUF == 1) {
+            if (ks) __syncthreads();   // every wave is done reading the previous step
+            store_lds(0);
+            __syncthreads();
+        }
         if (ks + 1 < nk) load_global(ks + 1);
         if constexpr (MT == 32) {
 #pragma unroll
-            for (int ksub = 0; ksub < 2; ++ksub) {
+            for (int ksub = 0; ksub < KB / 32; ++ksub) {
                 const int c = ksub * 2 + (lane >> 5);
                 v4i fa[FM], fb[FN];
 #pragma unroll
                 for (int fm = 0; fm < FM; ++fm) {
                     int r = wm * WM + fm * 32 + (lane & 31);
-                    fa[fm] = *(const v4i *)(&As[buf][r * 64 + ((c ^ swz(r)) << 4)]);
+                    fa[fm] = *(const v4i *)(&As[buf][r * KB + ((c ^ swz<CPR>(r)) << 4)]);
                 }
 #pragma unroll
                 for (int fn = 0; fn < FN; ++fn) {
                     int r = wn * WN + fn * 32 + (lane & 31);
-                    fb[fn] = *(const v4i *)(&Bs[buf][r * 64 + ((c ^ swz(r)) << 4)]);
+                    fb[fn] = *(const v4i *)(&Bs[buf][r * KB + ((c ^ swz<CPR>(r)) << 4)]);
                 }
 #pragma unroll
                 for (int fm = 0; fm < FM; ++fm)
@@ -246,26 +261,31 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
                         acc[fm][fn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[fm], fb[fn], acc[fm][fn], 0, 0, 0);
             }
         } else {
-            const int c = lane >> 4;
-            v4i fa[FM], fb[FN];
 #pragma unroll
-            for (int fm = 0; fm < FM; ++fm) {
-                int r = wm * WM + fm * 16 + (lane & 15);
-                fa[fm] = *(const v4i *)(&As[buf][r * 64 + ((c ^ swz(r)) << 4)]);
+            for (int ksub = 0; ksub < KB / 64; ++ksub) {
+                const int c = ksub * 4 + (lane >> 4);
+                v4i fa[FM], fb[FN];
+#pragma unroll
+                for (int fm = 0; fm < FM; ++fm) {
+                    int r = wm * WM + fm * 16 + (lane & 15);
+                    fa[fm] = *(const v4i *)(&As[buf][r * KB + ((c ^ swz<CPR>(r)) << 4)]);
+                }
+#pragma unroll
+                for (int fn = 0; fn < FN; ++fn) {
+                    int r = wn * WN + fn * 16 + (lane & 15);
+                    fb[fn] = *(const v4i *)(&Bs[buf][r * KB + ((c ^ swz<CPR>(r)) << 4)]);
+                }
+#pragma unroll
+                for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+                    for (int fn = 0; fn < FN; ++fn)
+                        acc[fm][fn] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[fm], fb[fn], acc[fm][fn], 0, 0, 0);
             }
-#pragma unroll
-            for (int fn = 0; fn < FN; ++fn) {
-                int r = wn * WN + fn * 16 + (lane & 15);
-                fb[fn] = *(const v4i *)(&Bs[buf][r * 64 + ((c ^ swz(r)) << 4)]);
-            }
-#pragma unroll
-            for (int fm = 0; fm < FM; ++fm)
-#pragma unroll
-                for (int fn = 0; fn < FN; ++fn)
-                    acc[fm][fn] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[fm], fb[fn], acc[fm][fn], 0, 0, 0);
         }
-        if (ks + 1 < nk) store_lds(buf ^ 1);
-        __syncthreads();
+        if constexpr (NBUF == 2) {
+            if (ks + 1 < nk) store_lds(buf ^ 1);
+            __syncthreads();
+        }
     }
 
     // epilogue: requantise, clamp, pack, store (NHWC)
@@ -339,28 +359,39 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
 
 int conv_tile_m(int cout_p) { return cout_p <= 16 ? 16 : (cout_p <= 32 ? 32 : (cout_p <= 64 ? 64 : 128)); }
 
-template <int MT, int BM, int BN, int WGM, int MINW, int MINW_FUSED>
-static hipError_t launch_one(const ConvParams &p, hipStream_t st) {
+template <int MT, int BM, int BN, int WGM, int MINW, int MINW_FUSED, int KB>
+static hipError_t launch_kb(const ConvParams &p, hipStream_t st) {
     dim3 grid((unsigned)(((p.npix + BN - 1) / BN) * ((p.Cout_p + BM - 1) / BM)));
     if (p.fuse_add && !p.fast_requant) return hipErrorInvalidValue;
     if (p.fuse_add)
-        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, true, MINW_FUSED, true>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, true, MINW_FUSED, true, KB>), grid, dim3(256), 0, st, p);
     else if (p.fast_requant)
-        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, true, MINW, false>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, true, MINW, false, KB>), grid, dim3(256), 0, st, p);
     else
-        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, false, 2, false>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, false, 2, false, 64>), grid, dim3(256), 0, st, p);
     return hipGetLastError();
+}
+
+// K bytes per step for a layer whose unpadded depth is `kreal` bytes over `cin_p`
+// stored input channels: 128 where it measured faster (1x1 layers up to K = 512 and
+// layers with at least 512 input channels), needs no extra padding and the
+// single-multiply epilogue applies; else 64.
+int conv_k_step(int kreal, int cin_p, int cout_p, int fast_requant) {
+    const bool one_by_one = kreal == cin_p;
+    const bool wanted = (one_by_one && kreal <= 512) || (!one_by_one && cin_p >= 512);
+    return (fast_requant && cout_p > 32 && kreal % 128 == 0 && wanted) ? 128 : 64;
 }
 
 hipError_t launch_conv(const ConvParams &p, hipStream_t st) {
     if (p.npix <= 0) return hipSuccess;
-    if (p.Kp % 64 != 0 || p.Kp > 8192 || p.Cout_p % 16 != 0 || p.Mp % 128 != 0 || p.Mp < p.Cout_p)
+    if ((p.kb != 64 && p.kb != 128) || p.Kp % p.kb != 0 || p.Kp > 8192 || p.Cout_p % 16 != 0 || p.Mp % 128 != 0 ||
+        p.Mp < p.Cout_p || (p.kb == 128 && (!p.fast_requant || p.Cout_p <= 32)))
         return hipErrorInvalidValue;
     switch (conv_tile_m(p.Cout_p)) {
-    case 16: return launch_one<16, 16, 256, 1, 4, 4>(p, st);
-    case 32: return launch_one<32, 32, 256, 1, 3, 3>(p, st);
-    case 64: return launch_one<32, 64, 256, 1, 3, 3>(p, st);
-    default: return launch_one<32, 128, 128, 2, 4, 3>(p, st);
+    case 16: return launch_kb<16, 16, 256, 1, 4, 4, 64>(p, st);
+    case 32: return launch_kb<32, 32, 256, 1, 3, 3, 64>(p, st);
+    case 64: return p.kb == 128 ? launch_kb<32, 64, 256, 1, 2, 2, 128>(p, st) : launch_kb<32, 64, 256, 1, 3, 3, 64>(p, st);
+    default: return p.kb == 128 ? launch_kb<32, 128, 128, 2, 3, 3, 128>(p, st) : launch_kb<32, 128, 128, 2, 4, 3, 64>(p, st);
     }
 }
 

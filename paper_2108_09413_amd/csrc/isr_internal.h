@@ -78,6 +78,7 @@ struct ConvParams {
     const int32_t *ktoff;    // [Kp/16] byte offset (ky*W + kx)*Cin_p + channel of the chunk
     int32_t H, W, Cin_p, Ho, Wo, Cout_p;
     int32_t stride, pad, Kp, Mp;
+    int32_t kb;              // K bytes per step of the kernel (64 or 128); Kp is a multiple of it
     int32_t zp_in, zp_out, relu;
     int32_t npix;            // B * Ho * Wo
     int32_t c4;              // 1: input is NHWC4 and a K chunk is 4 horizontal taps
@@ -131,6 +132,8 @@ hipError_t launch_fc(const FcParams &p, hipStream_t st);
 hipError_t launch_fill_u32(uint32_t *p, uint32_t value, size_t n, hipStream_t st);
 // Tile geometry of the convolution kernel chosen for (Cout_p): rows per M tile.
 int conv_tile_m(int cout_p);
+// K bytes per step chosen for a layer (see conv_igemm.hip).
+int conv_k_step(int kreal, int cin_p, int cout_p, int fast_requant);
 
 }  // namespace isr
 
