@@ -268,6 +268,8 @@ int build_device_ops(isr_model *m, ConstArena &arena) {
             c.chi = (const int32_t *)arena.put(chi.data(), chi.size() * 4);
             c.shm1 = (const int32_t *)arena.put(shm1.data(), shm1.size() * 4);
             c.fast_requant = fast ? 1 : 0;
+            const std::vector<int8_t> zfill(16, (int8_t)ti.zp);
+            c.zpad = (const int8_t *)arena.put(zfill.data(), zfill.size());
             c.ktab = flat ? (const uint32_t *)~(uintptr_t)0 : (const uint32_t *)arena.put(ktab.data(), ktab.size() * 4);
             c.ktoff = flat ? (const int32_t *)~(uintptr_t)0 : (const int32_t *)arena.put(ktoff.data(), ktoff.size() * 4);
             c.H = ti.H; c.W = ti.W; c.Cin_p = cin_p; c.Ho = to.H; c.Wo = to.W; c.Cout_p = cout_p;
@@ -497,7 +499,7 @@ int isr_load_model(const void *blob_host, size_t bytes, isr_model **out) {
         if (d.type == OP_CONV) {
             rebase(d.conv.w, m->dconst); rebase(d.conv.bias, m->dconst); rebase(d.conv.m0x2, m->dconst);
             rebase(d.conv.rnd_lo, m->dconst); rebase(d.conv.rnd_hi, m->dconst); rebase(d.conv.shift, m->dconst);
-            rebase(d.conv.ktab, m->dconst); rebase(d.conv.ktoff, m->dconst);
+            rebase(d.conv.ktab, m->dconst); rebase(d.conv.ktoff, m->dconst); rebase(d.conv.zpad, m->dconst);
             rebase(d.conv.m0s, m->dconst); rebase(d.conv.chi, m->dconst); rebase(d.conv.shm1, m->dconst);
         } else if (d.type == OP_FC) {
             rebase(d.fc.w, m->dconst); rebase(d.fc.bias, m->dconst);

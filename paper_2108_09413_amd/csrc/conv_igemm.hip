@@ -10,12 +10,20 @@
 // Epilogue: q = clamp(z_out + RHA(acc * M0, 31 + shift), relu ? z_out : -128, 127),
 // one rounding, half away from zero, written as int8 NHWC.
 //
-// Tile: 256 threads = 4 waves; a BM x BN block of the output, K consumed in steps
-// of KB bytes staged through LDS with register prefetch.  KB = 64: two LDS
-// buffers, one barrier per step.  KB = 128: every activation row read is a full
-// 128-byte line (64-byte row segments only reach about half of the L1 rate on
-// this chip), one LDS buffer, two barriers per step.
-// MT = 32 uses v_mfma_i32_32x32x32_i8, MT = 16 uses v_mfma_i32_16x16x64_i8.
+// Two kernels share the arithmetic:
+//  * conv_dma_kernel (layers with at least 64 output channels and the single-multiply
+//    epilogue): a workgroup of BM/64 x BN/64 waves, each wave a 64 x 64 output block of
+//    2 x 2 v_mfma_i32_32x32x32_i8 tiles.  K is consumed in steps of KB bytes; the
+//    operand tiles of a step go from global memory straight into LDS
+//    (global_load_lds_dwordx4, no staging registers) NST steps deep, tracked by hand
+//    with s_waitcnt vmcnt and one s_barrier per step.  Large tiles cut the bytes that
+//    cross the L1 per multiply, which is what bounds the K loop on this chip.
+//  * conv_igemm_kernel (few output channels, the RGB stem, the two-multiply epilogue):
+//    256 threads, operands staged through registers into LDS.  KB = 64: two LDS
+//    buffers, one barrier per step.  KB = 128: one buffer, two barriers per step.
+//    MT = 32 uses v_mfma_i32_32x32x32_i8, MT = 16 uses v_mfma_i32_16x16x64_i8.
+#include <cstdlib>
+
 #include "isr_internal.h"
 
 namespace isr {
@@ -357,41 +365,319 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
     }
 }
 
+
+// ---- direct-to-LDS kernel ---------------------------------------------------
+
+// 16 bytes per lane from global memory into LDS: lane l of the wave writes bytes
+// [16 l, 16 l + 16) after the wave-uniform LDS address `lptr`.
+#define ISR_GLOBAL_TO_LDS16(gptr, lptr)                                                             \
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gptr),        \
+                                     (__attribute__((address_space(3))) void *)(lptr), 16, 0, 0)
+
+// The compiler does not order LDS reads after loads that write LDS; this wait does.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+template <int BM, int BN, int KB, int NST, bool FUSE, int MINB>
+__global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_kernel(const ConvParams p) {
+    constexpr int MT = 32;
+    constexpr int WGM = BM / 64, WGN = BN / 64, NT = WGM * WGN * 64;
+    constexpr int FM = 2, FN = 2;
+    constexpr int CPR = KB / 16;             // 16-byte chunks per tile row
+    constexpr int RPP = NT / CPR;            // rows covered by one pass of all threads
+    constexpr int NA = BM / RPP, NB = BN / RPP;
+    constexpr int L = NA + NB;               // loads per lane per step
+    constexpr int ACC = 16;
+    constexpr int STAGE = (BM + BN) * KB;
+    constexpr int KS = KB / 32;
+    static_assert(BM % 64 == 0 && BN % 64 == 0 && BM % RPP == 0 && BN % RPP == 0 && RPP % 32 == 0 && NST >= 2 &&
+                      NST <= 3 && (KB == 64 || KB == 128),
+                  "tile shape");
+
+    __shared__ __attribute__((aligned(16))) int8_t Ls[NST][STAGE];   // per step: A rows, then B rows
+    __shared__ uint32_t ktg_s[512];   // per 16-byte K chunk: ky | kx << 8 | channel byte offset << 16; ~0 = padding
+    __shared__ __attribute__((aligned(16))) int prm_s[4][BM];   // bias, M0, chi, shift-1 of this M tile
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WGM, wn = wave / WGM;
+    // same XCD-aware tile order as conv_igemm_kernel
+    const int nblk = gridDim.x, mt = (p.Cout_p + BM - 1) / BM;
+    const int xcd = blockIdx.x & 7, per = nblk >> 3, extra = nblk & 7;
+    const int logical = xcd * per + (xcd < extra ? xcd : extra) + (blockIdx.x >> 3);
+    const int m0 = (logical % mt) * BM;
+    const long n0 = (long)(logical / mt) * BN;
+    const int nk = p.Kp / KB;
+    const bool flat = p.ktab == nullptr;
+    const int col = tid % CPR, row0 = tid / CPR;
+    // LDS position (row, col) holds K chunk col ^ swz(row); RPP is a multiple of 32, so
+    // the chunk a lane fetches is the same for all of its rows
+    const int cl = col ^ swz<CPR>(row0);
+
+    if (!flat)
+        for (int i = tid; i < nk * CPR; i += NT) {
+            const uint32_t g = p.ktab[i];
+            const int chan = p.ktoff[i] - (int)((g & 0xFF) * p.W + ((g >> 8) & 0xFF)) * p.Cin_p;
+            ktg_s[i] = g == 0xFFFFFFFFu ? g : (g | ((uint32_t)chan << 16));
+        }
+    for (int i = tid; i < BM; i += NT) {
+        const bool in = m0 + i < p.Mp;
+        prm_s[0][i] = in ? p.bias[m0 + i] : 0;
+        prm_s[1][i] = in ? p.m0s[m0 + i] : 0;
+        prm_s[2][i] = in ? p.chi[m0 + i] : 0;
+        prm_s[3][i] = in ? p.shm1[m0 + i] : 1;
+    }
+
+    int pixoff[NB];
+    int iy0[NB], ix0[NB];
+    bool rvalid[NB];
+    const int HoWo = p.Ho * p.Wo;
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        long n = n0 + row0 + RPP * j;
+        rvalid[j] = n < p.npix;
+        if (flat) {
+            // rows past the end re-read the last pixel; their results are never stored
+            pixoff[j] = (int)((rvalid[j] ? n : (long)p.npix - 1) * p.Cin_p) + cl * 16;
+            iy0[j] = ix0[j] = 0;
+        } else {
+            int nn = rvalid[j] ? (int)n : 0;
+            int b = nn / HoWo;
+            int rem = nn - b * HoWo;
+            int oy = rem / p.Wo, ox = rem - oy * p.Wo;
+            iy0[j] = oy * p.stride - p.pad;
+            ix0[j] = ox * p.stride - p.pad;
+            pixoff[j] = ((b * p.H + iy0[j]) * p.W + ix0[j]) * p.Cin_p;
+        }
+    }
+    // weight rows past Mp (tile taller than the padded matrix) re-read row 0; never stored
+    const int8_t *wrow[NA];
+#pragma unroll
+    for (int j = 0; j < NA; ++j) {
+        int r = m0 + row0 + RPP * j;
+        wrow[j] = p.w + (long)(r < p.Mp ? r : 0) * p.Kp + cl * 16;
+    }
+
+    // Enqueues the loads of K step ks into LDS buffer `buf`: L per lane.  A pass of all
+    // threads fills NT * 16 contiguous bytes, a wave 1 KiB of it.  Out-of-image taps read
+    // the 16 zero-point bytes at p.zpad, so they contribute 0 like everywhere else.
+    auto issue = [&](int ks, int buf) {
+        int8_t *sa = &Ls[buf][wave * 1024];
+#pragma unroll
+        for (int j = 0; j < NA; ++j) ISR_GLOBAL_TO_LDS16(wrow[j] + (long)ks * KB, sa + j * (NT * 16));
+        int8_t *sb = sa + BM * KB;
+        if (flat) {
+#pragma unroll
+            for (int j = 0; j < NB; ++j) ISR_GLOBAL_TO_LDS16(p.in + (uint32_t)(pixoff[j] + ks * KB), sb + j * (NT * 16));
+        } else {
+            const uint32_t g = ktg_s[ks * CPR + cl];
+            const int ky = g & 0xFF, kx = (g >> 8) & 0xFF;
+            const int toff = (ky * p.W + kx) * p.Cin_p + (int)(g >> 16);
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                int iy = iy0[j] + ky, ix = ix0[j] + kx;
+                const bool ok = (int)rvalid[j] & (int)(g != 0xFFFFFFFFu) & (int)((unsigned)iy < (unsigned)p.H) &
+                                (int)((unsigned)ix < (unsigned)p.W);
+                const int8_t *real = p.in + (uint32_t)(pixoff[j] + toff);
+                const int8_t *src = ok ? real : p.zpad;
+                ISR_GLOBAL_TO_LDS16(src, sb + j * (NT * 16));
+            }
+        }
+    };
+
+    typedef int acc_t __attribute__((ext_vector_type(ACC)));
+    acc_t acc[FM][FN];
+    auto lane_oc = [&](int fm) { return wm * 64 + fm * MT + 16 * (lane >> 5); };
+
+    // residual operand of a fused add: fetched up front, consumed in the epilogue
+    int rres[FUSE ? FM : 1][FUSE ? FN : 1][ACC / 4];
+    if constexpr (FUSE) {
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+            for (int fn = 0; fn < FN; ++fn) {
+                long n = n0 + wn * 64 + fn * MT + (lane & (MT - 1));
+                if (n >= p.npix) n = p.npix - 1;
+                int occ = m0 + lane_oc(fm);
+                if (occ >= p.Cout_p) occ = 0;
+                v4i rv = *(const v4i *)(p.res + n * p.Cout_p + occ);
+#pragma unroll
+                for (int d = 0; d < 4; ++d) rres[fm][fn][d] = rv[d];
+            }
+    }
+
+    __syncthreads();   // ktg_s, prm_s visible
+#pragma unroll
+    for (int fm = 0; fm < FM; ++fm) {
+        acc_t init;
+#pragma unroll
+        for (int i = 0; i < ACC; ++i) init[i] = prm_s[0][lane_oc(fm) + i];
+#pragma unroll
+        for (int fn = 0; fn < FN; ++fn) acc[fm][fn] = init;
+    }
+#pragma unroll
+    for (int s = 0; s < NST - 1; ++s)
+        if (s < nk) issue(s, s);
+
+    // per-lane fragment offsets inside a step's buffer
+    int aoff[KS][FM], boff[KS][FN];
+#pragma unroll
+    for (int ksub = 0; ksub < KS; ++ksub) {
+        const int c = ksub * 2 + (lane >> 5);
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm) {
+            int r = wm * 64 + fm * 32 + (lane & 31);
+            aoff[ksub][fm] = r * KB + ((c ^ swz<CPR>(r)) << 4);
+        }
+#pragma unroll
+        for (int fn = 0; fn < FN; ++fn) {
+            int r = wn * 64 + fn * 32 + (lane & 31);
+            boff[ksub][fn] = BM * KB + r * KB + ((c ^ swz<CPR>(r)) << 4);
+        }
+    }
+
+    int cur = 0, fill = NST - 1;   // buffer computed on now / buffer filled next
+    for (int ks = 0; ks < nk; ++ks) {
+        // This wave's loads of step ks have landed once at most the loads of the steps
+        // after it (min(nk - 1 - ks, NST - 2) of them, L each) are still in flight.
+        if (NST == 3 && ks + 1 < nk) wait_vmcnt<L>();
+        else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();   // every wave's loads of step ks landed; every wave is done with step ks - 1
+        if (ks + NST - 1 < nk) issue(ks + NST - 1, fill);
+        const int8_t *base = Ls[cur];
+#pragma unroll
+        for (int ksub = 0; ksub < KS; ++ksub) {
+            v4i fa[FM], fb[FN];
+#pragma unroll
+            for (int fm = 0; fm < FM; ++fm) fa[fm] = *(const v4i *)(base + aoff[ksub][fm]);
+#pragma unroll
+            for (int fn = 0; fn < FN; ++fn) fb[fn] = *(const v4i *)(base + boff[ksub][fn]);
+#pragma unroll
+            for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+                for (int fn = 0; fn < FN; ++fn)
+                    acc[fm][fn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[fm], fb[fn], acc[fm][fn], 0, 0, 0);
+        }
+        cur = cur + 1 == NST ? 0 : cur + 1;
+        fill = fill + 1 == NST ? 0 : fill + 1;
+    }
+
+    // epilogue: requantise, clamp, optional residual add, pack, store (NHWC)
+    const int lo = p.relu ? p.zp_out : -128;
+#pragma unroll
+    for (int fm = 0; fm < FM; ++fm) {
+        const int oc = m0 + lane_oc(fm);
+        if (oc >= p.Cout_p) continue;
+        int mm[ACC], ch[ACC], ss[ACC];
+#pragma unroll
+        for (int i = 0; i < ACC; ++i) {
+            mm[i] = prm_s[1][oc - m0 + i]; ch[i] = prm_s[2][oc - m0 + i]; ss[i] = prm_s[3][oc - m0 + i];
+        }
+#pragma unroll
+        for (int fn = 0; fn < FN; ++fn) {
+            long n = n0 + wn * 64 + fn * MT + (lane & (MT - 1));
+            if (n >= p.npix) continue;
+            int q[ACC];
+#pragma unroll
+            for (int i = 0; i < ACC; ++i) q[i] = clamp3(requant_fast(acc[fm][fn][i], mm[i], ch[i], ss[i]), lo, 127);
+            if constexpr (FUSE) {
+#pragma unroll
+                for (int i = 0; i < ACC; ++i) {
+                    int r8 = (int)(int8_t)((uint32_t)rres[fm][fn][i >> 2] >> (8 * (i & 3)));
+                    // 24-bit multiplies (full rate): |q|, |r8| < 2^8 and |multipliers| < 2^23
+                    int v = __mul24(q[i], p.add_mul_self) + p.add_c0 + __mul24(r8, p.add_mul_res);
+                    q[i] = clamp3((v + p.add_k + (v >> 31)) >> p.add_sh, p.add_lo, 127);
+                }
+            }
+            int8_t *dst = p.out + n * p.Cout_p + oc;
+            v4i v = {(int)pack4(q[0], q[1], q[2], q[3]), (int)pack4(q[4], q[5], q[6], q[7]),
+                     (int)pack4(q[8], q[9], q[10], q[11]), (int)pack4(q[12], q[13], q[14], q[15])};
+            *(v4i *)dst = v;
+        }
+    }
+}
+
 int conv_tile_m(int cout_p) { return cout_p <= 16 ? 16 : (cout_p <= 32 ? 32 : (cout_p <= 64 ? 64 : 128)); }
 
-template <int MT, int BM, int BN, int WGM, int MINW, int MINW_FUSED, int KB>
-static hipError_t launch_kb(const ConvParams &p, hipStream_t st) {
+template <int MT, int BM, int BN, int WGM, int MINW, int MINW_FUSED>
+static hipError_t launch_staged(const ConvParams &p, hipStream_t st) {
     dim3 grid((unsigned)(((p.npix + BN - 1) / BN) * ((p.Cout_p + BM - 1) / BM)));
-    if (p.fuse_add && !p.fast_requant) return hipErrorInvalidValue;
+    if (p.kb != 64 || (p.fuse_add && !p.fast_requant)) return hipErrorInvalidValue;
     if (p.fuse_add)
-        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, true, MINW_FUSED, true, KB>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, true, MINW_FUSED, true, 64>), grid, dim3(256), 0, st, p);
     else if (p.fast_requant)
-        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, true, MINW, false, KB>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, true, MINW, false, 64>), grid, dim3(256), 0, st, p);
     else
         hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, false, 2, false, 64>), grid, dim3(256), 0, st, p);
     return hipGetLastError();
 }
 
-// K bytes per step for a layer whose unpadded depth is `kreal` bytes over `cin_p`
-// stored input channels: 128 where it measured faster (1x1 layers up to K = 512 and
-// layers with at least 512 input channels), needs no extra padding and the
-// single-multiply epilogue applies; else 64.
+template <int BM, int BN, int KB, int NST, int MINB>
+static hipError_t launch_dma(const ConvParams &p, hipStream_t st) {
+    constexpr int NT = (BM / 64) * (BN / 64) * 64;
+    dim3 grid((unsigned)(((p.npix + BN - 1) / BN) * ((p.Cout_p + BM - 1) / BM)));
+    if (p.fuse_add)
+        hipLaunchKernelGGL((conv_dma_kernel<BM, BN, KB, NST, true, MINB>), grid, dim3(NT), 0, st, p);
+    else
+        hipLaunchKernelGGL((conv_dma_kernel<BM, BN, KB, NST, false, MINB>), grid, dim3(NT), 0, st, p);
+    return hipGetLastError();
+}
+
+// The direct-to-LDS kernel serves layers with at least 64 stored output channels,
+// the single-multiply epilogue and 16-channel-aligned input (not the RGB stem).
+static bool dma_path(int cout_p, int fast_requant, int c4) { return fast_requant && !c4 && cout_p >= 64; }
+
+// K bytes per step for a layer whose unpadded depth is `kreal` bytes (cin_p == 0 marks
+// the RGB stem): 128 for deep layers of the direct-to-LDS kernel with at least 256
+// output channels, where two 128-byte steps in flight measured faster than three
+// 64-byte ones and no extra K padding is needed; else 64.
 int conv_k_step(int kreal, int cin_p, int cout_p, int fast_requant) {
-    const bool one_by_one = kreal == cin_p;
-    const bool wanted = (one_by_one && kreal <= 512) || (!one_by_one && cin_p >= 512);
-    return (fast_requant && cout_p > 32 && kreal % 128 == 0 && wanted) ? 128 : 64;
+    return (dma_path(cout_p, fast_requant, cin_p == 0) && cout_p >= 256 && kreal % 128 == 0 && kreal >= 1024) ? 128 : 64;
+}
+
+// Output tile of the direct-to-LDS kernel for this launch.  Larger tiles move fewer
+// bytes per multiply but leave CUs idle when the layer has few tiles, and the
+// epilogue of a shallow (small K) layer hides better behind several small workgroups.
+enum DmaTile { T64x256, T128x128, T128x256, T256x128, T256x256 };
+
+static long tiles_of(const ConvParams &p, int bm, int bn) {
+    return ((long)(p.npix + bn - 1) / bn) * ((p.Cout_p + bm - 1) / bm);
+}
+
+static DmaTile pick_tile(const ConvParams &p) {
+    static const int forced = [] { const char *e = getenv("ISR_CONV_TILE"); return e ? atoi(e) : -1; }();
+    if (p.Cout_p <= 64) return T64x256;
+    if (forced >= T128x128 && forced <= T256x256 && !(p.Cout_p <= 128 && (forced == T256x128 || forced == T256x256)))
+        return (DmaTile)forced;
+    constexpr long CUS = 256;
+    if (p.Cout_p <= 128) return tiles_of(p, 128, 256) >= 2 * CUS ? T128x256 : T128x128;
+    if (p.Kp < 1024) return T128x128;
+    if (tiles_of(p, 256, 256) >= CUS - CUS / 8) return T256x256;
+    if (tiles_of(p, 256, 128) >= CUS) return T256x128;
+    return T128x128;
 }
 
 hipError_t launch_conv(const ConvParams &p, hipStream_t st) {
     if (p.npix <= 0) return hipSuccess;
     if ((p.kb != 64 && p.kb != 128) || p.Kp % p.kb != 0 || p.Kp > 8192 || p.Cout_p % 16 != 0 || p.Mp % 128 != 0 ||
-        p.Mp < p.Cout_p || (p.kb == 128 && (!p.fast_requant || p.Cout_p <= 32)))
+        p.Mp < p.Cout_p)
         return hipErrorInvalidValue;
+    if (dma_path(p.Cout_p, p.fast_requant, p.c4)) {
+        if (!p.zpad) return hipErrorInvalidValue;
+        const bool k128 = p.kb == 128;
+        switch (pick_tile(p)) {
+        case T64x256: return k128 ? hipErrorInvalidValue : launch_dma<64, 256, 64, 3, 2>(p, st);
+        case T128x128: return k128 ? launch_dma<128, 128, 128, 2, 2>(p, st) : launch_dma<128, 128, 64, 3, 3>(p, st);
+        case T128x256: return k128 ? launch_dma<128, 256, 128, 2, 1>(p, st) : launch_dma<128, 256, 64, 3, 2>(p, st);
+        case T256x128: return k128 ? launch_dma<256, 128, 128, 2, 1>(p, st) : launch_dma<256, 128, 64, 3, 2>(p, st);
+        case T256x256: return k128 ? launch_dma<256, 256, 128, 2, 1>(p, st) : launch_dma<256, 256, 64, 3, 1>(p, st);
+        }
+        return hipErrorInvalidValue;
+    }
     switch (conv_tile_m(p.Cout_p)) {
-    case 16: return launch_kb<16, 16, 256, 1, 4, 4, 64>(p, st);
-    case 32: return launch_kb<32, 32, 256, 1, 3, 3, 64>(p, st);
-    case 64: return p.kb == 128 ? launch_kb<32, 64, 256, 1, 2, 2, 128>(p, st) : launch_kb<32, 64, 256, 1, 3, 3, 64>(p, st);
-    default: return p.kb == 128 ? launch_kb<32, 128, 128, 2, 3, 3, 128>(p, st) : launch_kb<32, 128, 128, 2, 4, 3, 64>(p, st);
+    case 16: return launch_staged<16, 16, 256, 1, 4, 4>(p, st);
+    case 32: return launch_staged<32, 32, 256, 1, 3, 3>(p, st);
+    case 64: return launch_staged<32, 64, 256, 1, 3, 3>(p, st);
+    default: return launch_staged<32, 128, 128, 2, 4, 3>(p, st);
     }
 }
 

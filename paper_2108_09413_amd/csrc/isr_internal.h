@@ -76,6 +76,7 @@ struct ConvParams {
     int32_t fuse_add, add_mul_self, add_mul_res, add_c0, add_k, add_sh, add_lo;
     const uint32_t *ktab;    // [Kp/16] per 16-byte K chunk: ky | kx<<8, 0xFFFFFFFF = padding chunk; null = plain GEMM
     const int32_t *ktoff;    // [Kp/16] byte offset (ky*W + kx)*Cin_p + channel of the chunk
+    const int8_t *zpad;      // 16 bytes of z_in: source of out-of-image taps for loads that go straight to LDS
     int32_t H, W, Cin_p, Ho, Wo, Cout_p;
     int32_t stride, pad, Kp, Mp;
     int32_t kb;              // K bytes per step of the kernel (64 or 128); Kp is a multiple of it
