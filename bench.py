@@ -28,7 +28,8 @@ HBM_PEAK_GBS = 8000.0
 
 WORKLOADS = {
     # name: (config number, default chunk, oracle samples for the CPU baseline)
-    "resnet50": (4, 256, 16),
+    # 668 samples x 14x14 pixels = 512 output tiles of 256 pixels: the deep layers fill the 256 CUs twice
+    "resnet50": (4, 668, 16),
     "resnet20": (1, 8192, 2048),
     "resnet110": (2, 4096, 512),
     "tiny": (0, 1024, 1100),

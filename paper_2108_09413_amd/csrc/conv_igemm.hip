@@ -635,25 +635,32 @@ int conv_k_step(int kreal, int cin_p, int cout_p, int fast_requant) {
 }
 
 // Output tile of the direct-to-LDS kernel for this launch.  Larger tiles move fewer
-// bytes per multiply but leave CUs idle when the layer has few tiles, and the
-// epilogue of a shallow (small K) layer hides better behind several small workgroups.
+// bytes per multiply, so their K loop runs faster, but a layer with few tiles then
+// leaves CUs idle or pays for a mostly empty last round; the epilogue of a shallow
+// (small K) layer hides better behind several small workgroups.
 enum DmaTile { T64x256, T128x128, T128x256, T256x128, T256x256 };
-
-static long tiles_of(const ConvParams &p, int bm, int bn) {
-    return ((long)(p.npix + bn - 1) / bn) * ((p.Cout_p + bm - 1) / bm);
-}
 
 static DmaTile pick_tile(const ConvParams &p) {
     static const int forced = [] { const char *e = getenv("ISR_CONV_TILE"); return e ? atoi(e) : -1; }();
     if (p.Cout_p <= 64) return T64x256;
     if (forced >= T128x128 && forced <= T256x256 && !(p.Cout_p <= 128 && (forced == T256x128 || forced == T256x256)))
         return (DmaTile)forced;
+    if (p.Cout_p > 128 && p.Kp < 1024) return T128x128;
+    // cost of a candidate: workgroups per CU (rounded up: the last round costs a full
+    // one) x tile area / relative K-loop throughput of the tile, as measured
+    struct Cand { DmaTile t; int bm, bn; double rate64, rate128; };
+    static const Cand cands[] = {{T128x128, 128, 128, 1.00, 1.00}, {T128x256, 128, 256, 1.12, 1.15},
+                                 {T256x128, 256, 128, 1.12, 1.15}, {T256x256, 256, 256, 1.20, 1.35}};
     constexpr long CUS = 256;
-    if (p.Cout_p <= 128) return tiles_of(p, 128, 256) >= 2 * CUS ? T128x256 : T128x128;
-    if (p.Kp < 1024) return T128x128;
-    if (tiles_of(p, 256, 256) >= CUS - CUS / 8) return T256x256;
-    if (tiles_of(p, 256, 128) >= CUS) return T256x128;
-    return T128x128;
+    DmaTile best = T128x128;
+    double best_cost = 0;
+    for (const Cand &c : cands) {
+        if (c.bm > 128 && p.Cout_p <= 128) continue;
+        const long wgs = ((long)(p.npix + c.bn - 1) / c.bn) * ((p.Cout_p + c.bm - 1) / c.bm);
+        const double cost = (double)((wgs + CUS - 1) / CUS) * c.bm * c.bn / (p.kb == 128 ? c.rate128 : c.rate64);
+        if (best_cost == 0 || cost < best_cost) { best_cost = cost; best = c.t; }
+    }
+    return best;
 }
 
 hipError_t launch_conv(const ConvParams &p, hipStream_t st) {
