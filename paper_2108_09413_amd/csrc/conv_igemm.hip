@@ -397,6 +397,13 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
     __shared__ __attribute__((aligned(16))) int8_t Ls[NST][STAGE];   // per step: A rows, then B rows
     __shared__ uint32_t ktg_s[512];   // per 16-byte K chunk: ky | kx << 8 | channel byte offset << 16; ~0 = padding
     __shared__ __attribute__((aligned(16))) int prm_s[4][BM];   // bias, M0, chi, shift-1 of this M tile
+    // A fused residual add (two-buffer variant only) fetches the residual tile as whole pixel
+    // rows, [pixel][BM channels] with the 16-byte chunks XOR-swizzled per pixel, into the
+    // operand buffer that is idle during the last K step.
+    constexpr int RCH = BM / 16;                    // chunks per pixel row
+    constexpr int RPB = BM >= 256 ? 1 : 256 / BM;   // pixel rows per 256 bytes (one pass over the 64 banks)
+    static_assert(!FUSE || (NST == 2 && STAGE >= BM * BN && BM * BN / 16 % NT == 0), "residual tile fits a buffer");
+    auto rswz = [](int pixel) { return (pixel / RPB) & (RCH - 1); };
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % WGM, wn = wave / WGM;
@@ -488,22 +495,19 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
     acc_t acc[FM][FN];
     auto lane_oc = [&](int fm) { return wm * 64 + fm * MT + 16 * (lane >> 5); };
 
-    // residual operand of a fused add: fetched up front, consumed in the epilogue
-    int rres[FUSE ? FM : 1][FUSE ? FN : 1][ACC / 4];
-    if constexpr (FUSE) {
+    auto issue_residual = [&](int buf) {
 #pragma unroll
-        for (int fm = 0; fm < FM; ++fm)
-#pragma unroll
-            for (int fn = 0; fn < FN; ++fn) {
-                long n = n0 + wn * 64 + fn * MT + (lane & (MT - 1));
-                if (n >= p.npix) n = p.npix - 1;
-                int occ = m0 + lane_oc(fm);
-                if (occ >= p.Cout_p) occ = 0;
-                v4i rv = *(const v4i *)(p.res + n * p.Cout_p + occ);
-#pragma unroll
-                for (int d = 0; d < 4; ++d) rres[fm][fn][d] = rv[d];
-            }
-    }
+        for (int j = 0; j < BM * BN / 16 / NT; ++j) {
+            const int c = j * NT + tid, pixel = c / RCH, chunk = (c % RCH) ^ rswz(pixel);
+            long n = n0 + pixel;
+            if (n >= p.npix) n = p.npix - 1;
+            int oc = m0 + chunk * 16;
+            if (oc >= p.Cout_p) oc = 0;
+            ISR_GLOBAL_TO_LDS16(p.res + n * p.Cout_p + oc, &Ls[buf][(j * NT + wave * 64) * 16]);
+        }
+    };
+    if constexpr (FUSE)
+        if (nk == 1) issue_residual(1);   // the second buffer is never used by a K step
 
     __syncthreads();   // ktg_s, prm_s visible
 #pragma unroll
@@ -543,6 +547,7 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
         else wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();   // every wave's loads of step ks landed; every wave is done with step ks - 1
         if (ks + NST - 1 < nk) issue(ks + NST - 1, fill);
+        else if (FUSE && ks + 1 == nk && nk > 1) issue_residual(fill);
         const int8_t *base = Ls[cur];
 #pragma unroll
         for (int ksub = 0; ksub < KS; ++ksub) {
@@ -562,6 +567,12 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
     }
 
     // epilogue: requantise, clamp, optional residual add, pack, store (NHWC)
+    const int8_t *resbuf = nullptr;
+    if constexpr (FUSE) {
+        wait_vmcnt<0>();
+        __syncthreads();   // the residual tile is in LDS
+        resbuf = Ls[nk == 1 ? 1 : (nk & 1)];   // the buffer that held step nk - 2
+    }
     const int lo = p.relu ? p.zp_out : -128;
 #pragma unroll
     for (int fm = 0; fm < FM; ++fm) {
@@ -580,9 +591,11 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
 #pragma unroll
             for (int i = 0; i < ACC; ++i) q[i] = clamp3(requant_fast(acc[fm][fn][i], mm[i], ch[i], ss[i]), lo, 127);
             if constexpr (FUSE) {
+                const int pixel = wn * 64 + fn * MT + (lane & (MT - 1));
+                const v4i rv = *(const v4i *)(resbuf + (pixel * RCH + ((lane_oc(fm) >> 4) ^ rswz(pixel))) * 16);
 #pragma unroll
                 for (int i = 0; i < ACC; ++i) {
-                    int r8 = (int)(int8_t)((uint32_t)rres[fm][fn][i >> 2] >> (8 * (i & 3)));
+                    int r8 = (int)(int8_t)((uint32_t)rv[i >> 2] >> (8 * (i & 3)));
                     // 24-bit multiplies (full rate): |q|, |r8| < 2^8 and |multipliers| < 2^23
                     int v = __mul24(q[i], p.add_mul_self) + p.add_c0 + __mul24(r8, p.add_mul_res);
                     q[i] = clamp3((v + p.add_k + (v >> 31)) >> p.add_sh, p.add_lo, 127);
@@ -615,10 +628,17 @@ template <int BM, int BN, int KB, int NST, int MINB>
 static hipError_t launch_dma(const ConvParams &p, hipStream_t st) {
     constexpr int NT = (BM / 64) * (BN / 64) * 64;
     dim3 grid((unsigned)(((p.npix + BN - 1) / BN) * ((p.Cout_p + BM - 1) / BM)));
-    if (p.fuse_add)
-        hipLaunchKernelGGL((conv_dma_kernel<BM, BN, KB, NST, true, MINB>), grid, dim3(NT), 0, st, p);
-    else
-        hipLaunchKernelGGL((conv_dma_kernel<BM, BN, KB, NST, false, MINB>), grid, dim3(NT), 0, st, p);
+    hipLaunchKernelGGL((conv_dma_kernel<BM, BN, KB, NST, false, MINB>), grid, dim3(NT), 0, st, p);
+    return hipGetLastError();
+}
+
+// With a fused residual add: 64-byte K steps in two buffers (any Kp is a multiple of 64),
+// the second of which also receives the residual tile; small tiles, 3-4 workgroups per CU.
+template <int BM, int BN, int MINB>
+static hipError_t launch_dma_fused(const ConvParams &p, hipStream_t st) {
+    constexpr int NT = (BM / 64) * (BN / 64) * 64;
+    dim3 grid((unsigned)(((p.npix + BN - 1) / BN) * ((p.Cout_p + BM - 1) / BM)));
+    hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 2, true, MINB>), grid, dim3(NT), 0, st, p);
     return hipGetLastError();
 }
 
@@ -671,9 +691,14 @@ hipError_t launch_conv(const ConvParams &p, hipStream_t st) {
     if (dma_path(p.Cout_p, p.fast_requant, p.c4)) {
         if (!p.zpad) return hipErrorInvalidValue;
         const bool k128 = p.kb == 128;
+        if (p.fuse_add) return p.Cout_p <= 64 ? launch_dma_fused<64, 256, 3>(p, st) : launch_dma_fused<128, 128, 4>(p, st);
         switch (pick_tile(p)) {
         case T64x256: return k128 ? hipErrorInvalidValue : launch_dma<64, 256, 64, 3, 2>(p, st);
-        case T128x128: return k128 ? launch_dma<128, 128, 128, 2, 2>(p, st) : launch_dma<128, 128, 64, 3, 3>(p, st);
+        case T128x128:
+            // shallow layers are epilogue-bound: two steps in flight suffice and a fourth
+            // workgroup per CU hides more of the epilogue's memory latency
+            if (!p.fuse_add && p.Kp < 1024 && !k128) return launch_dma<128, 128, 64, 2, 4>(p, st);
+            return k128 ? launch_dma<128, 128, 128, 2, 2>(p, st) : launch_dma<128, 128, 64, 3, 3>(p, st);
         case T128x256: return k128 ? launch_dma<128, 256, 128, 2, 1>(p, st) : launch_dma<128, 256, 64, 3, 2>(p, st);
         case T256x128: return k128 ? launch_dma<256, 128, 128, 2, 1>(p, st) : launch_dma<256, 128, 64, 3, 2>(p, st);
         case T256x256: return k128 ? launch_dma<256, 256, 128, 2, 1>(p, st) : launch_dma<256, 256, 64, 3, 1>(p, st);
