@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 WORKLOADS = {
     # name: (config number, default chunk, oracle samples for the CPU baseline)
     # 668 samples x 14x14 pixels = 512 output tiles of 256 pixels: the deep layers fill the 256 CUs twice
-    "resnet50": (4, 668, 16),
+    "resnet50": (4, 668, 48),
     "resnet20": (1, 8192, 2048),
     "resnet110": (2, 4096, 512),
     "tiny": (0, 1024, 1100),
@@ -83,11 +83,14 @@ def main():
         return isr.isr_certify(model, images[i], s, n0, n, alpha, seed=0, image_id=i + 1, want_counts=False)[0]
 
     if args.copy_calibration_mib:
-        src = torch.zeros(args.copy_calibration_mib << 20, dtype=torch.uint8, device="cuda")
+        # random (non-zero) source far larger than the caches, evicted from them by a second buffer first
+        src = torch.empty(args.copy_calibration_mib << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
         dst = torch.empty_like(src)
+        flush = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 255)
+        torch.cuda.synchronize()
         dst.copy_(src)
         torch.cuda.synchronize()
-        del src, dst
+        del src, dst, flush
     for k in range(args.warmup):
         step(k)
     isr.isr_profile(model, args.profile_every)
@@ -106,11 +109,11 @@ def main():
     conv_ops = sum(s["alg_ops"] for s in conv)
     conv_launches = sum(s["launches"] for s in conv)
     all_ms = sum(s["total_ms"] for s in stats)
-    roofline = None
+    roofline = roofline_hbm = None
     if conv_ms > 0:
         achieved = conv_ops / (conv_ms * 1e-3) / 1e12
         roofline = {
-            "bound": "mfma", "kernel": "conv_igemm_kernel (all tile variants)",
+            "bound": "mfma", "kernel": "conv_dma_kernel + conv_igemm_kernel (all tile variants)",
             "achieved": round(achieved, 2), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
             "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4), "traffic": None,
             "launches_timed": conv_launches,
@@ -134,8 +137,13 @@ def main():
             mt = re.search(r"conv_hbm_bytes_per_inference: fetch=(\d+) write=(\d+)", txt)
             launches_per_inference = conv_launches / max(sum(s["launches"] for s in stats if s["name"] == "noise"), 1) / chunk
             roofline["traffic"] = round((int(mt.group(1)) + int(mt.group(2))) / launches_per_inference)
-            roofline["traffic_note"] = "HBM bytes per conv launch: rocprofv3 FETCH_SIZE+WRITE_SIZE per inference x inferences per launch"
+            roofline["traffic_note"] = ("HBM bytes per conv launch: rocprofv3 FETCH_SIZE+WRITE_SIZE per inference "
+                                        "(scaled by the copy calibration) x inferences per launch")
             roofline["alg_bytes_per_launch"] = round(sum(s["alg_bytes"] for s in conv) / max(conv_launches, 1))
+            hbm_gbs = roofline["traffic"] * conv_launches / (conv_ms * 1e-3) / 1e9
+            roofline_hbm = {"bound": "hbm", "kernel": roofline["kernel"], "achieved": round(hbm_gbs, 1),
+                            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(hbm_gbs / HBM_PEAK_GBS, 4),
+                            "traffic": roofline["traffic"]}
         except Exception:
             pass
 
@@ -166,6 +174,7 @@ def main():
         "whole_path_int8_tops": round(2.0 * macs * value / 1e12, 2),
         "whole_path_frac_of_int8_peak": round(2.0 * macs * value / 1e12 / INT8_MFMA_PEAK_TOPS, 4),
         "roofline": roofline,
+        "roofline_hbm": roofline_hbm,
         "cpu_baseline": cpu,
         "last_result": {"cls": results[-1].cls, "radius": results[-1].radius, "n_top": results[-1].n_top},
     }
