@@ -34,6 +34,7 @@ struct DevOp {
     int kclass = 0;
     double ops_per_sample = 0.0, bytes_per_sample = 0.0;   // algorithmic, for the timing report
     ConvParams conv{};
+    int stem_pool = 0;                  // conv fused with the max pooling after it (out = the pooled tensor)
     AddParams add{};
     PoolParams pool{};
     GapParams gap{};
@@ -186,6 +187,32 @@ void fuse_adds(const ParsedModel &pm, const std::vector<DevOp> &plain, std::vect
     }
 }
 
+// Folds the max pooling that follows the first convolution into it when the fused
+// kernel covers the geometry and the convolution output has no other reader.
+void fuse_stem_pool(const ParsedModel &pm, std::vector<DevOp> &ops) {
+    std::vector<int> uses(pm.tensors.size(), 0);
+    for (const DevOp &d : ops) {
+        if (d.a >= 0) uses[d.a]++;
+        if (d.b >= 0) uses[d.b]++;
+    }
+    for (size_t i = 0; i + 1 < ops.size(); ++i) {
+        DevOp &c = ops[i];
+        const DevOp &q = ops[i + 1];
+        if (c.type != OP_CONV || !c.conv.c4 || c.conv.fuse_add || q.type != OP_MAXPOOL || q.a != c.out || uses[c.out] != 1)
+            continue;
+        if (c.conv.Kp != 256) continue;   // K = 7 rows x 8 taps x 4 channels
+        if (!stem_pool_supported(c.conv.k, c.conv.stride, c.conv.pad, c.conv.Cout_p, c.conv.H, c.conv.W, c.conv.fast_requant,
+                                 q.pool.k, q.pool.stride, q.pool.pad))
+            continue;
+        c.stem_pool = 1;
+        c.bytes_per_sample = (double)pm.tensors[c.a].C * c.conv.H * c.conv.W +
+                             (double)pm.tensors[q.out].C * pm.tensors[q.out].H * pm.tensors[q.out].W;
+        c.out = q.out;
+        ops.erase(ops.begin() + i + 1);
+        return;
+    }
+}
+
 struct ConstArena {
     std::vector<uint8_t> host;
     size_t put(const void *src, size_t n) {
@@ -273,7 +300,7 @@ int build_device_ops(isr_model *m, ConstArena &arena) {
             c.ktab = flat ? (const uint32_t *)~(uintptr_t)0 : (const uint32_t *)arena.put(ktab.data(), ktab.size() * 4);
             c.ktoff = flat ? (const int32_t *)~(uintptr_t)0 : (const int32_t *)arena.put(ktoff.data(), ktoff.size() * 4);
             c.H = ti.H; c.W = ti.W; c.Cin_p = cin_p; c.Ho = to.H; c.Wo = to.W; c.Cout_p = cout_p;
-            c.stride = o.stride; c.pad = o.pad; c.Kp = Kp; c.Mp = Mp; c.kb = kb;
+            c.k = k; c.stride = o.stride; c.pad = o.pad; c.Kp = Kp; c.Mp = Mp; c.kb = kb;
             c.zp_in = ti.zp; c.zp_out = to.zp; c.relu = o.relu; c.c4 = c4 ? 1 : 0;
             int tm = conv_tile_m(cout_p);
             d.kclass = tm == 16 ? KC_CONV16 : tm == 32 ? KC_CONV32 : tm == 64 ? KC_CONV64 : KC_CONV128;
@@ -393,6 +420,17 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
                 ev_work.push_back({d.ops_per_sample * cnt, d.bytes_per_sample * cnt});
                 switch (d.type) {
                 case OP_CONV: {
+                    if (d.stem_pool) {
+                        const TensorDesc &to = pm.tensors[d.out];
+                        StemPoolParams sp;
+                        sp.in = (const int8_t *)(ws + pl.toff[d.a]);
+                        sp.out = (int8_t *)(ws + pl.toff[d.out]);
+                        sp.w = d.conv.w; sp.bias = d.conv.bias; sp.m0s = d.conv.m0s; sp.chi = d.conv.chi; sp.shm1 = d.conv.shm1;
+                        sp.H = d.conv.H; sp.W = d.conv.W; sp.Ho = d.conv.Ho; sp.Wo = d.conv.Wo; sp.Hp = to.H; sp.Wp = to.W;
+                        sp.zp_in = d.conv.zp_in; sp.zp_out = d.conv.zp_out; sp.relu = d.conv.relu; sp.B = (int32_t)cnt;
+                        HIP_TRY(launch_stem_pool(sp, m->stream));
+                        break;
+                    }
                     ConvParams c = d.conv;
                     c.in = (const int8_t *)(ws + pl.toff[d.a]);
                     c.out = (int8_t *)(ws + pl.toff[d.out]);
@@ -507,6 +545,7 @@ int isr_load_model(const void *blob_host, size_t bytes, isr_model **out) {
     }
     m->plan[0].ops = m->ops;
     fuse_adds(m->pm, m->ops, m->plan[1].ops);
+    fuse_stem_pool(m->pm, m->plan[1].ops);
     *out = m;
     return ISR_OK;
 }

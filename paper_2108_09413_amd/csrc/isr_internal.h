@@ -78,11 +78,22 @@ struct ConvParams {
     const int32_t *ktoff;    // [Kp/16] byte offset (ky*W + kx)*Cin_p + channel of the chunk
     const int8_t *zpad;      // 16 bytes of z_in: source of out-of-image taps for loads that go straight to LDS
     int32_t H, W, Cin_p, Ho, Wo, Cout_p;
-    int32_t stride, pad, Kp, Mp;
+    int32_t k, stride, pad, Kp, Mp;   // k: kernel size (k x k taps)
     int32_t kb;              // K bytes per step of the kernel (64 or 128); Kp is a multiple of it
     int32_t zp_in, zp_out, relu;
     int32_t npix;            // B * Ho * Wo
     int32_t c4;              // 1: input is NHWC4 and a K chunk is 4 horizontal taps
+};
+
+// First convolution (7x7 stride 2 pad 3 on the NHWC4 image, 64 stored output channels)
+// fused with the 3x3 stride-2 pad-1 max pooling that follows it.
+struct StemPoolParams {
+    const int8_t *in;        // [B][H][W][4] noisy image
+    int8_t *out;             // [B][Hp][Wp][64] pooled activations
+    const int8_t *w;         // [>= 64][256] rows in MFMA row order, K = (ky, kx padded to 8, channel padded to 4)
+    const int32_t *bias, *m0s, *chi, *shm1;   // as in ConvParams (single-multiply requantisation)
+    int32_t H, W, Ho, Wo, Hp, Wp;
+    int32_t zp_in, zp_out, relu, B;
 };
 
 struct AddParams {
@@ -126,6 +137,9 @@ struct NoiseParams {
 // Kernel launchers (kernels.hip / conv_igemm.hip).  All asynchronous on `st`.
 hipError_t launch_noise(const NoiseParams &p, hipStream_t st);
 hipError_t launch_conv(const ConvParams &p, hipStream_t st);
+hipError_t launch_stem_pool(const StemPoolParams &p, hipStream_t st);
+bool stem_pool_supported(int k, int stride, int pad, int cout_p, int H, int W, int fast_requant, int pool_k,
+                         int pool_stride, int pool_pad);
 hipError_t launch_add(const AddParams &p, hipStream_t st);
 hipError_t launch_maxpool(const PoolParams &p, hipStream_t st);
 hipError_t launch_gap(const GapParams &p, hipStream_t st);

@@ -126,6 +126,23 @@ def test_first_layer_7x7_stride2(isr):
     _check_all_tensors(isr, b.blob(), x, 32)
 
 
+@pytest.mark.parametrize("shape", [(224, 224), (64, 64), (37, 28), (30, 44), (9, 8)])
+def test_first_layer_fused_with_max_pooling(isr, shape):
+    """7x7/2 convolution into 64 channels followed by 3x3/2 max pooling (one fused kernel):
+    every tensor against the oracle, at the full 224 x 224 size, sizes with odd row
+    counts, ragged last bands and images narrower than one fragment row."""
+    h, w = shape
+    _say(f"layer parity fused stem + pool {h}x{w}")
+    b = NetBuilder(rng=np.random.default_rng(31), in_shape=(3, h, w), num_classes=5)
+    t0 = b.tensor(3, h, w, 0, 74.0)
+    t1 = b.conv(t0, 61, 7, 2, 3, True, zp_out=-100)
+    t2 = b.maxpool(t1, 3, 2, 1)
+    t3 = b.conv(t2, 64, 1, 1, 0, True)
+    b.fc(b.gap(t3), 5)
+    x = np.random.default_rng(7).integers(0, 256, size=(3, h, w)).astype(np.uint8)
+    _check_all_tensors(isr, b.blob(), x, 64, sample=3, chunk=5)
+
+
 # ---- S6-S8: logits, votes, decisions -----------------------------------------
 
 def test_config0_full_certify_and_predict(isr):
