@@ -1,6 +1,7 @@
 // C ABI: model loading, workspace planning and the Monte-Carlo driver that
 // enqueues noise -> layers -> vote kernels for chunks of sample indices.
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <new>
@@ -177,6 +178,15 @@ void fuse_adds(const ParsedModel &pm, const std::vector<DevOp> &plain, std::vect
                 c.conv.add_k = (int32_t)k;
                 c.conv.add_sh = a.sh;
                 c.conv.add_lo = a.relu ? a.zo : -128;
+                // v = q Ms + r Mr + c0 over all int8 pairs: is a negative exact half of 2^sh ever met?
+                bool add_ties = false;
+                const int64_t halfbit = 1ll << (a.sh - 1), mask = (1ll << a.sh) - 1;
+                for (int q = -128; q <= 127 && !add_ties; ++q)
+                    for (int r = -128; r <= 127; ++r) {
+                        const int64_t v = q * m_self + r * m_res + c0;
+                        if (v < 0 && (v & mask) == halfbit) { add_ties = true; break; }
+                    }
+                c.conv.add_tie_free = add_ties ? 0 : 1;
                 c.b = res;
                 c.out = d.out;
                 c.bytes_per_sample += d.bytes_per_sample / 3.0;   // the residual read
@@ -244,11 +254,13 @@ int build_device_ops(isr_model *m, ConstArena &arena) {
             const bool perm = conv_tile_m(cout_p) != 16;
             std::vector<int8_t> w((size_t)Mp * Kp, 0);
             std::vector<int32_t> bias(Mp, 0);
+            bool tie_free = fast;
+            const int64_t maxdev = std::max<int64_t>(127 - ti.zp, ti.zp + 128);   // |q - z_in| of an int8 input
             std::vector<uint32_t> m0x2(Mp, 0x80000000u), rlo(Mp, 0), rhi(Mp, 1), sh(Mp, 1);
             std::vector<int32_t> m0s(Mp, 1 << 30), chi(Mp, 1 + 2 * to.zp), shm1(Mp, 1);
             for (int oc = 0; oc < to.C; ++oc) {
                 int row = perm ? (oc & ~31) + mfma32_row_of_channel(oc & 31) : oc;
-                int64_t wsum = 0;
+                int64_t wsum = 0, wabs = 0;
                 for (int ic = 0; ic < ti.C; ++ic)
                     for (int ky = 0; ky < k; ++ky)
                         for (int kx = 0; kx < k; ++kx) {
@@ -256,7 +268,14 @@ int build_device_ops(isr_model *m, ConstArena &arena) {
                             int kk = c4 ? (ky * kwp + kx) * 4 + ic : (ky * k + kx) * cin_p + ic;
                             w[(size_t)row * Kp + kk] = v;
                             wsum += v;
+                            wabs += v < 0 ? -v : v;
                         }
+                {
+                    // acc * M0 is an exact half of 2^(31 + shift) only if acc = (odd) * 2^(30 + shift - tz(M0))
+                    const int64_t accmax = std::llabs((int64_t)o.bias[oc]) + maxdev * wabs;
+                    const int need = 30 + o.shift[oc] - __builtin_ctz((unsigned)o.M0[oc]);
+                    if (need < 40 && accmax >= (1ll << need)) tie_free = false;
+                }
                 int64_t b = (int64_t)o.bias[oc] - (int64_t)ti.zp * wsum;
                 if (b < INT32_MIN || b > INT32_MAX) return ISR_ERR_UNSUPPORTED;
                 bias[oc] = (int32_t)b;
@@ -295,6 +314,7 @@ int build_device_ops(isr_model *m, ConstArena &arena) {
             c.chi = (const int32_t *)arena.put(chi.data(), chi.size() * 4);
             c.shm1 = (const int32_t *)arena.put(shm1.data(), shm1.size() * 4);
             c.fast_requant = fast ? 1 : 0;
+            c.tie_free = tie_free ? 1 : 0;
             const std::vector<int8_t> zfill(16, (int8_t)ti.zp);
             c.zpad = (const int8_t *)arena.put(zfill.data(), zfill.size());
             c.ktab = flat ? (const uint32_t *)~(uintptr_t)0 : (const uint32_t *)arena.put(ktab.data(), ktab.size() * 4);
@@ -427,7 +447,7 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
                         sp.out = (int8_t *)(ws + pl.toff[d.out]);
                         sp.w = d.conv.w; sp.bias = d.conv.bias; sp.m0s = d.conv.m0s; sp.chi = d.conv.chi; sp.shm1 = d.conv.shm1;
                         sp.H = d.conv.H; sp.W = d.conv.W; sp.Ho = d.conv.Ho; sp.Wo = d.conv.Wo; sp.Hp = to.H; sp.Wp = to.W;
-                        sp.zp_in = d.conv.zp_in; sp.zp_out = d.conv.zp_out; sp.relu = d.conv.relu; sp.B = (int32_t)cnt;
+                        sp.zp_in = d.conv.zp_in; sp.zp_out = d.conv.zp_out; sp.relu = d.conv.relu; sp.tie_free = d.conv.tie_free; sp.B = (int32_t)cnt;
                         HIP_TRY(launch_stem_pool(sp, m->stream));
                         break;
                     }

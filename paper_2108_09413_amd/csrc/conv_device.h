@@ -3,6 +3,8 @@
 #ifndef ISR_CONV_DEVICE_H
 #define ISR_CONV_DEVICE_H
 
+#include <type_traits>
+
 #include "isr_internal.h"
 
 namespace isr {
@@ -37,11 +39,37 @@ __device__ __forceinline__ int requant_fast(int acc, int m0, int chi, int shm1) 
     return (int)(w >> 32) >> shm1;
 }
 
+// The same again for a layer whose products acc * M0 can never be an exact half
+// (ConvParams::tie_free): with the low word of the rounding term gone only the high
+// word of the product is needed.
+__device__ __forceinline__ int requant_tie_free(int acc, int m0, int chi, int shm1) {
+    return (__mulhi(acc, m0) + chi) >> shm1;
+}
+
+template <bool TIE_FREE>
+__device__ __forceinline__ int requant_q(int acc, int m0, int chi, int shm1) {
+    if constexpr (TIE_FREE) return requant_tie_free(acc, m0, chi, shm1);
+    else return requant_fast(acc, m0, chi, shm1);
+}
+
 // clamp(v, lo, hi) for lo <= hi in one instruction
 __device__ __forceinline__ int clamp3(int v, int lo, int hi) {
     int r;
     asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "v"(lo), "v"(hi));
     return r;
+}
+
+// Residual add on the int8 result q of the convolution and the int8 residual r8 (second
+// requantisation): v = q Ms + r8 Mr + c0, out = clamp((v + k + (v >> 31)) >> sh, lo, 127)
+// with k = 2^(sh-1) + z_out 2^sh; 24-bit multiplies: |q|, |r8| <= 2^7, |multipliers| < 2^23.
+template <bool TIE_FREE>
+__device__ __forceinline__ int fused_add(int q, int r8, const ConvParams &p) {
+    if constexpr (TIE_FREE) {
+        const int v = __mul24(q, p.add_mul_self) + (p.add_c0 + p.add_k) + __mul24(r8, p.add_mul_res);
+        return clamp3(v >> p.add_sh, p.add_lo, 127);
+    }
+    const int v = __mul24(q, p.add_mul_self) + p.add_c0 + __mul24(r8, p.add_mul_res);
+    return clamp3((v + p.add_k + (v >> 31)) >> p.add_sh, p.add_lo, 127);
 }
 
 // low bytes of four registers -> one dword (3 byte-permutes)

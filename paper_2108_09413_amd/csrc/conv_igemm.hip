@@ -28,7 +28,7 @@
 
 namespace isr {
 
-template <int MT, int BM, int BN, int WGM, bool FAST, int MINW, bool FUSE, int KB>
+template <int MT, int BM, int BN, int WGM, bool FAST, int MINW, bool FUSE, int KB, bool TF>
 __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams p) {
     constexpr int WGN = 4 / WGM;
     constexpr int WM = BM / WGM, WN = BN / WGN;
@@ -264,32 +264,30 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
             for (int i = 0; i < ACC; ++i) {
                 mm[i] = prm_s[1][oc - m0 + i]; ch[i] = prm_s[2][oc - m0 + i]; ss[i] = prm_s[3][oc - m0 + i];
             }
+            {
 #pragma unroll
-            for (int fn = 0; fn < FN; ++fn) {
-                long n = n0 + wn * WN + fn * MT + (lane & (MT - 1));
-                if (n >= p.npix) continue;
-                int q[ACC];
+                for (int fn = 0; fn < FN; ++fn) {
+                    long n = n0 + wn * WN + fn * MT + (lane & (MT - 1));
+                    if (n >= p.npix) continue;
+                    int q[ACC];
 #pragma unroll
-                for (int i = 0; i < ACC; ++i) {
-                    q[i] = clamp3(requant_fast(acc[fm][fn][i], mm[i], ch[i], ss[i]), lo, 127);
-                }
-                if constexpr (FUSE) {
-                    // second requantisation: the residual add on the int8 result
+                    for (int i = 0; i < ACC; ++i) q[i] = clamp3(requant_q<TF>(acc[fm][fn][i], mm[i], ch[i], ss[i]), lo, 127);
+                    if constexpr (FUSE) {
+                        // second requantisation: the residual add on the int8 result
 #pragma unroll
-                    for (int i = 0; i < ACC; ++i) {
-                        int r8 = (int)(int8_t)((uint32_t)rres[fm][fn][i >> 2] >> (8 * (i & 3)));
-                        // 24-bit multiplies (full rate): |q|, |r8| < 2^8 and |multipliers| < 2^23
-                        int v = __mul24(q[i], p.add_mul_self) + p.add_c0 + __mul24(r8, p.add_mul_res);
-                        q[i] = clamp3((v + p.add_k + (v >> 31)) >> p.add_sh, p.add_lo, 127);
+                        for (int i = 0; i < ACC; ++i) {
+                            int r8 = (int)(int8_t)((uint32_t)rres[fm][fn][i >> 2] >> (8 * (i & 3)));
+                            q[i] = fused_add<TF>(q[i], r8, p);
+                        }
                     }
-                }
-                int8_t *dst = p.out + n * p.Cout_p + oc;
-                if constexpr (MT == 32) {
-                    v4i v = {(int)pack4(q[0], q[1], q[2], q[3]), (int)pack4(q[4], q[5], q[6], q[7]),
-                             (int)pack4(q[8], q[9], q[10], q[11]), (int)pack4(q[12], q[13], q[14], q[15])};
-                    *(v4i *)dst = v;
-                } else {
-                    *(uint32_t *)dst = pack4(q[0], q[1], q[2], q[3]);
+                    int8_t *dst = p.out + n * p.Cout_p + oc;
+                    if constexpr (MT == 32) {
+                        v4i v = {(int)pack4(q[0], q[1], q[2], q[3]), (int)pack4(q[4], q[5], q[6], q[7]),
+                                 (int)pack4(q[8], q[9], q[10], q[11]), (int)pack4(q[12], q[13], q[14], q[15])};
+                        *(v4i *)dst = v;
+                    } else {
+                        *(uint32_t *)dst = pack4(q[0], q[1], q[2], q[3]);
+                    }
                 }
             }
         } else {
@@ -334,7 +332,7 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-template <int BM, int BN, int KB, int NST, bool FUSE, int MINB>
+template <int BM, int BN, int KB, int NST, bool FUSE, int MINB, bool TF>
 __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_kernel(const ConvParams p) {
     constexpr int MT = 32;
     constexpr int WGM = BM / 64, WGN = BN / 64, NT = WGM * WGN * 64;
@@ -539,28 +537,28 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
         for (int i = 0; i < ACC; ++i) {
             mm[i] = prm_s[1][oc - m0 + i]; ch[i] = prm_s[2][oc - m0 + i]; ss[i] = prm_s[3][oc - m0 + i];
         }
+        {
 #pragma unroll
-        for (int fn = 0; fn < FN; ++fn) {
-            long n = n0 + wn * 64 + fn * MT + (lane & (MT - 1));
-            if (n >= p.npix) continue;
-            int q[ACC];
+            for (int fn = 0; fn < FN; ++fn) {
+                long n = n0 + wn * 64 + fn * MT + (lane & (MT - 1));
+                if (n >= p.npix) continue;
+                int q[ACC];
 #pragma unroll
-            for (int i = 0; i < ACC; ++i) q[i] = clamp3(requant_fast(acc[fm][fn][i], mm[i], ch[i], ss[i]), lo, 127);
-            if constexpr (FUSE) {
-                const int pixel = wn * 64 + fn * MT + (lane & (MT - 1));
-                const v4i rv = *(const v4i *)(resbuf + (pixel * RCH + ((lane_oc(fm) >> 4) ^ rswz(pixel))) * 16);
+                for (int i = 0; i < ACC; ++i) q[i] = clamp3(requant_q<TF>(acc[fm][fn][i], mm[i], ch[i], ss[i]), lo, 127);
+                if constexpr (FUSE) {
+                    const int pixel = wn * 64 + fn * MT + (lane & (MT - 1));
+                    const v4i rv = *(const v4i *)(resbuf + (pixel * RCH + ((lane_oc(fm) >> 4) ^ rswz(pixel))) * 16);
 #pragma unroll
-                for (int i = 0; i < ACC; ++i) {
-                    int r8 = (int)(int8_t)((uint32_t)rv[i >> 2] >> (8 * (i & 3)));
-                    // 24-bit multiplies (full rate): |q|, |r8| < 2^8 and |multipliers| < 2^23
-                    int v = __mul24(q[i], p.add_mul_self) + p.add_c0 + __mul24(r8, p.add_mul_res);
-                    q[i] = clamp3((v + p.add_k + (v >> 31)) >> p.add_sh, p.add_lo, 127);
+                    for (int i = 0; i < ACC; ++i) {
+                        int r8 = (int)(int8_t)((uint32_t)rv[i >> 2] >> (8 * (i & 3)));
+                        q[i] = fused_add<TF>(q[i], r8, p);
+                    }
                 }
+                int8_t *dst = p.out + n * p.Cout_p + oc;
+                v4i v = {(int)pack4(q[0], q[1], q[2], q[3]), (int)pack4(q[4], q[5], q[6], q[7]),
+                         (int)pack4(q[8], q[9], q[10], q[11]), (int)pack4(q[12], q[13], q[14], q[15])};
+                *(v4i *)dst = v;
             }
-            int8_t *dst = p.out + n * p.Cout_p + oc;
-            v4i v = {(int)pack4(q[0], q[1], q[2], q[3]), (int)pack4(q[4], q[5], q[6], q[7]),
-                     (int)pack4(q[8], q[9], q[10], q[11]), (int)pack4(q[12], q[13], q[14], q[15])};
-            *(v4i *)dst = v;
         }
     }
 }
@@ -571,12 +569,18 @@ template <int MT, int BM, int BN, int WGM, int MINW, int MINW_FUSED>
 static hipError_t launch_staged(const ConvParams &p, hipStream_t st) {
     dim3 grid((unsigned)(((p.npix + BN - 1) / BN) * ((p.Cout_p + BM - 1) / BM)));
     if (p.kb != 64 || (p.fuse_add && !p.fast_requant)) return hipErrorInvalidValue;
-    if (p.fuse_add)
-        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, true, MINW_FUSED, true, 64>), grid, dim3(256), 0, st, p);
+    // TF: the rounding of this layer (and of its fused add) never meets an exact half -> shorter epilogue
+    const bool tf = p.tie_free && (!p.fuse_add || p.add_tie_free);
+    if (p.fuse_add && tf)
+        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, true, MINW_FUSED, true, 64, true>), grid, dim3(256), 0, st, p);
+    else if (p.fuse_add)
+        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, true, MINW_FUSED, true, 64, false>), grid, dim3(256), 0, st, p);
+    else if (p.fast_requant && tf)
+        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, true, MINW, false, 64, true>), grid, dim3(256), 0, st, p);
     else if (p.fast_requant)
-        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, true, MINW, false, 64>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, true, MINW, false, 64, false>), grid, dim3(256), 0, st, p);
     else
-        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, false, 2, false, 64>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((conv_igemm_kernel<MT, BM, BN, WGM, false, 2, false, 64, false>), grid, dim3(256), 0, st, p);
     return hipGetLastError();
 }
 
@@ -584,7 +588,10 @@ template <int BM, int BN, int KB, int NST, int MINB>
 static hipError_t launch_dma(const ConvParams &p, hipStream_t st) {
     constexpr int NT = (BM / 64) * (BN / 64) * 64;
     dim3 grid((unsigned)(((p.npix + BN - 1) / BN) * ((p.Cout_p + BM - 1) / BM)));
-    hipLaunchKernelGGL((conv_dma_kernel<BM, BN, KB, NST, false, MINB>), grid, dim3(NT), 0, st, p);
+    if (p.tie_free)
+        hipLaunchKernelGGL((conv_dma_kernel<BM, BN, KB, NST, false, MINB, true>), grid, dim3(NT), 0, st, p);
+    else
+        hipLaunchKernelGGL((conv_dma_kernel<BM, BN, KB, NST, false, MINB, false>), grid, dim3(NT), 0, st, p);
     return hipGetLastError();
 }
 
@@ -594,7 +601,10 @@ template <int BM, int BN, int MINB>
 static hipError_t launch_dma_fused(const ConvParams &p, hipStream_t st) {
     constexpr int NT = (BM / 64) * (BN / 64) * 64;
     dim3 grid((unsigned)(((p.npix + BN - 1) / BN) * ((p.Cout_p + BM - 1) / BM)));
-    hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 2, true, MINB>), grid, dim3(NT), 0, st, p);
+    if (p.tie_free && p.add_tie_free)
+        hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 2, true, MINB, true>), grid, dim3(NT), 0, st, p);
+    else
+        hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 2, true, MINB, false>), grid, dim3(NT), 0, st, p);
     return hipGetLastError();
 }
 

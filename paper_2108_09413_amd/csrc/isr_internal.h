@@ -69,11 +69,16 @@ struct ConvParams {
     const int32_t *chi;      // [Mp] 2^(shift-2) + z_out * 2^(shift-1)   } valid when every
     const int32_t *shm1;     // [Mp] shift - 1                           } shift is in [2, 22]
     int32_t fast_requant;
+    // 1: no output channel can meet acc * M0 = (odd) * 2^(30 + shift) within its accumulator range, so RHA
+    // never rounds an exact half and the sign correction of the rounding term is dead: the kernel then
+    // takes (mulhi(acc, M0) + chi) >> (shift - 1) (decided per layer when the model is loaded)
+    int32_t tie_free;
     // residual add folded into the epilogue (fuse_add != 0): with q the int8 result above,
     //   v = q * add_mul_self + res * add_mul_res + add_c0            (= (q-z)Ms + (res-zr)Mr)
     //   out = clamp((v + add_k + (v >> 31)) >> add_sh, add_lo, 127)  (add_k = 2^(sh-1) + z_o 2^sh)
     const int8_t *res;       // [B][Ho][Wo][Cout_p] other input of the add
     int32_t fuse_add, add_mul_self, add_mul_res, add_c0, add_k, add_sh, add_lo;
+    int32_t add_tie_free;    // 1: no pair of int8 inputs makes v a negative exact half: out = clamp((v + add_k) >> add_sh)
     const uint32_t *ktab;    // [Kp/16] per 16-byte K chunk: ky | kx<<8, 0xFFFFFFFF = padding chunk; null = plain GEMM
     const int32_t *ktoff;    // [Kp/16] byte offset (ky*W + kx)*Cin_p + channel of the chunk
     const int8_t *zpad;      // 16 bytes of z_in: source of out-of-image taps for loads that go straight to LDS
@@ -93,7 +98,7 @@ struct StemPoolParams {
     const int8_t *w;         // [>= 64][256] rows in MFMA row order, K = (ky, kx padded to 8, channel padded to 4)
     const int32_t *bias, *m0s, *chi, *shm1;   // as in ConvParams (single-multiply requantisation)
     int32_t H, W, Ho, Wo, Hp, Wp;
-    int32_t zp_in, zp_out, relu, B;
+    int32_t zp_in, zp_out, relu, tie_free, B;
 };
 
 struct AddParams {

@@ -100,15 +100,19 @@ __global__ __launch_bounds__(256, 3) void stem_pool_kernel(const StemPoolParams 
 #pragma unroll
         for (int i = 0; i < 16; ++i) va[i] = vb[i] = INT_MIN;
 
-        auto emit = [&](const int *v, int py) {
-            if (py >= p.Hp || !pxok) return;
+        auto emit_as = [&](const int *v, int py, auto tie_free) {
             int q[16];
 #pragma unroll
             for (int i = 0; i < 16; ++i)
-                q[i] = clamp3(requant_fast(v[i], prm[1][oc + i], prm[2][oc + i], prm[3][oc + i]), lo, 127);
+                q[i] = clamp3(requant_q<decltype(tie_free)::value>(v[i], prm[1][oc + i], prm[2][oc + i], prm[3][oc + i]), lo, 127);
             const v4i o = {(int)pack4(q[0], q[1], q[2], q[3]), (int)pack4(q[4], q[5], q[6], q[7]),
                            (int)pack4(q[8], q[9], q[10], q[11]), (int)pack4(q[12], q[13], q[14], q[15])};
             *(v4i *)(p.out + ((((long)b * p.Hp + py) * p.Wp + px) << 6) + oc) = o;
+        };
+        auto emit = [&](const int *v, int py) {
+            if (py >= p.Hp || !pxok) return;
+            if (p.tie_free) emit_as(v, py, std::true_type{});
+            else emit_as(v, py, std::false_type{});
         };
 
 #pragma unroll

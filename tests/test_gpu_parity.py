@@ -143,6 +143,28 @@ def test_first_layer_fused_with_max_pooling(isr, shape):
     _check_all_tensors(isr, b.blob(), x, 64, sample=3, chunk=5)
 
 
+def test_exact_halves_in_both_requantisations(isr):
+    """Power-of-two multipliers make acc * M0 and the residual sum land on exact halves
+    all the time (negative ones included), so the rounding's sign correction decides
+    results: layers that cannot take the tie-free shortcut, next to ones that can."""
+    _say("layer parity with rounding ties")
+    rng = np.random.default_rng(41)
+    b = NetBuilder(rng=np.random.default_rng(42), in_shape=(3, 16, 16), num_classes=6)
+    t0 = b.tensor(3, 16, 16, 0, 74.0)
+    m_pow2 = np.full(64, 1 << 30, dtype=np.int64)
+    m_mixed = np.where(np.arange(64) % 2 == 0, 1 << 30, (1 << 30) + 12345).astype(np.int64)
+    t1 = b.conv(t0, 64, 3, 1, 1, True, m0=m_pow2, sh=np.full(64, 9))
+    t2 = b.conv(t1, 64, 3, 1, 1, False, m0=m_mixed, sh=np.full(64, 10), zp_out=3)
+    t3 = b.conv(t2, 64, 1, 1, 0, False, m0=m_pow2, sh=np.full(64, 8), zp_out=-7)
+    t4 = b.add(t2, t3, True, ma=1 << 19, mb=1 << 19, sh=20, zp_out=-20)      # ties in the fused add
+    t5 = b.conv(t4, 128, 1, 1, 0, False, sh=rng.integers(6, 9, size=128))
+    t6 = b.conv(t5, 128, 3, 1, 1, False, m0=np.full(128, 3 << 29, dtype=np.int64), sh=np.full(128, 9))
+    t7 = b.add(t5, t6, False, ma=700001, mb=-(1 << 20), sh=20, zp_out=5)
+    b.fc(b.gap(t7), 6)
+    x = np.random.default_rng(8).integers(0, 256, size=(3, 16, 16)).astype(np.uint8)
+    _check_all_tensors(isr, b.blob(), x, 64, sample=2, chunk=3)
+
+
 # ---- S6-S8: logits, votes, decisions -----------------------------------------
 
 def test_config0_full_certify_and_predict(isr):
