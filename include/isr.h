@@ -147,6 +147,14 @@ int isr_decide_predict(const uint32_t *counts, uint32_t classes, double alpha, i
  * of the blob as its own kernel.  Results are identical either way. */
 int isr_set_fusion(isr_model *m, int enable);
 
+/* Kernel-variant switch for parity checks and tuning: output tile of the
+ * direct-to-LDS convolution kernel for layers with more than 64 stored output
+ * channels.  0 (the default) lets the library choose per launch; 1..4 force
+ * 128x128, 128x256, 256x128, 256x256 (channels x pixels; the 256-channel tiles
+ * only where a layer has more than 128 channels).  Results are identical for
+ * every choice.  ISR_ERR_ARG for other values. */
+int isr_set_conv_tile(isr_model *m, int tile);
+
 /* ---- per-kernel timing (HIP events on the model's stream) ------------------ */
 
 typedef struct isr_kernel_stat {

@@ -22,7 +22,7 @@ EXPORTS = [
     "isr_load_model", "isr_free_model", "isr_validate_model", "isr_model_info", "isr_workspace_bytes",
     "isr_set_workspace", "isr_certify", "isr_predict", "isr_debug_noisy", "isr_debug_forward",
     "isr_debug_tensor", "isr_noise_table", "isr_cp_lower", "isr_normal_quantile", "isr_binom_pvalue",
-    "isr_decide_certify", "isr_decide_predict", "isr_set_fusion", "isr_profile", "isr_profile_read", "isr_strerror",
+    "isr_decide_certify", "isr_decide_predict", "isr_set_fusion", "isr_set_conv_tile", "isr_profile", "isr_profile_read", "isr_strerror",
     "isr_last_device_error",
 ]
 
@@ -81,6 +81,7 @@ def lib():
         L.isr_decide_certify.argtypes = [vp, vp, u32, dbl, u32, dbl, C.POINTER(Result)]
         L.isr_decide_predict.argtypes = [vp, u32, dbl, C.POINTER(Result)]
         L.isr_set_fusion.argtypes = [vp, C.c_int]
+        L.isr_set_conv_tile.argtypes = [vp, C.c_int]
         L.isr_profile.argtypes = [vp, u32]
         L.isr_profile_read.argtypes = [vp, C.POINTER(KernelStat), u32, C.POINTER(u32)]
         L.isr_strerror.argtypes = [C.c_int]
@@ -266,6 +267,10 @@ def isr_debug_tensor(model: Model, x, sigma: int, seed: int, image_id: int, phas
 
 def isr_set_fusion(model: Model, enable: bool):
     _check(lib().isr_set_fusion(model.handle, 1 if enable else 0), "isr_set_fusion")
+
+
+def isr_set_conv_tile(model: Model, tile: int):
+    _check(lib().isr_set_conv_tile(model.handle, tile), "isr_set_conv_tile")
 
 
 def isr_profile(model: Model, every_chunks: int):

@@ -67,6 +67,7 @@ struct isr_model {
     std::vector<DevOp> ops;             // one descriptor per op of the blob
     Plan plan[2];                       // [0] op by op, [1] residual adds fused into the preceding conv
     int use_fused = 1;
+    int conv_tile = 0;                  // forced conv output tile (0 = automatic)
     uint8_t *dconst = nullptr;          // weights and per-channel tables
     DeviceNoiseTable *dtables = nullptr;  // TABLE_SLOTS entries
     DeviceNoiseTable *htables = nullptr;  // pinned staging, TABLE_SLOTS entries
@@ -456,6 +457,7 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
                     c.out = (int8_t *)(ws + pl.toff[d.out]);
                     c.res = c.fuse_add ? (const int8_t *)(ws + pl.toff[d.b]) : nullptr;
                     c.npix = (int32_t)(cnt * c.Ho * c.Wo);
+                    c.force_tile = m->conv_tile;
                     HIP_TRY(launch_conv(c, m->stream));
                     break; }
                 case OP_ADD: {
@@ -573,6 +575,12 @@ int isr_load_model(const void *blob_host, size_t bytes, isr_model **out) {
 int isr_set_fusion(isr_model *m, int enable) {
     if (!m) return ISR_ERR_ARG;
     m->use_fused = enable ? 1 : 0;
+    return ISR_OK;
+}
+
+int isr_set_conv_tile(isr_model *m, int tile) {
+    if (!m || tile < 0 || tile > 4) return ISR_ERR_ARG;
+    m->conv_tile = tile;
     return ISR_OK;
 }
 

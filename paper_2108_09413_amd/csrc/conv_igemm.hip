@@ -627,7 +627,7 @@ int conv_k_step(int kreal, int cin_p, int cout_p, int fast_requant) {
 enum DmaTile { T64x256, T128x128, T128x256, T256x128, T256x256 };
 
 static DmaTile pick_tile(const ConvParams &p) {
-    static const int forced = [] { const char *e = getenv("ISR_CONV_TILE"); return e ? atoi(e) : -1; }();
+    const int forced = p.force_tile;
     if (p.Cout_p <= 64) return T64x256;
     if (forced >= T128x128 && forced <= T256x256 && !(p.Cout_p <= 128 && (forced == T256x128 || forced == T256x256)))
         return (DmaTile)forced;

@@ -84,6 +84,7 @@ struct ConvParams {
     const int8_t *zpad;      // 16 bytes of z_in: source of out-of-image taps for loads that go straight to LDS
     int32_t H, W, Cin_p, Ho, Wo, Cout_p;
     int32_t k, stride, pad, Kp, Mp;   // k: kernel size (k x k taps)
+    int32_t force_tile;      // 0: the launcher picks the output tile; 1..4: 128x128, 128x256, 256x128, 256x256
     int32_t kb;              // K bytes per step of the kernel (64 or 128); Kp is a multiple of it
     int32_t zp_in, zp_out, relu;
     int32_t npix;            // B * Ho * Wo

@@ -272,6 +272,63 @@ def test_resnet50_full_size_logits(isr):
     m.close()
 
 
+def test_resnet50_in_the_benchmarked_launch_configuration(isr):
+    """bench.py's configuration: chunks of 668 noisy copies, library-chosen tiles
+    (256x256, 128x256, 128x128 and the fused first layer all occur).  One full chunk
+    on the device; the oracle checks sampled copies one by one, the vote counts must
+    add up, and forcing each tile must not change a single logit."""
+    _say("resnet50 224 parity at chunk 668")
+    blob = synth.build_model(4)
+    om = oracle.Model(blob)
+    m = _load(isr, blob, 668)
+    x = synth.make_image(4, 2)
+    lg, am, cnt = isr.isr_debug_forward(m, x, 128, 0, 2, 1, 20000, 668)
+    assert int(cnt.sum()) == 668 and np.array_equal(np.bincount(am, minlength=len(cnt)), cnt)
+    assert np.array_equal(am, np.argmax(lg, axis=1))
+    for i in (0, 255, 667):
+        _say(f"  oracle sample {20000 + i}")
+        olg, oam, _ = om.mc(x, 128, 0, 2, 1, 20000 + i, 1)
+        assert np.array_equal(lg[i], olg[0]) and am[i] == oam[0]
+    for tile in (1, 2, 3, 4):
+        _say(f"  forced tile {tile}")
+        isr.isr_set_conv_tile(m, tile)
+        lg2, am2, cnt2 = isr.isr_debug_forward(m, x, 128, 0, 2, 1, 20000, 668)
+        assert np.array_equal(lg2, lg) and np.array_equal(cnt2, cnt)
+    m.close()
+
+
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
+def test_every_conv_tile_against_the_oracle(isr, tile):
+    """Layers deep enough for 128-byte K steps and for every output tile of the
+    direct-to-LDS kernel, channel counts that leave a ragged last M tile, a ragged
+    last pixel tile (37 copies of a 12x12 image), strides; tile forced through the C ABI."""
+    _say(f"conv tile {tile} parity")
+    rng = np.random.default_rng(51)
+    b = NetBuilder(rng=np.random.default_rng(52), in_shape=(3, 12, 12), num_classes=9)
+    t0 = b.tensor(3, 12, 12, 0, 74.0)
+    t1 = b.conv(t0, 128, 3, 1, 1, True)
+    t2 = b.conv(t1, 128, 3, 1, 1, True)                 # K = 1152
+    t3 = b.conv(t2, 256, 1, 1, 0, True)                 # K = 128
+    t4 = b.conv(t3, 256, 3, 1, 1, True)                 # K = 2304, 128-byte steps
+    t5 = b.conv(t4, 512, 1, 1, 0, False)                # K = 256
+    t6 = b.conv(t5, 272, 1, 1, 0, True)                 # K = 512, ragged M
+    t7 = b.conv(t6, 320, 3, 2, 1, True)                 # K = 2448 (not a multiple of 128), stride 2, ragged M
+    t8 = b.conv(t7, 1024, 1, 1, 0, True)                # K = 320
+    t9 = b.conv(t8, 256, 1, 1, 0, True)                 # K = 1024, 128-byte steps, 1x1
+    b.fc(b.gap(t9), 9)
+    blob = b.blob()
+    x = np.random.default_rng(9).integers(0, 256, size=(3, 12, 12)).astype(np.uint8)
+    m = _load(isr, blob, 37)
+    isr.isr_set_conv_tile(m, tile)
+    om = oracle.Model(blob)
+    lg, am, cnt = isr.isr_debug_forward(m, x, 64, 1, 1, 1, 5, 37)
+    olg, oam, ocnt = om.mc(x, 64, 1, 1, 1, 5, 37)
+    assert np.array_equal(lg, olg) and np.array_equal(am, oam) and np.array_equal(cnt, ocnt)
+    m.close()
+    if tile == 4:
+        _check_all_tensors(isr, blob, x, 64)
+
+
 # ---- argument handling --------------------------------------------------------
 
 def test_error_paths(isr):
