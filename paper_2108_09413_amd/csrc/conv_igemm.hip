@@ -659,14 +659,19 @@ hipError_t launch_conv(const ConvParams &p, hipStream_t st) {
         const bool k128 = p.kb == 128;
         if (p.fuse_add) return p.Cout_p <= 64 ? launch_dma_fused<64, 256, 3>(p, st) : launch_dma_fused<128, 128, 4>(p, st);
         switch (pick_tile(p)) {
-        case T64x256: return k128 ? hipErrorInvalidValue : launch_dma<64, 256, 64, 3, 2>(p, st);
+        case T64x256:
+            // two steps in flight and three workgroups per CU measured faster than three and two
+            if (k128) return hipErrorInvalidValue;
+            return launch_dma<64, 256, 64, 2, 3>(p, st);
         case T128x128:
             // shallow layers are epilogue-bound: two steps in flight suffice and a fourth
             // workgroup per CU hides more of the epilogue's memory latency
             if (!p.fuse_add && p.Kp < 1024 && !k128) return launch_dma<128, 128, 64, 2, 4>(p, st);
             return k128 ? launch_dma<128, 128, 128, 2, 2>(p, st) : launch_dma<128, 128, 64, 3, 3>(p, st);
-        case T128x256: return k128 ? launch_dma<128, 256, 128, 2, 1>(p, st) : launch_dma<128, 256, 64, 3, 2>(p, st);
-        case T256x128: return k128 ? launch_dma<256, 128, 128, 2, 1>(p, st) : launch_dma<256, 128, 64, 3, 2>(p, st);
+        case T128x256:
+            return k128 ? launch_dma<128, 256, 128, 2, 1>(p, st) : launch_dma<128, 256, 64, 3, 2>(p, st);
+        case T256x128:
+            return k128 ? launch_dma<256, 128, 128, 2, 1>(p, st) : launch_dma<256, 128, 64, 3, 2>(p, st);
         case T256x256: return k128 ? launch_dma<256, 256, 128, 2, 1>(p, st) : launch_dma<256, 256, 64, 3, 1>(p, st);
         }
         return hipErrorInvalidValue;
