@@ -191,6 +191,30 @@ void fuse_adds(const ParsedModel &pm, const std::vector<DevOp> &plain, std::vect
                 c.b = res;
                 c.out = d.out;
                 c.bytes_per_sample += d.bytes_per_sample / 3.0;   // the residual read
+                // The residual is the output of the 1x1 convolution issued right before, read by this
+                // add alone: compute it inside the same kernel instead of round-tripping it through memory.
+                if (fused.size() >= 2) {
+                    const DevOp &r = fused[fused.size() - 2];
+                    const ConvParams &rc = r.conv;
+                    const bool direct = c.conv.fast_requant && !c.conv.c4 && c.conv.Cout_p >= 64;
+                    if (direct && r.type == OP_CONV && r.out == res && uses[res] == 1 && !rc.fuse_add && rc.fast_requant &&
+                        !rc.c4 && rc.ktab == nullptr && rc.Cin_p % 64 == 0 && rc.Kp == rc.Cin_p &&
+                        rc.Cout_p == c.conv.Cout_p && rc.Mp == c.conv.Mp && rc.Ho == c.conv.Ho && rc.Wo == c.conv.Wo) {
+                        DevOp merged = c;
+                        merged.conv.fuse_add = 2;
+                        merged.conv.w2 = rc.w; merged.conv.bias2 = rc.bias; merged.conv.m0s2 = rc.m0s;
+                        merged.conv.chi2 = rc.chi; merged.conv.shm12 = rc.shm1;
+                        merged.conv.Cin2_p = rc.Cin_p;
+                        merged.conv.lo2 = rc.relu ? rc.zp_out : -128;
+                        merged.conv.tie_free2 = rc.tie_free;
+                        merged.b = r.a;   // second input tensor (kept alive until this op is issued)
+                        merged.ops_per_sample += r.ops_per_sample;
+                        merged.bytes_per_sample += r.bytes_per_sample - 2.0 * d.bytes_per_sample / 3.0;   // no residual write + read
+                        fused.pop_back();
+                        fused.pop_back();
+                        fused.push_back(merged);
+                    }
+                }
                 continue;
             }
         }
@@ -455,7 +479,8 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
                     ConvParams c = d.conv;
                     c.in = (const int8_t *)(ws + pl.toff[d.a]);
                     c.out = (int8_t *)(ws + pl.toff[d.out]);
-                    c.res = c.fuse_add ? (const int8_t *)(ws + pl.toff[d.b]) : nullptr;
+                    c.res = c.fuse_add == 1 ? (const int8_t *)(ws + pl.toff[d.b]) : nullptr;
+                    c.in2 = c.fuse_add == 2 ? (const int8_t *)(ws + pl.toff[d.b]) : nullptr;
                     c.npix = (int32_t)(cnt * c.Ho * c.Wo);
                     c.force_tile = m->conv_tile;
                     HIP_TRY(launch_conv(c, m->stream));

@@ -332,7 +332,9 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-template <int BM, int BN, int KB, int NST, bool FUSE, int MINB, bool TF>
+// FUSE: 0 plain, 1 residual add with the residual read from memory, 2 residual add with the
+// residual computed here by a second (1x1, stride 1) convolution.
+template <int BM, int BN, int KB, int NST, int FUSE, int MINB, bool TF>
 __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_kernel(const ConvParams p) {
     constexpr int MT = 32;
     constexpr int WGM = BM / 64, WGN = BN / 64, NT = WGM * WGN * 64;
@@ -356,7 +358,8 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
     // operand buffer that is idle during the last K step.
     constexpr int RCH = BM / 16;                    // chunks per pixel row
     constexpr int RPB = BM >= 256 ? 1 : 256 / BM;   // pixel rows per 256 bytes (one pass over the 64 banks)
-    static_assert(!FUSE || (NST == 2 && STAGE >= BM * BN && BM * BN / 16 % NT == 0), "residual tile fits a buffer");
+    static_assert(FUSE != 1 || (NST == 2 && STAGE >= BM * BN && BM * BN / 16 % NT == 0), "residual tile fits a buffer");
+    __shared__ __attribute__((aligned(16))) int prm2_s[4][FUSE == 2 ? BM : 1];   // the same for the residual convolution
     auto rswz = [](int pixel) { return (pixel / RPB) & (RCH - 1); };
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -386,6 +389,12 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
         prm_s[1][i] = in ? p.m0s[m0 + i] : 0;
         prm_s[2][i] = in ? p.chi[m0 + i] : 0;
         prm_s[3][i] = in ? p.shm1[m0 + i] : 1;
+        if constexpr (FUSE == 2) {
+            prm2_s[0][i] = in ? p.bias2[m0 + i] : 0;
+            prm2_s[1][i] = in ? p.m0s2[m0 + i] : 0;
+            prm2_s[2][i] = in ? p.chi2[m0 + i] : 0;
+            prm2_s[3][i] = in ? p.shm12[m0 + i] : 1;
+        }
     }
 
     int pixoff[NB];
@@ -445,6 +454,29 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
         }
     };
 
+    // the residual convolution's operands: pixel n of the output reads pixel n of in2
+    int pixoff2[FUSE == 2 ? NB : 1];
+    const int8_t *wrow2[FUSE == 2 ? NA : 1];
+    if constexpr (FUSE == 2) {
+#pragma unroll
+        for (int j = 0; j < NB; ++j) pixoff2[j] = (int)((rvalid[j] ? n0 + row0 + RPP * j : (long)p.npix - 1) * p.Cin2_p) + cl * 16;
+#pragma unroll
+        for (int j = 0; j < NA; ++j) {
+            int r = m0 + row0 + RPP * j;
+            wrow2[j] = p.w2 + (long)(r < p.Mp ? r : 0) * p.Cin2_p + cl * 16;
+        }
+    }
+    auto issue2 = [&](int ks, int buf) {
+        if constexpr (FUSE == 2) {
+            int8_t *sa = &Ls[buf][wave * 1024];
+#pragma unroll
+            for (int j = 0; j < NA; ++j) ISR_GLOBAL_TO_LDS16(wrow2[j] + (long)ks * KB, sa + j * (NT * 16));
+            int8_t *sb = sa + BM * KB;
+#pragma unroll
+            for (int j = 0; j < NB; ++j) ISR_GLOBAL_TO_LDS16(p.in2 + (uint32_t)(pixoff2[j] + ks * KB), sb + j * (NT * 16));
+        }
+    };
+
     typedef int acc_t __attribute__((ext_vector_type(ACC)));
     acc_t acc[FM][FN];
     auto lane_oc = [&](int fm) { return wm * 64 + fm * MT + 16 * (lane >> 5); };
@@ -460,22 +492,10 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
             ISR_GLOBAL_TO_LDS16(p.res + n * p.Cout_p + oc, &Ls[buf][(j * NT + wave * 64) * 16]);
         }
     };
-    if constexpr (FUSE)
+    if constexpr (FUSE == 1)
         if (nk == 1) issue_residual(1);   // the second buffer is never used by a K step
 
     __syncthreads();   // ktg_s, prm_s visible
-#pragma unroll
-    for (int fm = 0; fm < FM; ++fm) {
-        acc_t init;
-#pragma unroll
-        for (int i = 0; i < ACC; ++i) init[i] = prm_s[0][lane_oc(fm) + i];
-#pragma unroll
-        for (int fn = 0; fn < FN; ++fn) acc[fm][fn] = init;
-    }
-#pragma unroll
-    for (int s = 0; s < NST - 1; ++s)
-        if (s < nk) issue(s, s);
-
     // per-lane fragment offsets inside a step's buffer
     int aoff[KS][FM], boff[KS][FN];
 #pragma unroll
@@ -493,36 +513,71 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
         }
     }
 
-    int cur = 0, fill = NST - 1;   // buffer computed on now / buffer filled next
-    for (int ks = 0; ks < nk; ++ks) {
-        // This wave's loads of step ks have landed once at most the loads of the steps
-        // after it (min(nk - 1 - ks, NST - 2) of them, L each) are still in flight.
-        if (NST == 3 && ks + 1 < nk) wait_vmcnt<L>();
-        else wait_vmcnt<0>();
-        __builtin_amdgcn_s_barrier();   // every wave's loads of step ks landed; every wave is done with step ks - 1
-        if (ks + NST - 1 < nk) issue(ks + NST - 1, fill);
-        else if (FUSE && ks + 1 == nk && nk > 1) issue_residual(fill);
-        const int8_t *base = Ls[cur];
+    // One GEMM over `steps` K steps fetched by `fetch(step, buffer)`; accumulators start at `bias_s`.
+    auto gemm = [&](int steps, const int *bias_s, auto fetch, bool with_residual_tile) {
 #pragma unroll
-        for (int ksub = 0; ksub < KS; ++ksub) {
-            v4i fa[FM], fb[FN];
+        for (int fm = 0; fm < FM; ++fm) {
+            acc_t init;
 #pragma unroll
-            for (int fm = 0; fm < FM; ++fm) fa[fm] = *(const v4i *)(base + aoff[ksub][fm]);
+            for (int i = 0; i < ACC; ++i) init[i] = bias_s[lane_oc(fm) + i];
 #pragma unroll
-            for (int fn = 0; fn < FN; ++fn) fb[fn] = *(const v4i *)(base + boff[ksub][fn]);
-#pragma unroll
-            for (int fm = 0; fm < FM; ++fm)
-#pragma unroll
-                for (int fn = 0; fn < FN; ++fn)
-                    acc[fm][fn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[fm], fb[fn], acc[fm][fn], 0, 0, 0);
+            for (int fn = 0; fn < FN; ++fn) acc[fm][fn] = init;
         }
-        cur = cur + 1 == NST ? 0 : cur + 1;
-        fill = fill + 1 == NST ? 0 : fill + 1;
+#pragma unroll
+        for (int s = 0; s < NST - 1; ++s)
+            if (s < steps) fetch(s, s);
+        int cur = 0, fill = NST - 1;   // buffer computed on now / buffer filled next
+        for (int ks = 0; ks < steps; ++ks) {
+            // This wave's loads of step ks have landed once at most the loads of the steps
+            // after it (min(steps - 1 - ks, NST - 2) of them, L each) are still in flight.
+            if (NST == 3 && ks + 1 < steps) wait_vmcnt<L>();
+            else wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();   // every wave's loads of step ks landed; every wave is done with step ks - 1
+            if (ks + NST - 1 < steps) fetch(ks + NST - 1, fill);
+            else if (FUSE == 1 && with_residual_tile && ks + 1 == steps && steps > 1) issue_residual(fill);
+            const int8_t *base = Ls[cur];
+#pragma unroll
+            for (int ksub = 0; ksub < KS; ++ksub) {
+                v4i fa[FM], fb[FN];
+#pragma unroll
+                for (int fm = 0; fm < FM; ++fm) fa[fm] = *(const v4i *)(base + aoff[ksub][fm]);
+#pragma unroll
+                for (int fn = 0; fn < FN; ++fn) fb[fn] = *(const v4i *)(base + boff[ksub][fn]);
+#pragma unroll
+                for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+                    for (int fn = 0; fn < FN; ++fn)
+                        acc[fm][fn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[fm], fb[fn], acc[fm][fn], 0, 0, 0);
+            }
+            cur = cur + 1 == NST ? 0 : cur + 1;
+            fill = fill + 1 == NST ? 0 : fill + 1;
+        }
+    };
+
+    // residual convolution first: its int8 result stays packed in registers (16 channels per dword group)
+    v4i rq[FUSE == 2 ? FM : 1][FUSE == 2 ? FN : 1];
+    if constexpr (FUSE == 2) {
+        gemm(p.Cin2_p / KB, prm2_s[0], issue2, false);
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+            for (int fn = 0; fn < FN; ++fn) {
+                int q[ACC];
+#pragma unroll
+                for (int i = 0; i < ACC; ++i) {
+                    const int c = lane_oc(fm) + i;
+                    q[i] = clamp3(requant_q<TF>(acc[fm][fn][i], prm2_s[1][c], prm2_s[2][c], prm2_s[3][c]), p.lo2, 127);
+                }
+                rq[fm][fn] = v4i{(int)pack4(q[0], q[1], q[2], q[3]), (int)pack4(q[4], q[5], q[6], q[7]),
+                                 (int)pack4(q[8], q[9], q[10], q[11]), (int)pack4(q[12], q[13], q[14], q[15])};
+            }
+        __syncthreads();   // every wave is done with the operand buffers before the main GEMM refills them
     }
+    gemm(nk, prm_s[0], issue, true);
 
     // epilogue: requantise, clamp, optional residual add, pack, store (NHWC)
     const int8_t *resbuf = nullptr;
-    if constexpr (FUSE) {
+    if constexpr (FUSE == 1) {
         wait_vmcnt<0>();
         __syncthreads();   // the residual tile is in LDS
         resbuf = Ls[nk == 1 ? 1 : (nk & 1)];   // the buffer that held step nk - 2
@@ -545,9 +600,11 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
                 int q[ACC];
 #pragma unroll
                 for (int i = 0; i < ACC; ++i) q[i] = clamp3(requant_q<TF>(acc[fm][fn][i], mm[i], ch[i], ss[i]), lo, 127);
-                if constexpr (FUSE) {
+                if constexpr (FUSE != 0) {
                     const int pixel = wn * 64 + fn * MT + (lane & (MT - 1));
-                    const v4i rv = *(const v4i *)(resbuf + (pixel * RCH + ((lane_oc(fm) >> 4) ^ rswz(pixel))) * 16);
+                    v4i rv;
+                    if constexpr (FUSE == 2) rv = rq[fm][fn];
+                    else rv = *(const v4i *)(resbuf + (pixel * RCH + ((lane_oc(fm) >> 4) ^ rswz(pixel))) * 16);
 #pragma unroll
                     for (int i = 0; i < ACC; ++i) {
                         int r8 = (int)(int8_t)((uint32_t)rv[i >> 2] >> (8 * (i & 3)));
@@ -568,7 +625,7 @@ int conv_tile_m(int cout_p) { return cout_p <= 16 ? 16 : (cout_p <= 32 ? 32 : (c
 template <int MT, int BM, int BN, int WGM, int MINW, int MINW_FUSED>
 static hipError_t launch_staged(const ConvParams &p, hipStream_t st) {
     dim3 grid((unsigned)(((p.npix + BN - 1) / BN) * ((p.Cout_p + BM - 1) / BM)));
-    if (p.kb != 64 || (p.fuse_add && !p.fast_requant)) return hipErrorInvalidValue;
+    if (p.kb != 64 || (p.fuse_add && !p.fast_requant) || p.fuse_add == 2) return hipErrorInvalidValue;
     // TF: the rounding of this layer (and of its fused add) never meets an exact half -> shorter epilogue
     const bool tf = p.tie_free && (!p.fuse_add || p.add_tie_free);
     if (p.fuse_add && tf)
@@ -589,22 +646,28 @@ static hipError_t launch_dma(const ConvParams &p, hipStream_t st) {
     constexpr int NT = (BM / 64) * (BN / 64) * 64;
     dim3 grid((unsigned)(((p.npix + BN - 1) / BN) * ((p.Cout_p + BM - 1) / BM)));
     if (p.tie_free)
-        hipLaunchKernelGGL((conv_dma_kernel<BM, BN, KB, NST, false, MINB, true>), grid, dim3(NT), 0, st, p);
+        hipLaunchKernelGGL((conv_dma_kernel<BM, BN, KB, NST, 0, MINB, true>), grid, dim3(NT), 0, st, p);
     else
-        hipLaunchKernelGGL((conv_dma_kernel<BM, BN, KB, NST, false, MINB, false>), grid, dim3(NT), 0, st, p);
+        hipLaunchKernelGGL((conv_dma_kernel<BM, BN, KB, NST, 0, MINB, false>), grid, dim3(NT), 0, st, p);
     return hipGetLastError();
 }
 
 // With a fused residual add: 64-byte K steps in two buffers (any Kp is a multiple of 64),
 // the second of which also receives the residual tile; small tiles, 3-4 workgroups per CU.
-template <int BM, int BN, int MINB>
+template <int BM, int BN, int MINB, int MINB2>
 static hipError_t launch_dma_fused(const ConvParams &p, hipStream_t st) {
     constexpr int NT = (BM / 64) * (BN / 64) * 64;
     dim3 grid((unsigned)(((p.npix + BN - 1) / BN) * ((p.Cout_p + BM - 1) / BM)));
-    if (p.tie_free && p.add_tie_free)
-        hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 2, true, MINB, true>), grid, dim3(NT), 0, st, p);
+    if (p.fuse_add == 2) {
+        if (!p.in2 || !p.w2 || p.Cin2_p < 64 || p.Cin2_p % 64 != 0) return hipErrorInvalidValue;
+        if (p.tie_free && p.add_tie_free && p.tie_free2)
+            hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 2, 2, MINB2, true>), grid, dim3(NT), 0, st, p);
+        else
+            hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 2, 2, MINB2, false>), grid, dim3(NT), 0, st, p);
+    } else if (p.tie_free && p.add_tie_free)
+        hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 2, 1, MINB, true>), grid, dim3(NT), 0, st, p);
     else
-        hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 2, true, MINB, false>), grid, dim3(NT), 0, st, p);
+        hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 2, 1, MINB, false>), grid, dim3(NT), 0, st, p);
     return hipGetLastError();
 }
 
@@ -657,7 +720,7 @@ hipError_t launch_conv(const ConvParams &p, hipStream_t st) {
     if (dma_path(p.Cout_p, p.fast_requant, p.c4)) {
         if (!p.zpad) return hipErrorInvalidValue;
         const bool k128 = p.kb == 128;
-        if (p.fuse_add) return p.Cout_p <= 64 ? launch_dma_fused<64, 256, 3>(p, st) : launch_dma_fused<128, 128, 4>(p, st);
+        if (p.fuse_add) return p.Cout_p <= 64 ? launch_dma_fused<64, 256, 3, 3>(p, st) : launch_dma_fused<128, 128, 4, 3>(p, st);
         switch (pick_tile(p)) {
         case T64x256:
             // two steps in flight and three workgroups per CU measured faster than three and two

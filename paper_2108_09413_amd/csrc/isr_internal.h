@@ -79,6 +79,13 @@ struct ConvParams {
     const int8_t *res;       // [B][Ho][Wo][Cout_p] other input of the add
     int32_t fuse_add, add_mul_self, add_mul_res, add_c0, add_k, add_sh, add_lo;
     int32_t add_tie_free;    // 1: no pair of int8 inputs makes v a negative exact half: out = clamp((v + add_k) >> add_sh)
+    // fuse_add == 2: the residual is itself the output of a 1x1 stride-1 convolution (same pixels, same
+    // channels) that has no other reader; the kernel computes it first, keeps it in registers and never
+    // stores it.  Its operands:
+    const int8_t *in2;       // [B][Ho][Wo][Cin2_p]
+    const int8_t *w2;        // [Mp][Cin2_p] rows in MFMA row order
+    const int32_t *bias2, *m0s2, *chi2, *shm12;   // as bias / m0s / chi / shm1
+    int32_t Cin2_p, lo2, tie_free2;                // lo2: lower clamp of the residual tensor
     const uint32_t *ktab;    // [Kp/16] per 16-byte K chunk: ky | kx<<8, 0xFFFFFFFF = padding chunk; null = plain GEMM
     const int32_t *ktoff;    // [Kp/16] byte offset (ky*W + kx)*Cin_p + channel of the chunk
     const int8_t *zpad;      // 16 bytes of z_in: source of out-of-image taps for loads that go straight to LDS

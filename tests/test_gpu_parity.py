@@ -143,6 +143,42 @@ def test_first_layer_fused_with_max_pooling(isr, shape):
     _check_all_tensors(isr, b.blob(), x, 64, sample=3, chunk=5)
 
 
+def test_residual_computed_by_a_second_convolution(isr):
+    """Projection-shortcut pattern: the residual of an add is the output of a 1x1
+    convolution issued right before the add's other convolution; the fused plan then
+    computes both in one kernel and never stores the residual.  Main convolution 3x3
+    (gather), 1x1 stride 2 (gather) and 1x1 stride 1 (plain GEMM); channel counts that
+    leave a ragged last M tile; K of the two convolutions different; 29 copies."""
+    _say("layer parity dual-convolution residual add")
+    rng = np.random.default_rng(61)
+    b = NetBuilder(rng=np.random.default_rng(62), in_shape=(3, 12, 12), num_classes=8)
+    t0 = b.tensor(3, 12, 12, 0, 74.0)
+    t1 = b.conv(t0, 64, 3, 1, 1, True)
+    t2 = b.conv(t1, 192, 1, 1, 0, False, zp_out=11)          # residual producer (K = 64)
+    t3 = b.conv(t1, 192, 3, 1, 1, False, zp_out=-9)          # main, K = 576
+    t4 = b.add(t2, t3, True)
+    u = b.conv(t4, 128, 3, 2, 1, True)                       # 6 x 6
+    r = b.conv(u, 320, 1, 1, 0, False)                       # residual producer (K = 128)
+    mn = b.conv(t4, 320, 1, 2, 0, False)                     # main: 1x1 stride 2, K = 192
+    t5 = b.add(mn, r, True)                                  # residual is the second operand here
+    r2 = b.conv(t5, 64, 1, 1, 0, False)                      # 64 output channels: the 64 x 256 tile
+    m2 = b.conv(t5, 64, 1, 1, 0, True)
+    t6 = b.add(r2, m2, False, ma=-500000, mb=800000, sh=20)
+    b.fc(b.gap(t6), 8)
+    blob = b.blob()
+    x = np.random.default_rng(10).integers(0, 256, size=(3, 12, 12)).astype(np.uint8)
+    _check_all_tensors(isr, blob, x, 64, sample=1, chunk=3)
+    m = _load(isr, blob, 29)
+    om = oracle.Model(blob)
+    lg, am, cnt = isr.isr_debug_forward(m, x, 64, 1, 1, 1, 0, 29)
+    olg, oam, ocnt = om.mc(x, 64, 1, 1, 1, 0, 29)
+    assert np.array_equal(lg, olg) and np.array_equal(cnt, ocnt)
+    isr.isr_set_fusion(m, False)
+    lg2, _, _ = isr.isr_debug_forward(m, x, 64, 1, 1, 1, 0, 29)
+    assert np.array_equal(lg2, olg)
+    m.close()
+
+
 def test_exact_halves_in_both_requantisations(isr):
     """Power-of-two multipliers make acc * M0 and the residual sum land on exact halves
     all the time (negative ones included), so the rounding's sign correction decides
