@@ -142,9 +142,13 @@ int isr_decide_certify(const uint32_t *counts0, const uint32_t *counts1, uint32_
                        double sigma, uint32_t n, double alpha, isr_result *out);
 int isr_decide_predict(const uint32_t *counts, uint32_t classes, double alpha, isr_result *out);
 
-/* Kernel-variant switch for parity checks: enable != 0 (the default) folds each
- * residual add into the epilogue of the convolution before it; 0 runs every op
- * of the blob as its own kernel.  Results are identical either way. */
+/* Kernel-variant switch for parity checks: enable != 0 (the default) lets the
+ * library fuse ops of the blob into one kernel where it can (a residual add into
+ * the convolution before it; the first convolution with the max pooling after
+ * it; a 1x1 convolution that only feeds a residual add into that add's kernel);
+ * 0 runs every op of the blob as its own kernel.  Results are identical either
+ * way; tensors that a fused kernel never stores are served by the unfused plan
+ * in isr_debug_tensor. */
 int isr_set_fusion(isr_model *m, int enable);
 
 /* Kernel-variant switch for parity checks and tuning: output tile of the
