@@ -27,6 +27,33 @@ def radius(sigma: float, p_lower: float) -> float:
     return float(sigma * _st.norm.ppf(p_lower))
 
 
+def discrete_quantile(sigma: int, p_lower: float) -> int:
+    """Integer-only tail of the certification (Thm 3.2, proof steps 2 and 3): the inverse
+    cdf of the one-dimensional discrete Gaussian N_Z(0, sigma^2) (Def. 3.3) by lookup in
+    its precomputed cdf table -- the largest lattice point t, in input grid units, with
+    P[delta <= t] <= p_lower.  With Phi^-1 of the discrete law in place of the normal
+    one the radius sigma * Phi^-1(p) of Alg. 1 is t itself and the squared radius
+    t * t stays on the lattice.  The cdf is the 64-bit fixed-point table of the sampler:
+    T[i] = floor(2^64 P[delta <= i - R]); p_lower enters as floor(2^64 p_lower), exact
+    for a float64 below 1.  Returns -R - 1 when even the first table entry exceeds p."""
+    from fractions import Fraction
+
+    from . import noise_table
+    T, R = noise_table(int(sigma))
+    if not 0.0 <= p_lower <= 1.0:
+        raise ValueError("p_lower outside [0, 1]")
+    u = min(int(Fraction(p_lower) * (1 << 64)), (1 << 64) - 1)
+    below = sum(1 for t in T if int(t) <= u)
+    return -R - 1 + below
+
+
+def radius_squared_int(sigma: int, p_lower: float) -> int:
+    """Squared certified radius in squared grid units, integers only: 0 unless the
+    discrete quantile is positive (Thm 3.2, proof step 3)."""
+    t = discrete_quantile(sigma, p_lower)
+    return t * t if t > 0 else 0
+
+
 def lowest_argmax(counts) -> int:
     best = 0
     for i in range(1, len(counts)):
