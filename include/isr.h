@@ -135,6 +135,15 @@ int isr_noise_table(uint32_t sigma, uint64_t *T_host, size_t cap, uint32_t *R_ou
 int isr_cp_lower(uint32_t k, uint32_t n, double alpha, double *p_lower);
 /* Standard normal quantile Phi^-1(p), 0 < p < 1 (radius factor of Alg. 1). */
 int isr_normal_quantile(double p, double *z);
+/* Integer-only tail of the certification (Thm 3.2, proof steps 2 and 3): the inverse cdf of
+ * the one-dimensional discrete Gaussian N_Z(0, sigma^2) by lookup in the table of
+ * isr_noise_table -- t_out = the largest lattice point t (input grid units) with
+ * floor(2^64 P[delta <= t]) <= floor(2^64 p_lower), -R - 1 if there is none -- and the squared
+ * radius radius_sq_out = t * t for t > 0, else 0 (squared grid units).  With the discrete
+ * law's Phi^-1 the radius sigma * Phi^-1(p) of Alg. 1 is t itself.  Host only, integers but
+ * for the conversion of p_lower; either output pointer may be NULL.  ISR_ERR_ARG unless
+ * 1 <= sigma <= 1024 and 0 <= p_lower <= 1. */
+int isr_discrete_quantile(uint32_t sigma, double p_lower, int32_t *t_out, uint64_t *radius_sq_out);
 /* Two-sided binomial p-value min(1, 2 P[Bin(n_a+n_b, 1/2) >= n_a]) (Alg. 2). */
 int isr_binom_pvalue(uint32_t n_a, uint32_t n_b, double *pvalue);
 /* Decisions of Alg. 1 / Alg. 2 on tallies already on the host. */

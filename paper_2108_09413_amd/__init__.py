@@ -22,7 +22,7 @@ EXPORTS = [
     "isr_load_model", "isr_free_model", "isr_validate_model", "isr_model_info", "isr_workspace_bytes",
     "isr_set_workspace", "isr_certify", "isr_predict", "isr_debug_noisy", "isr_debug_forward",
     "isr_debug_tensor", "isr_noise_table", "isr_cp_lower", "isr_normal_quantile", "isr_binom_pvalue",
-    "isr_decide_certify", "isr_decide_predict", "isr_set_fusion", "isr_set_conv_tile", "isr_profile", "isr_profile_read", "isr_strerror",
+    "isr_decide_certify", "isr_decide_predict", "isr_discrete_quantile", "isr_set_fusion", "isr_set_conv_tile", "isr_profile", "isr_profile_read", "isr_strerror",
     "isr_last_device_error",
 ]
 
@@ -78,6 +78,7 @@ def lib():
         L.isr_cp_lower.argtypes = [u32, u32, dbl, C.POINTER(dbl)]
         L.isr_normal_quantile.argtypes = [dbl, C.POINTER(dbl)]
         L.isr_binom_pvalue.argtypes = [u32, u32, C.POINTER(dbl)]
+        L.isr_discrete_quantile.argtypes = [u32, dbl, C.POINTER(i32), C.POINTER(u64)]
         L.isr_decide_certify.argtypes = [vp, vp, u32, dbl, u32, dbl, C.POINTER(Result)]
         L.isr_decide_predict.argtypes = [vp, u32, dbl, C.POINTER(Result)]
         L.isr_set_fusion.argtypes = [vp, C.c_int]
@@ -128,6 +129,13 @@ def isr_normal_quantile(p: float) -> float:
     out = C.c_double(0)
     _check(lib().isr_normal_quantile(p, C.byref(out)), "isr_normal_quantile")
     return out.value
+
+
+def isr_discrete_quantile(sigma: int, p_lower: float):
+    """(t, t*t or 0): discrete-Gaussian quantile in grid units and the squared radius."""
+    t, r2 = C.c_int32(0), C.c_uint64(0)
+    _check(lib().isr_discrete_quantile(sigma, p_lower, C.byref(t), C.byref(r2)), "isr_discrete_quantile")
+    return t.value, r2.value
 
 
 def isr_binom_pvalue(n_a: int, n_b: int) -> float:

@@ -1,6 +1,7 @@
 // C ABI: model loading, workspace planning and the Monte-Carlo driver that
 // enqueues noise -> layers -> vote kernels for chunks of sample indices.
 #include <algorithm>
+#include <cmath>
 #include <cstdlib>
 #include <cstring>
 #include <map>
@@ -600,6 +601,21 @@ int isr_load_model(const void *blob_host, size_t bytes, isr_model **out) {
 int isr_set_fusion(isr_model *m, int enable) {
     if (!m) return ISR_ERR_ARG;
     m->use_fused = enable ? 1 : 0;
+    return ISR_OK;
+}
+
+int isr_discrete_quantile(uint32_t sigma, double p_lower, int32_t *t_out, uint64_t *radius_sq_out) {
+    if (sigma < 1 || sigma > 1024 || !(p_lower >= 0.0 && p_lower <= 1.0)) return ISR_ERR_ARG;
+    std::vector<uint64_t> T;
+    uint32_t R = 0;
+    if (!build_noise_table(sigma, T, R)) return ISR_ERR_ARG;
+    // floor(2^64 p): exact for a double below 1 (53 significant bits, scaled by a power of two)
+    const uint64_t u = p_lower >= 1.0 ? ~0ull : (uint64_t)std::ldexp(p_lower, 64);
+    // thresholds ascend: the number of entries <= u by binary search
+    const int64_t below = std::upper_bound(T.begin(), T.end(), u) - T.begin();
+    const int64_t t = -(int64_t)R - 1 + below;
+    if (t_out) *t_out = (int32_t)t;
+    if (radius_sq_out) *radius_sq_out = t > 0 ? (uint64_t)(t * t) : 0;
     return ISR_OK;
 }
 

@@ -131,3 +131,25 @@ def test_validate_model_accepts_workloads_and_rejects_damage():
     u = b.conv(t, 4, 3, 1, 1, True)
     b.fc(b.gap(u), 3)
     assert isr.isr_validate_model(b.blob()) == isr.ISR_ERR_UNSUPPORTED
+
+
+def test_discrete_quantile_matches_the_oracle():
+    """Integer-only certification tail (Thm 3.2): the library's table lookup against
+    the oracle's on random levels, levels next to table entries, and the edges."""
+    from oracle import stats
+    rng = np.random.default_rng(77)
+    for sigma in (1, 2, 32, 64, 128, 256, 1024):
+        T, R = oracle.noise_table(sigma)
+        ps = list(rng.uniform(0.0, 1.0, 30)) + [0.0, 0.5, 1.0, 1 - 2.0 ** -53, 2.0 ** -60]
+        # levels at and just around a few table entries (floor(2^64 p) == T[i] exactly where representable)
+        for i in rng.integers(0, len(T), 6):
+            ps.append(float(int(T[i]) >> 11 << 11) / 2.0 ** 64)
+        for p in ps:
+            t, r2 = isr.isr_discrete_quantile(sigma, float(p))
+            want = stats.discrete_quantile(sigma, float(p))
+            assert t == want, (sigma, p, t, want)
+            assert r2 == stats.radius_squared_int(sigma, float(p))
+    with pytest.raises(isr.IsrError):
+        isr.isr_discrete_quantile(0, 0.9)
+    with pytest.raises(isr.IsrError):
+        isr.isr_discrete_quantile(32, 1.5)
