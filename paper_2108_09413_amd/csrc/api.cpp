@@ -37,6 +37,8 @@ struct DevOp {
     double ops_per_sample = 0.0, bytes_per_sample = 0.0;   // algorithmic, for the timing report
     ConvParams conv{};
     int stem_pool = 0;                  // conv fused with the max pooling after it (out = the pooled tensor)
+    int block = 0;                      // identity residual block: this conv, conv2 and the add in one kernel
+    ConvParams conv2{};
     AddParams add{};
     PoolParams pool{};
     GapParams gap{};
@@ -220,6 +222,34 @@ void fuse_adds(const ParsedModel &pm, const std::vector<DevOp> &plain, std::vect
             }
         }
         fused.push_back(d);
+    }
+}
+
+// Folds conv3x3 -> conv3x3 -> add-with-the-block-input (identity residual block) into one
+// kernel for the shapes that fit LDS whole.  Runs on the list in which the add is already
+// folded into the second convolution.
+void fuse_basic_blocks(const ParsedModel &pm, std::vector<DevOp> &ops) {
+    std::vector<int> uses(pm.tensors.size(), 0);
+    for (const DevOp &d : ops) {
+        if (d.a >= 0) uses[d.a]++;
+        if (d.b >= 0) uses[d.b]++;
+    }
+    for (size_t i = 0; i + 1 < ops.size(); ++i) {
+        DevOp &a = ops[i];
+        const DevOp &b = ops[i + 1];
+        if (a.type != OP_CONV || b.type != OP_CONV || a.stem_pool || a.block || a.conv.fuse_add || b.conv.fuse_add != 1) continue;
+        const ConvParams &ca = a.conv, &cb = b.conv;
+        auto is3x3 = [](const ConvParams &c) { return c.k == 3 && c.stride == 1 && c.pad == 1 && !c.c4 && c.fast_requant; };
+        if (!is3x3(ca) || !is3x3(cb) || b.a != a.out || b.b != a.a || uses[a.out] != 1) continue;
+        if (ca.Cin_p != ca.Cout_p || cb.Cin_p != ca.Cout_p || cb.Cout_p != ca.Cout_p || ca.H != ca.W || ca.Ho != ca.H ||
+            !basic_block_supported(ca.Cout_p, ca.H))
+            continue;
+        a.block = 1;
+        a.conv2 = cb;
+        a.ops_per_sample += b.ops_per_sample;
+        a.bytes_per_sample = (double)pm.tensors[a.a].C * ca.H * ca.W + (double)pm.tensors[b.out].C * ca.H * ca.W;
+        a.out = b.out;
+        ops.erase(ops.begin() + i + 1);
     }
 }
 
@@ -477,6 +507,22 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
                         HIP_TRY(launch_stem_pool(sp, m->stream));
                         break;
                     }
+                    if (d.block) {
+                        const ConvParams &c1 = d.conv, &c2 = d.conv2;
+                        BlockParams bp;
+                        bp.in = (const int8_t *)(ws + pl.toff[d.a]);
+                        bp.out = (int8_t *)(ws + pl.toff[d.out]);
+                        bp.w1 = c1.w; bp.bias1 = c1.bias; bp.m0s1 = c1.m0s; bp.chi1 = c1.chi; bp.shm11 = c1.shm1;
+                        bp.w2 = c2.w; bp.bias2 = c2.bias; bp.m0s2 = c2.m0s; bp.chi2 = c2.chi; bp.shm12 = c2.shm1;
+                        bp.C = c1.Cout_p; bp.S = c1.H; bp.B = (int32_t)cnt;
+                        bp.zp_x = c1.zp_in; bp.zp_t = c1.zp_out; bp.relu1 = c1.relu;
+                        bp.zp_u = c2.zp_out; bp.relu2 = c2.relu;
+                        bp.add_mul_self = c2.add_mul_self; bp.add_mul_res = c2.add_mul_res; bp.add_c0 = c2.add_c0;
+                        bp.add_k = c2.add_k; bp.add_sh = c2.add_sh; bp.add_lo = c2.add_lo;
+                        bp.tie_free = c1.tie_free && c2.tie_free && c2.add_tie_free;
+                        HIP_TRY(launch_basic_block(bp, m->stream));
+                        break;
+                    }
                     ConvParams c = d.conv;
                     c.in = (const int8_t *)(ws + pl.toff[d.a]);
                     c.out = (int8_t *)(ws + pl.toff[d.out]);
@@ -594,6 +640,7 @@ int isr_load_model(const void *blob_host, size_t bytes, isr_model **out) {
     m->plan[0].ops = m->ops;
     fuse_adds(m->pm, m->ops, m->plan[1].ops);
     fuse_stem_pool(m->pm, m->plan[1].ops);
+    fuse_basic_blocks(m->pm, m->plan[1].ops);
     *out = m;
     return ISR_OK;
 }

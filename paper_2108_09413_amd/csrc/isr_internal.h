@@ -109,6 +109,21 @@ struct StemPoolParams {
     int32_t zp_in, zp_out, relu, tie_free, B;
 };
 
+// Identity residual block in one kernel: t = conv3x3(x), y = add(conv3x3(t), x); both
+// convolutions C -> C channels, stride 1, pad 1, on S x S images (basic_block.hip).
+struct BlockParams {
+    const int8_t *in;        // [B][S][S][C] block input x (also the residual)
+    int8_t *out;             // [B][S][S][C]
+    const int8_t *w1, *w2;   // [>= C][Kp] each, K = (tap, channel), Kp = 9 C rounded up to 64
+    const int32_t *bias1, *m0s1, *chi1, *shm11;   // first convolution, as in ConvParams
+    const int32_t *bias2, *m0s2, *chi2, *shm12;   // second convolution
+    int32_t C, S, B;
+    int32_t zp_x, zp_t, relu1;   // zero-points of x and t; lower clamp of t is zp_t when relu1
+    int32_t zp_u, relu2;         // the same for the second convolution's own int8 result
+    int32_t add_mul_self, add_mul_res, add_c0, add_k, add_sh, add_lo;   // as in ConvParams
+    int32_t tie_free;            // both convolutions and the add are free of rounding ties
+};
+
 struct AddParams {
     const int8_t *a, *b;
     int8_t *out;
@@ -153,6 +168,8 @@ hipError_t launch_conv(const ConvParams &p, hipStream_t st);
 hipError_t launch_stem_pool(const StemPoolParams &p, hipStream_t st);
 bool stem_pool_supported(int k, int stride, int pad, int cout_p, int H, int W, int fast_requant, int pool_k,
                          int pool_stride, int pool_pad);
+hipError_t launch_basic_block(const BlockParams &p, hipStream_t st);
+bool basic_block_supported(int channels, int size);
 hipError_t launch_add(const AddParams &p, hipStream_t st);
 hipError_t launch_maxpool(const PoolParams &p, hipStream_t st);
 hipError_t launch_gap(const GapParams &p, hipStream_t st);

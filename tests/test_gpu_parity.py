@@ -143,6 +143,43 @@ def test_first_layer_fused_with_max_pooling(isr, shape):
     _check_all_tensors(isr, b.blob(), x, 64, sample=3, chunk=5)
 
 
+def test_identity_residual_blocks_in_one_kernel(isr):
+    """conv3x3 -> conv3x3 -> add with the block input, at the three shapes that run as one
+    LDS-resident kernel (16 channels at 32x32, 32 at 16x16, 64 at 8x8): non-trivial zero-points
+    on every tensor, ReLU on and off, power-of-two multipliers (rounding ties) in one block,
+    7 copies (ragged against 2 and 4 images per workgroup)."""
+    _say("layer parity fused identity blocks")
+    rng = np.random.default_rng(71)
+    b = NetBuilder(rng=np.random.default_rng(72), in_shape=(3, 32, 32), num_classes=6)
+    t = b.conv(b.tensor(3, 32, 32, 0, 74.0), 16, 3, 1, 1, True)
+    def block(t, ch, relu1, relu_out, z1, z2, zo, pow2=False):
+        m0 = np.full(ch, 1 << 30, dtype=np.int64) if pow2 else None
+        u = b.conv(t, ch, 3, 1, 1, relu1, zp_out=z1, m0=m0, sh=np.full(ch, 9) if pow2 else None)
+        u = b.conv(u, ch, 3, 1, 1, False, zp_out=z2)
+        if pow2:
+            return b.add(t, u, relu_out, ma=1 << 19, mb=1 << 19, sh=20, zp_out=zo)
+        return b.add(t, u, relu_out, zp_out=zo)
+    t = block(t, 16, True, True, -128, 0, -128)
+    t = block(t, 16, False, False, 7, -5, 3)
+    t = block(t, 16, True, True, -100, 9, -120, pow2=True)
+    t = b.conv(t, 32, 3, 2, 1, True)
+    t = block(t, 32, True, False, -128, 4, -2)
+    t = block(t, 32, False, True, 11, 0, -128, pow2=True)
+    t = b.conv(t, 64, 3, 2, 1, True)
+    t = block(t, 64, True, True, -128, 0, -128)
+    t = block(t, 64, False, False, -9, 13, 6)
+    b.fc(b.gap(t), 6)
+    blob = b.blob()
+    x = np.random.default_rng(11).integers(0, 256, size=(3, 32, 32)).astype(np.uint8)
+    _check_all_tensors(isr, blob, x, 64, sample=4, chunk=3)
+    m = _load(isr, blob, 7)
+    om = oracle.Model(blob)
+    lg, am, cnt = isr.isr_debug_forward(m, x, 64, 2, 1, 1, 100, 7)
+    olg, oam, ocnt = om.mc(x, 64, 2, 1, 1, 100, 7)
+    assert np.array_equal(lg, olg) and np.array_equal(cnt, ocnt)
+    m.close()
+
+
 def test_residual_computed_by_a_second_convolution(isr):
     """Projection-shortcut pattern: the residual of an add is the output of a 1x1
     convolution issued right before the add's other convolution; the fused plan then
