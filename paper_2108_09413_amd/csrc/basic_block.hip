@@ -2,11 +2,13 @@
 //   t = clamp(requant(conv3x3(x)));  y = add_requant(clamp(requant(conv3x3(t))), x)
 // (both convolutions stride 1, pad 1, C -> C channels, S x S pixels).  A workgroup keeps
 // NI whole images in LDS -- x and t as (S+2) x (S+2) x C int8 tiles whose border holds the
-// tensor's zero-point, so taps need no bounds checks and contribute 0 -- together with both
-// weight matrices; t never leaves the CU and x is read from HBM once for both the first
-// convolution and the residual.  The 16 K-bytes of an MFMA operand lane are 16 channels of
-// one tap: one aligned 128-bit LDS read at (pixel + tap offset) * C, no gather through the
-// texture path.  C = 16 uses v_mfma_i32_16x16x64_i8, C = 32 / 64 v_mfma_i32_32x32x32_i8.
+// tensor's zero-point, so taps need no bounds checks and contribute 0; t never leaves the
+// CU and x is read from HBM once for both the first convolution and the residual.  The
+// weight fragments a wave needs do not depend on the pixel fragment: it reads them from
+// global memory (L2-resident, a few KiB) once per convolution into registers; with 64
+// channels the two M fragments are split over the waves so that they fit.  The 16 K-bytes
+// of an MFMA operand lane are 16 channels of one tap: one aligned 128-bit LDS read at
+// (pixel + tap offset) * C, no gather through the texture path.  C = 16 uses v_mfma_i32_16x16x64_i8, C = 32 / 64 v_mfma_i32_32x32x32_i8.
 #include "conv_device.h"
 
 namespace isr {
@@ -17,9 +19,9 @@ template <int C, int S, int NI, bool TF>
 __global__ __launch_bounds__(256) void basic_block_kernel(const BlockParams p) {
     constexpr int P = S + 2;                         // padded tile edge
     constexpr int KP = (9 * C + 63) / 64 * 64;       // K bytes per weight row in global memory
-    constexpr int WR = KP + 16;                      // weight row stride in LDS (spreads rows over the banks)
     constexpr int MT = C == 16 ? 16 : 32;            // MFMA tile edge
     constexpr int MF = C / MT;                       // M fragments
+    constexpr int MSPLIT = MF;                       // waves that share one pixel fragment, one M fragment each
     constexpr int NF = S * S / MT;                   // pixel fragments per image
     constexpr int KS = C == 16 ? KP / 64 : KP / 32;  // K steps
     constexpr int ACC = MT == 16 ? 4 : 16;
@@ -29,17 +31,12 @@ __global__ __launch_bounds__(256) void basic_block_kernel(const BlockParams p) {
 
     __shared__ __attribute__((aligned(16))) int8_t X[NI][P * P * C];
     __shared__ __attribute__((aligned(16))) int8_t T[NI][P * P * C];
-    __shared__ __attribute__((aligned(16))) int8_t W[2][C * WR];
     __shared__ int prm[2][4][C];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const long img0 = (long)blockIdx.x * NI;
 
-    // ---- stage weights, per-channel constants, the images and the borders ----
-    for (int i = tid; i < 2 * C * (KP / 16); i += 256) {
-        const int cv = i / (C * (KP / 16)), j = i % (C * (KP / 16)), r = j / (KP / 16), c = j % (KP / 16);
-        *(v4i *)(&W[cv][r * WR + c * 16]) = *(const v4i *)((cv ? p.w2 : p.w1) + (long)r * KP + c * 16);
-    }
+    // ---- stage per-channel constants, the images and the borders ----
     for (int i = tid; i < 2 * C; i += 256) {
         const int cv = i / C, c = i % C;
         prm[cv][0][c] = (cv ? p.bias2 : p.bias1)[c];
@@ -74,18 +71,21 @@ __global__ __launch_bounds__(256) void basic_block_kernel(const BlockParams p) {
     constexpr int CPS = 64 / MT == 4 ? 4 : 2;        // 16-byte chunks per K step (4 for 16x16x64, 2 for 32x32x32)
     const int ocl = MT == 16 ? 4 * kg : 16 * kg;     // first output channel (within an M fragment) this lane holds
 
-    // One 3x3 convolution over all NI images from the padded tile `src`, weights W[cv];
+    // One 3x3 convolution over all NI images from the padded tile `src`, weights `w`;
     // `emit(image, pixel, m fragment, accumulators)` consumes each fragment.
-    auto conv = [&](const int8_t (*src)[P * P * C], int cv, auto emit) {
-        for (int f = wave; f < NI * NF; f += 4) {
+    const int mf = wave % MSPLIT;                    // this wave's M fragment
+    auto conv = [&](const int8_t (*src)[P * P * C], int cv, const int8_t *w, auto emit) {
+        v4i fa[KS];                                  // the wave's weight fragments, all K steps
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) fa[ks] = *(const v4i *)(w + (long)(mf * MT + l) * KP + (ks * CPS + kg) * 16);
+        acc_t binit;
+#pragma unroll
+        for (int i = 0; i < ACC; ++i) binit[i] = prm[cv][0][mf * MT + ocl + i];
+        for (int f = wave / MSPLIT; f < NI * NF; f += 4 / MSPLIT) {
             const int im = f / NF, pix = (f % NF) * MT + l;
             const int y = pix / S, x = pix % S;
             const int8_t *base = &src[im][(y * P + x) * C];   // tap (0, 0) of this pixel in the padded tile
-            acc_t acc[MF];
-#pragma unroll
-            for (int mf = 0; mf < MF; ++mf)
-#pragma unroll
-                for (int i = 0; i < ACC; ++i) acc[mf][i] = prm[cv][0][mf * MT + ocl + i];
+            acc_t acc = binit;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 const int j = ks * CPS + kg;              // 16-byte K chunk: tap j / CH, channel chunk j % CH
@@ -93,21 +93,16 @@ __global__ __launch_bounds__(256) void basic_block_kernel(const BlockParams p) {
                 const int cc = j % CH;
                 if (tap > 8) tap = 0;                     // K padding: zero weights, any readable address
                 const v4i fb = *(const v4i *)(base + ((tap / 3) * P + tap % 3) * C + cc * 16);
-#pragma unroll
-                for (int mf = 0; mf < MF; ++mf) {
-                    const v4i fa = *(const v4i *)(&W[cv][(mf * MT + l) * WR + j * 16]);
-                    if constexpr (MT == 16) acc[mf] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa, fb, acc[mf], 0, 0, 0);
-                    else acc[mf] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa, fb, acc[mf], 0, 0, 0);
-                }
+                if constexpr (MT == 16) acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[ks], fb, acc, 0, 0, 0);
+                else acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[ks], fb, acc, 0, 0, 0);
             }
-#pragma unroll
-            for (int mf = 0; mf < MF; ++mf) emit(im, pix, mf, acc[mf]);
+            emit(im, pix, mf, acc);
         }
     };
 
     // ---- first convolution: requantise, clamp, into the interior of T ----
     const int lo1 = p.relu1 ? p.zp_t : -128;
-    conv(X, 0, [&](int im, int pix, int mf, const acc_t &a) {
+    conv(X, 0, p.w1, [&](int im, int pix, int mf, const acc_t &a) {
         const int c0 = mf * MT + ocl;
         int q[ACC];
 #pragma unroll
@@ -126,7 +121,7 @@ __global__ __launch_bounds__(256) void basic_block_kernel(const BlockParams p) {
     ConvParams ap{};   // the fused add reads its constants from here
     ap.add_mul_self = p.add_mul_self; ap.add_mul_res = p.add_mul_res; ap.add_c0 = p.add_c0; ap.add_k = p.add_k;
     ap.add_sh = p.add_sh; ap.add_lo = p.add_lo;
-    conv(T, 1, [&](int im, int pix, int mf, const acc_t &a) {
+    conv(T, 1, p.w2, [&](int im, int pix, int mf, const acc_t &a) {
         const int c0 = mf * MT + ocl;
         const long g = img0 + im;
         const int8_t *res = &X[im][((pix / S + 1) * P + pix % S + 1) * C + c0];
