@@ -44,6 +44,10 @@ def main():
     ap.add_argument("--workload", default="resnet50", choices=sorted(WORKLOADS))
     ap.add_argument("--chunk", type=int, default=0, help="noisy copies per device chunk (0 = default)")
     ap.add_argument("--n", type=int, default=0, help="override estimation samples per step")
+    ap.add_argument("--mode", default="certify", choices=["certify", "predict"],
+                    help="procedure a step runs: Alg. 1 (n0 + n samples) or Alg. 2 (n samples)")
+    ap.add_argument("--batch", type=int, default=1,
+                    help="(image, sigma) pairs per step; above 1 a step is one batched call over that many pairs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference for HBM byte counters)")
@@ -78,8 +82,20 @@ def main():
     for s in cfg["sigmas"]:
         isr.isr_certify(model, images[0], s, 1, 1, alpha, want_counts=False)
 
+    if args.mode == "predict":
+        n0 = 0
+    image_array = torch.stack(images)
+
     def step(k):
+        if args.batch > 1:
+            items = [(pairs[j % len(pairs)][0], pairs[j % len(pairs)][1], pairs[j % len(pairs)][0] + 1)
+                     for j in range(k * args.batch, (k + 1) * args.batch)]
+            if args.mode == "predict":
+                return isr.isr_predict_batch(model, image_array, items, n, alpha, seed=0)[0][-1]
+            return isr.isr_certify_batch(model, image_array, items, n0, n, alpha, seed=0)[0][-1]
         i, s = pairs[k % len(pairs)]
+        if args.mode == "predict":
+            return isr.isr_predict(model, images[i], s, n, alpha, seed=0, image_id=i + 1)[0]
         return isr.isr_certify(model, images[i], s, n0, n, alpha, seed=0, image_id=i + 1, want_counts=False)[0]
 
     if args.copy_calibration_mib:
@@ -102,7 +118,7 @@ def main():
     stats = isr.isr_profile_read(model)
     isr.isr_profile(model, 0)
 
-    inferences = args.steps * (n0 + n)
+    inferences = args.steps * args.batch * (n0 + n)
     value = inferences / dt
     conv = [s for s in stats if s["name"].startswith("conv")]
     conv_ms = sum(s["total_ms"] for s in conv)
@@ -166,11 +182,12 @@ def main():
         "ms_per_step": round(dt / args.steps * 1e3, 2), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": f"config {cfg_id} ({cfg['name']}): {cfg['arch']} int8, input "
-                               f"{'x'.join(map(str, cfg['shape']))}, {cfg['classes']} classes; one step = certify "
-                               f"one (image, sigma) pair with n0={n0}, n={n}, alpha={alpha}; pairs cycle over "
+                               f"{'x'.join(map(str, cfg['shape']))}, {cfg['classes']} classes; one step = {args.mode} "
+                               f"{args.batch if args.batch > 1 else 'one'} (image, sigma) pair{'s in one batched call' if args.batch > 1 else ''} "
+                               f"with n0={n0}, n={n}, alpha={alpha}; pairs cycle over "
                                f"{n_img} images x sigma {list(cfg['sigmas'])}",
                    "chunk_samples": chunk, "macs_per_inference": macs},
-        "certified_images_per_s": round(args.steps / dt, 4),
+        "certified_images_per_s": round(args.steps * args.batch / dt, 4),
         "whole_path_int8_tops": round(2.0 * macs * value / 1e12, 2),
         "whole_path_frac_of_int8_peak": round(2.0 * macs * value / 1e12 / INT8_MFMA_PEAK_TOPS, 4),
         "roofline": roofline,

@@ -101,6 +101,35 @@ int isr_certify(isr_model *m, const uint8_t *x_device, uint32_t sigma, uint32_t 
 int isr_predict(isr_model *m, const uint8_t *x_device, uint32_t sigma, uint32_t n, double alpha,
                 uint64_t seed, uint32_t image_id, isr_result *out, uint32_t *counts_host);
 
+/* ---- the two procedures over many (image, sigma) pairs at once ------------- */
+
+/* One pair of a batched call: which image of the array, which noise level, and
+ * the image_id word of its random stream. */
+typedef struct isr_item {
+    uint32_t image;    /* index into x_device, < n_images */
+    uint32_t sigma;    /* 1..1024 grid units */
+    uint32_t image_id;
+} isr_item;
+
+/* Alg. 1 / Alg. 2 for n_items (image, sigma) pairs in one pass -- the sweeps of the
+ * paper's evaluation (many test images, certification sigma varied against the
+ * training sigma, prediction with small n as in the appendix table of Alg. 2's
+ * sample sizes).  x_device: uint8 [n_images][C][H][W] in device memory;
+ * items_host: n_items descriptors (host); at most 8 distinct sigma values per
+ * call.  All pairs share n0, n, alpha and seed.  out_host[i], and row i of the
+ * optional uint32 [n_items][classes] vote arrays (host), are exactly what
+ * isr_certify / isr_predict return for (x[items[i].image], items[i].sigma, n0, n,
+ * alpha, seed, items[i].image_id).  The sample slots of all pairs form one list
+ * that is cut into chunks of chunk_samples regardless of pair boundaries, so a
+ * call with small n per pair still launches full chunks.  ISR_ERR_ARG for an
+ * image index or sigma out of range, more than 8 distinct sigmas, n_items == 0. */
+int isr_certify_batch(isr_model *m, const uint8_t *x_device, uint32_t n_images, const isr_item *items_host,
+                      uint32_t n_items, uint32_t n0, uint32_t n, double alpha, uint64_t seed,
+                      isr_result *out_host, uint32_t *counts0_host, uint32_t *counts1_host);
+int isr_predict_batch(isr_model *m, const uint8_t *x_device, uint32_t n_images, const isr_item *items_host,
+                      uint32_t n_items, uint32_t n, double alpha, uint64_t seed, isr_result *out_host,
+                      uint32_t *counts_host);
+
 /* ---- parity / resume hooks (sample-index ranges are reproducible) -------- */
 
 /* Noisy copies for sample indices [sample_begin, sample_begin+count) of one
@@ -150,6 +179,17 @@ int isr_binom_pvalue(uint32_t n_a, uint32_t n_b, double *pvalue);
 int isr_decide_certify(const uint32_t *counts0, const uint32_t *counts1, uint32_t classes,
                        double sigma, uint32_t n, double alpha, isr_result *out);
 int isr_decide_predict(const uint32_t *counts, uint32_t classes, double alpha, isr_result *out);
+
+/* The paper's two evaluation metrics (section "Evaluation Metrics") over `count`
+ * certification results with ground-truth labels (host arrays):
+ *   certified percentage  CP    = #{i : not abstained} / count
+ *   certified accuracy    CA(r) = #{i : not abstained, cls_i == label_i, radius_i >= r} / #{i : not abstained}
+ * (the denominator of CA as in the paper's formula; CA(r) * CP is the fraction of
+ * the whole set; CA = 0 when every result abstained).  cp_out may be NULL; ca_out
+ * gets n_radii values for the thresholds radii[] (same unit as isr_result.radius);
+ * n_radii may be 0, then labels, radii and ca_out may be NULL. */
+int isr_certified_metrics(const isr_result *results, const int32_t *labels, uint32_t count, const double *radii,
+                          uint32_t n_radii, double *cp_out, double *ca_out);
 
 /* Kernel-variant switch for parity checks: enable != 0 (the default) lets the
  * library fuse ops of the blob into one kernel where it can (a residual add into

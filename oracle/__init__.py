@@ -176,3 +176,14 @@ def predict(model: Model, x, sigma, n, alpha, seed=0, image=0, threads=None):
     _, _, counts = model.mc(x, sigma, seed, image, 0, 0, n, threads, want_logits=False)
     cls, pv, n_a, n_b = stats.predict_decision(counts, alpha)
     return cls, pv, n_a, n_b, counts
+
+
+def certify_batch(model: Model, xs, items, n0, n, alpha, seed=0, threads=None):
+    """Alg. 1 for a list of (image index, sigma, image id) pairs: by definition the
+    single-pair procedure applied to each pair in turn.  Returns a list of certify() tuples."""
+    return [certify(model, xs[i], sigma, n0, n, alpha, seed, image_id, threads) for i, sigma, image_id in items]
+
+
+def predict_batch(model: Model, xs, items, n, alpha, seed=0, threads=None):
+    """Alg. 2 for a list of (image index, sigma, image id) pairs, one pair after the other."""
+    return [predict(model, xs[i], sigma, n, alpha, seed, image_id, threads) for i, sigma, image_id in items]

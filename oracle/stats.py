@@ -91,3 +91,25 @@ def predict_decision(counts, alpha: float):
     n_a = int(counts[c_a])
     pv = binom_pvalue(n_a, n_b)
     return (c_a if pv <= alpha else ABSTAIN), pv, n_a, n_b
+
+
+def certified_percentage(classes) -> float:
+    """Certified percentage CP (section "Evaluation Metrics", first formula): the share
+    of the L inputs whose certification did not abstain.  classes: the returned class
+    per input, ABSTAIN where the procedure abstained."""
+    classes = list(classes)
+    return sum(1 for c in classes if c != ABSTAIN) / len(classes)
+
+
+def certified_accuracy(classes, radii, labels, r: float) -> float:
+    """Certified accuracy CA at radius r (section "Evaluation Metrics", second formula):
+    among the inputs that did not abstain, the share with the correct class and a
+    certified radius of at least r.  The denominator is the number of non-abstaining
+    inputs, as the formula prints it (the sentence before it says "fraction of the test
+    set"; CA * CP is that fraction); 0 when every input abstained."""
+    classes, radii, labels = list(classes), list(radii), list(labels)
+    certified = [i for i, c in enumerate(classes) if c != ABSTAIN]
+    if not certified:
+        return 0.0
+    good = [i for i in certified if classes[i] == labels[i] and radii[i] >= r]
+    return len(good) / len(certified)

@@ -23,7 +23,7 @@ EXPORTS = [
     "isr_set_workspace", "isr_certify", "isr_predict", "isr_debug_noisy", "isr_debug_forward",
     "isr_debug_tensor", "isr_noise_table", "isr_cp_lower", "isr_normal_quantile", "isr_binom_pvalue",
     "isr_decide_certify", "isr_decide_predict", "isr_discrete_quantile", "isr_set_fusion", "isr_set_conv_tile", "isr_profile", "isr_profile_read", "isr_strerror",
-    "isr_last_device_error",
+    "isr_last_device_error", "isr_certify_batch", "isr_predict_batch", "isr_certified_metrics",
 ]
 
 
@@ -43,6 +43,10 @@ class Result(C.Structure):
     def __repr__(self):
         return (f"Result(cls={self.cls}, radius={self.radius!r}, p_lower={self.p_lower!r}, "
                 f"n_top={self.n_top}, n_second={self.n_second})")
+
+
+class Item(C.Structure):
+    _fields_ = [("image", C.c_uint32), ("sigma", C.c_uint32), ("image_id", C.c_uint32)]
 
 
 class KernelStat(C.Structure):
@@ -81,6 +85,9 @@ def lib():
         L.isr_discrete_quantile.argtypes = [u32, dbl, C.POINTER(i32), C.POINTER(u64)]
         L.isr_decide_certify.argtypes = [vp, vp, u32, dbl, u32, dbl, C.POINTER(Result)]
         L.isr_decide_predict.argtypes = [vp, u32, dbl, C.POINTER(Result)]
+        L.isr_certify_batch.argtypes = [vp, vp, u32, C.POINTER(Item), u32, u32, u32, dbl, u64, C.POINTER(Result), vp, vp]
+        L.isr_predict_batch.argtypes = [vp, vp, u32, C.POINTER(Item), u32, u32, dbl, u64, C.POINTER(Result), vp]
+        L.isr_certified_metrics.argtypes = [C.POINTER(Result), vp, u32, vp, u32, C.POINTER(dbl), vp]
         L.isr_set_fusion.argtypes = [vp, C.c_int]
         L.isr_set_conv_tile.argtypes = [vp, C.c_int]
         L.isr_profile.argtypes = [vp, u32]
@@ -158,6 +165,19 @@ def isr_decide_predict(counts, alpha: float) -> Result:
     res = Result()
     _check(lib().isr_decide_predict(_np_ptr(c), c.size, alpha, C.byref(res)), "isr_decide_predict")
     return res
+
+
+def isr_certified_metrics(results, labels, radii):
+    """(CP, CA at each radius) of a list of Result against ground-truth labels."""
+    arr = (Result * len(results))(*results)
+    lab = np.ascontiguousarray(labels, dtype=np.int32)
+    rad = np.ascontiguousarray(radii, dtype=np.float64)
+    assert lab.size == len(results)
+    cp = C.c_double(0)
+    ca = np.zeros(rad.size, dtype=np.float64)
+    _check(lib().isr_certified_metrics(arr, _np_ptr(lab), len(results), _np_ptr(rad), rad.size, C.byref(cp), _np_ptr(ca)),
+           "isr_certified_metrics")
+    return cp.value, ca
 
 
 # ---- device entry points ----------------------------------------------------
@@ -242,6 +262,39 @@ def isr_predict(model: Model, x, sigma: int, n: int, alpha: float, seed: int = 0
     _check(lib().isr_predict(model.handle, C.c_void_p(x.data_ptr()), sigma, n, alpha, C.c_uint64(seed), image_id,
                              C.byref(res), _np_ptr(c)), "isr_predict")
     return res, c
+
+
+def _dev_images(xs):
+    """uint8 [n][C][H][W] image array on the device."""
+    import torch
+    if isinstance(xs, np.ndarray):
+        xs = torch.from_numpy(np.ascontiguousarray(xs, dtype=np.uint8)).cuda()
+    assert xs.dtype == torch.uint8 and xs.is_cuda and xs.is_contiguous() and xs.dim() == 4
+    return xs
+
+
+def _items(items):
+    return (Item * len(items))(*[Item(int(i), int(s), int(d)) for i, s, d in items])
+
+
+def isr_certify_batch(model: Model, xs, items, n0: int, n: int, alpha: float, seed: int = 0):
+    """items: list of (image index, sigma, image_id).  Returns (results, counts0, counts1)."""
+    xs = _dev_images(xs)
+    res = (Result * len(items))()
+    c0 = np.zeros((len(items), model.classes), dtype=np.uint32)
+    c1 = np.zeros((len(items), model.classes), dtype=np.uint32)
+    _check(lib().isr_certify_batch(model.handle, C.c_void_p(xs.data_ptr()), xs.shape[0], _items(items), len(items), n0, n,
+                                   alpha, C.c_uint64(seed), res, _np_ptr(c0), _np_ptr(c1)), "isr_certify_batch")
+    return list(res), c0, c1
+
+
+def isr_predict_batch(model: Model, xs, items, n: int, alpha: float, seed: int = 0):
+    xs = _dev_images(xs)
+    res = (Result * len(items))()
+    c = np.zeros((len(items), model.classes), dtype=np.uint32)
+    _check(lib().isr_predict_batch(model.handle, C.c_void_p(xs.data_ptr()), xs.shape[0], _items(items), len(items), n,
+                                   alpha, C.c_uint64(seed), res, _np_ptr(c)), "isr_predict_batch")
+    return list(res), c
 
 
 def isr_debug_noisy(model: Model, x, sigma: int, seed: int, image_id: int, phase: int, sample_begin: int, count: int):

@@ -78,6 +78,10 @@ struct isr_model {
     int table_next = 0;
     uint32_t *dcounts = nullptr;        // 2 * classes
     uint32_t *hcounts = nullptr;        // pinned, 2 * classes
+    // batched calls: item descriptors and per-item vote counters, grown on demand
+    NoiseItem *ditems = nullptr, *hitems = nullptr;
+    uint32_t *dcounts_b = nullptr, *hcounts_b = nullptr;   // 2 * items_cap * classes each
+    uint32_t items_cap = 0;
     // workspace
     uint8_t *ws = nullptr;
     size_t ws_bytes = 0;
@@ -455,17 +459,29 @@ int get_table(isr_model *m, uint32_t sigma, const DeviceNoiseTable **out) {
     return ISR_OK;
 }
 
+// A batched call: items (device array) that own n_per_item consecutive slots each.
+struct BatchCtx {
+    const NoiseItem *items;
+    uint32_t n_items, n_per_item;
+};
+
 // Enqueues the Monte-Carlo loop for sample indices [begin, begin+count) of one
 // phase.  Optional outputs: per-sample logits / argmax (device buffers inside
 // the workspace, copied to the host pointers chunk by chunk) and the device
 // vote counters.  stop_tensor >= 0 ends each forward right after that tensor.
+// With `bc` the loop runs over the n_items * n_per_item slots of a batch instead
+// (x = the image array, table = the table array, dcounts = [items][classes];
+// image / begin / count are ignored): chunks are cut from the slot list without
+// regard to item boundaries, so short per-item runs still fill the device.
 int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseTable *table, uint64_t seed,
-              uint32_t image, uint32_t phase, uint32_t begin, uint32_t count, int32_t *logits_host,
-              int32_t *argmax_host, uint32_t *dcounts, int stop_tensor) {
+              uint32_t image, uint32_t phase, uint32_t begin, uint64_t count, int32_t *logits_host,
+              int32_t *argmax_host, uint32_t *dcounts, int stop_tensor, const BatchCtx *bc = nullptr) {
     const ParsedModel &pm = m->pm;
     uint8_t *ws = m->ws;
-    for (uint32_t done = 0; done < count;) {
-        const uint32_t cnt = std::min(m->chunk, count - done);
+    if (bc) count = (uint64_t)bc->n_items * bc->n_per_item;
+    for (uint64_t done = 0; done < count;) {
+        uint32_t cnt = (uint32_t)std::min<uint64_t>(m->chunk, count - done);
+        if (bc) cnt = (uint32_t)std::min<uint64_t>(cnt, (uint64_t)bc->n_per_item * 65534);   // one grid row per item
         const bool timed = m->profile_every && (m->chunk_counter++ % m->profile_every) == 0;
         size_t ev = 0;
         std::vector<int> ev_class;
@@ -486,7 +502,13 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
         np.x = x; np.table = table; np.out = (int8_t *)(ws + pl.toff[0]);
         np.C = pm.C; np.H = pm.H; np.W = pm.W;
         np.key0 = (uint32_t)seed; np.key1 = (uint32_t)(seed >> 32);
-        np.image = image; np.phase = phase; np.sample_begin = begin + done; np.count = cnt;
+        np.image = image; np.phase = phase; np.sample_begin = begin + (uint32_t)done; np.count = cnt;
+        np.items = nullptr; np.n_per_item = 0; np.item_first = 0; np.item_count = 0; np.slot_begin = 0;
+        if (bc) {
+            np.items = bc->items; np.n_per_item = bc->n_per_item; np.slot_begin = done;
+            np.item_first = (uint32_t)(done / bc->n_per_item);
+            np.item_count = (uint32_t)((done + cnt - 1) / bc->n_per_item) - np.item_first + 1;
+        }
         if ((prc = mark(KC_NOISE)) != ISR_OK) return prc;
         ev_work.push_back({0.0, (double)cnt * pm.H * pm.W * 4});
         HIP_TRY(launch_noise(np, m->stream));
@@ -562,6 +584,7 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
                     f.logits = logits_host ? (int32_t *)(ws + pl.logits_off) : nullptr;
                     f.argmax = argmax_host ? (int32_t *)(ws + pl.argmax_off) : nullptr;
                     f.counts = dcounts;
+                    if (bc) { f.n_per_item = bc->n_per_item; f.slot_begin = done; }
                     HIP_TRY(launch_fc(f, m->stream));
                     break; }
                 }
@@ -592,6 +615,75 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
         if (logits_host || argmax_host) HIP_TRY(hipStreamSynchronize(m->stream));
         done += cnt;
     }
+    return ISR_OK;
+}
+
+// Makes the tables of every sigma in `sigmas` resident at once (at most TABLE_SLOTS
+// distinct values) and returns the slot of each.
+int get_tables(isr_model *m, const std::vector<uint32_t> &sigmas, std::vector<uint32_t> &slots) {
+    std::vector<uint32_t> distinct;
+    for (uint32_t s : sigmas)
+        if (std::find(distinct.begin(), distinct.end(), s) == distinct.end()) distinct.push_back(s);
+    if ((int)distinct.size() > TABLE_SLOTS) return ISR_ERR_ARG;
+    bool synced = false;
+    for (uint32_t s : distinct) {
+        bool have = false;
+        for (int i = 0; i < TABLE_SLOTS; ++i) have = have || m->table_sigma[i] == s;
+        if (have) continue;
+        int slot = -1;   // a slot whose table this batch does not need
+        for (int k = 0; k < TABLE_SLOTS && slot < 0; ++k) {
+            const int c = (m->table_next + k) % TABLE_SLOTS;
+            if (std::find(distinct.begin(), distinct.end(), m->table_sigma[c]) == distinct.end()) slot = c;
+        }
+        if (slot < 0) return ISR_ERR_ARG;   // cannot happen: fewer needed tables than slots
+        m->table_next = (slot + 1) % TABLE_SLOTS;
+        if (!synced) { HIP_TRY(hipStreamSynchronize(m->stream)); synced = true; }   // staging slots may be in flight
+        if (!build_device_table(s, m->htables[slot])) return ISR_ERR_ARG;
+        HIP_TRY(hipMemcpyAsync(m->dtables + slot, m->htables + slot, sizeof(DeviceNoiseTable), hipMemcpyHostToDevice, m->stream));
+        m->table_sigma[slot] = s;
+    }
+    slots.resize(sigmas.size());
+    for (size_t i = 0; i < sigmas.size(); ++i)
+        for (int k = 0; k < TABLE_SLOTS; ++k)
+            if (m->table_sigma[k] == sigmas[i]) slots[i] = (uint32_t)k;
+    return ISR_OK;
+}
+
+// Validates a batch, uploads its item descriptors and clears its vote counters
+// (phases * n_items * classes words).
+int prepare_batch(isr_model *m, const void *x, uint32_t n_images, const isr_item *items, uint32_t n_items, double alpha,
+                  int phases) {
+    if (!m || !x || !items || n_images == 0 || n_items == 0) return ISR_ERR_ARG;
+    if (!(alpha > 0.0 && alpha < 1.0)) return ISR_ERR_ARG;
+    if (!m->ws || m->chunk == 0) return ISR_ERR_WORKSPACE;
+    std::vector<uint32_t> sigmas(n_items), slots;
+    for (uint32_t i = 0; i < n_items; ++i) {
+        if (items[i].image >= n_images || items[i].sigma < 1 || items[i].sigma > 1024) return ISR_ERR_ARG;
+        sigmas[i] = items[i].sigma;
+    }
+    const size_t C = (size_t)m->pm.classes;
+    if (n_items > m->items_cap) {
+        HIP_TRY(hipStreamSynchronize(m->stream));
+        if (m->ditems) (void)hipFree(m->ditems);
+        if (m->hitems) (void)hipHostFree(m->hitems);
+        if (m->dcounts_b) (void)hipFree(m->dcounts_b);
+        if (m->hcounts_b) (void)hipHostFree(m->hcounts_b);
+        m->ditems = m->hitems = nullptr;
+        m->dcounts_b = m->hcounts_b = nullptr;
+        m->items_cap = 0;
+        const uint32_t cap = std::max<uint32_t>(n_items, 64);
+        HIP_TRY(hipMalloc((void **)&m->ditems, sizeof(NoiseItem) * cap));
+        HIP_TRY(hipHostMalloc((void **)&m->hitems, sizeof(NoiseItem) * cap, hipHostMallocDefault));
+        HIP_TRY(hipMalloc((void **)&m->dcounts_b, sizeof(uint32_t) * 2 * cap * C));
+        HIP_TRY(hipHostMalloc((void **)&m->hcounts_b, sizeof(uint32_t) * 2 * cap * C, hipHostMallocDefault));
+        m->items_cap = cap;
+    }
+    int rc = get_tables(m, sigmas, slots);
+    if (rc != ISR_OK) return rc;
+    HIP_TRY(hipStreamSynchronize(m->stream));   // the pinned descriptors of an earlier call may still be in flight
+    for (uint32_t i = 0; i < n_items; ++i) m->hitems[i] = NoiseItem{items[i].image, slots[i], items[i].image_id};
+    HIP_TRY(hipMemcpyAsync(m->ditems, m->hitems, sizeof(NoiseItem) * n_items, hipMemcpyHostToDevice, m->stream));
+    HIP_TRY(launch_fill_u32(m->dcounts_b, 0, (size_t)phases * n_items * C, m->stream));
     return ISR_OK;
 }
 
@@ -703,6 +795,10 @@ int isr_free_model(isr_model *m) {
     if (m->htables) (void)hipHostFree(m->htables);
     if (m->dcounts) (void)hipFree(m->dcounts);
     if (m->hcounts) (void)hipHostFree(m->hcounts);
+    if (m->ditems) (void)hipFree(m->ditems);
+    if (m->hitems) (void)hipHostFree(m->hitems);
+    if (m->dcounts_b) (void)hipFree(m->dcounts_b);
+    if (m->hcounts_b) (void)hipHostFree(m->hcounts_b);
     delete m;
     return ISR_OK;
 }
@@ -775,6 +871,49 @@ int isr_predict(isr_model *m, const uint8_t *x_device, uint32_t sigma, uint32_t 
     HIP_TRY(hipStreamSynchronize(m->stream));
     if (counts_host) std::memcpy(counts_host, m->hcounts, sizeof(uint32_t) * C);
     return isr_decide_predict(m->hcounts, C, alpha, out);
+}
+
+int isr_certify_batch(isr_model *m, const uint8_t *x_device, uint32_t n_images, const isr_item *items_host,
+                      uint32_t n_items, uint32_t n0, uint32_t n, double alpha, uint64_t seed, isr_result *out_host,
+                      uint32_t *counts0_host, uint32_t *counts1_host) {
+    if (!out_host || n0 == 0 || n == 0) return ISR_ERR_ARG;
+    int rc = prepare_batch(m, x_device, n_images, items_host, n_items, alpha, 2);
+    if (rc != ISR_OK) return rc;
+    const size_t C = (size_t)m->pm.classes, per_phase = (size_t)n_items * C;
+    const Plan &pl = m->plan[m->use_fused];
+    BatchCtx bc{m->ditems, n_items, n0};
+    if ((rc = run_range(m, pl, x_device, m->dtables, seed, 0, 0, 0, 0, nullptr, nullptr, m->dcounts_b, -1, &bc)) != ISR_OK) return rc;
+    bc.n_per_item = n;
+    if ((rc = run_range(m, pl, x_device, m->dtables, seed, 0, 1, 0, 0, nullptr, nullptr, m->dcounts_b + per_phase, -1, &bc)) != ISR_OK) return rc;
+    HIP_TRY(hipMemcpyAsync(m->hcounts_b, m->dcounts_b, sizeof(uint32_t) * 2 * per_phase, hipMemcpyDeviceToHost, m->stream));
+    HIP_TRY(hipStreamSynchronize(m->stream));
+    if (counts0_host) std::memcpy(counts0_host, m->hcounts_b, sizeof(uint32_t) * per_phase);
+    if (counts1_host) std::memcpy(counts1_host, m->hcounts_b + per_phase, sizeof(uint32_t) * per_phase);
+    for (uint32_t i = 0; i < n_items; ++i) {
+        rc = isr_decide_certify(m->hcounts_b + i * C, m->hcounts_b + per_phase + i * C, (uint32_t)C, (double)items_host[i].sigma, n,
+                                alpha, out_host + i);
+        if (rc != ISR_OK) return rc;
+    }
+    return ISR_OK;
+}
+
+int isr_predict_batch(isr_model *m, const uint8_t *x_device, uint32_t n_images, const isr_item *items_host,
+                      uint32_t n_items, uint32_t n, double alpha, uint64_t seed, isr_result *out_host,
+                      uint32_t *counts_host) {
+    if (!out_host || n == 0) return ISR_ERR_ARG;
+    int rc = prepare_batch(m, x_device, n_images, items_host, n_items, alpha, 1);
+    if (rc != ISR_OK) return rc;
+    const size_t C = (size_t)m->pm.classes, per_phase = (size_t)n_items * C;
+    BatchCtx bc{m->ditems, n_items, n};
+    if ((rc = run_range(m, m->plan[m->use_fused], x_device, m->dtables, seed, 0, 0, 0, 0, nullptr, nullptr, m->dcounts_b, -1, &bc)) != ISR_OK) return rc;
+    HIP_TRY(hipMemcpyAsync(m->hcounts_b, m->dcounts_b, sizeof(uint32_t) * per_phase, hipMemcpyDeviceToHost, m->stream));
+    HIP_TRY(hipStreamSynchronize(m->stream));
+    if (counts_host) std::memcpy(counts_host, m->hcounts_b, sizeof(uint32_t) * per_phase);
+    for (uint32_t i = 0; i < n_items; ++i) {
+        rc = isr_decide_predict(m->hcounts_b + i * C, (uint32_t)C, alpha, out_host + i);
+        if (rc != ISR_OK) return rc;
+    }
+    return ISR_OK;
 }
 
 int isr_debug_noisy(isr_model *m, const uint8_t *x_device, uint32_t sigma, uint64_t seed, uint32_t image_id,

@@ -161,3 +161,18 @@ extern "C" int isr_decide_predict(const uint32_t *counts, uint32_t classes, doub
     out->cls = pv <= alpha ? (int32_t)ca : ISR_ABSTAIN;
     return ISR_OK;
 }
+
+extern "C" int isr_certified_metrics(const isr_result *results, const int32_t *labels, uint32_t count, const double *radii,
+                                     uint32_t n_radii, double *cp_out, double *ca_out) {
+    if (!results || count == 0 || (n_radii && (!radii || !ca_out || !labels))) return ISR_ERR_ARG;
+    uint32_t certified = 0;
+    for (uint32_t i = 0; i < count; ++i) certified += results[i].cls != ISR_ABSTAIN;
+    if (cp_out) *cp_out = (double)certified / (double)count;
+    for (uint32_t j = 0; j < n_radii; ++j) {
+        uint32_t hit = 0;
+        for (uint32_t i = 0; i < count; ++i)
+            hit += results[i].cls != ISR_ABSTAIN && results[i].cls == labels[i] && results[i].radius >= radii[j];
+        ca_out[j] = certified ? (double)hit / (double)certified : 0.0;
+    }
+    return ISR_OK;
+}

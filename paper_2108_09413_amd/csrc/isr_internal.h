@@ -151,15 +151,32 @@ struct FcParams {
     int32_t Kp, classes, B;
     int32_t *logits;         // [B][classes] or null
     int32_t *argmax;         // [B] or null
-    uint32_t *counts;        // [classes] (accumulated) or null
+    uint32_t *counts;        // [classes] (accumulated) or null; [items][classes] in batch mode
+    // batch mode (n_per_item != 0): copy s of the chunk is slot slot_begin + s of a list in which
+    // every item owns n_per_item consecutive slots; its vote goes to counts[slot / n_per_item]
+    uint32_t n_per_item;
+    uint64_t slot_begin;
+};
+
+// One (image, sigma) pair of a batched call.
+struct NoiseItem {
+    uint32_t image;          // index into the array of clean images
+    uint32_t table_slot;     // index into the array of noise tables
+    uint32_t image_id;       // counter word of the random stream
 };
 
 struct NoiseParams {
-    const uint8_t *x;        // [C][H][W] clean image
-    const DeviceNoiseTable *table;
+    const uint8_t *x;        // [C][H][W] clean image ([images][C][H][W] in batch mode)
+    const DeviceNoiseTable *table;   // the table (batch mode: table 0 of the array indexed by table_slot)
     int8_t *out;             // [B][H][W][4]
     int32_t C, H, W;
     uint32_t key0, key1, image, phase, sample_begin, count;
+    // batch mode (items != null): copy s of the chunk is slot slot_begin + s; item i owns slots
+    // [i * n_per_item, (i + 1) * n_per_item) and sample index = slot - i * n_per_item; the
+    // launch covers items item_first .. item_first + item_count - 1 (one grid row each)
+    const NoiseItem *items;
+    uint32_t n_per_item, item_first, item_count;
+    uint64_t slot_begin;
 };
 
 // Kernel launchers (kernels.hip / conv_igemm.hip).  All asynchronous on `st`.

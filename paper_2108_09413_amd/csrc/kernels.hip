@@ -61,25 +61,43 @@ __device__ __noinline__ int threshold_count_slow(const NoiseLds &t, int n, uint3
 
 __global__ __launch_bounds__(256) void noise_kernel(const NoiseParams p) {
     __shared__ NoiseLds t;
+    // what this workgroup draws: one image, one table, a range of sample indices, a range of output copies
+    const uint8_t *xim = p.x;
+    const DeviceNoiseTable *tab = p.table;
+    uint32_t image_id = p.image, sample_begin = p.sample_begin, count = p.count;
+    long out_copy0 = 0;
+    if (p.items) {   // batch mode: grid row = item; its slots that fall into this chunk
+        const uint64_t item = (uint64_t)p.item_first + blockIdx.y;
+        const uint64_t first = item * p.n_per_item, last = first + p.n_per_item, chunk_end = p.slot_begin + p.count;
+        const uint64_t lo = first > p.slot_begin ? first : p.slot_begin, hi = last < chunk_end ? last : chunk_end;
+        if (hi <= lo) return;   // uniform over the workgroup
+        const NoiseItem it = p.items[item];
+        xim = p.x + (size_t)it.image * p.C * p.H * p.W;
+        tab = p.table + it.table_slot;
+        image_id = it.image_id;
+        sample_begin = (uint32_t)(lo - first);
+        count = (uint32_t)(hi - lo);
+        out_copy0 = (long)(lo - p.slot_begin);
+    }
     for (int i = threadIdx.x; i < (int)NOISE_TABLE_MAX; i += 256) {
-        t.hi[i] = p.table->hi[i];
-        t.lo[i] = p.table->lo[i];
+        t.hi[i] = tab->hi[i];
+        t.lo[i] = tab->lo[i];
     }
     if (threadIdx.x < 2) t.hi[NOISE_TABLE_MAX + threadIdx.x] = 0xFFFFFFFFu;
     for (int i = threadIdx.x; i < (int)(NOISE_GUIDE_SIZE + 2) / 2; i += 256)   // two 16-bit entries per word
-        ((uint32_t *)t.guide)[i] = ((const uint32_t *)p.table->guide)[i];
-    const int n = (int)p.table->n;
-    const int dmin = p.table->dmin;
+        ((uint32_t *)t.guide)[i] = ((const uint32_t *)tab->guide)[i];
+    const int n = (int)tab->n;
+    const int dmin = tab->dmin;
     __syncthreads();
 
     const int W4 = p.W >> 2;
     const long groups_per_sample = (long)p.H * W4;
-    const long total = groups_per_sample * p.count;
+    const long total = groups_per_sample * count;
     for (long g = (long)blockIdx.x * 256 + threadIdx.x; g < total; g += (long)gridDim.x * 256) {
         const uint32_t s_local = (uint32_t)(g / groups_per_sample);
         const int rem = (int)(g - (long)s_local * groups_per_sample);
         const int y = rem / W4, x4 = rem - y * W4;
-        const uint32_t sample = p.sample_begin + s_local;
+        const uint32_t sample = sample_begin + s_local;
         uint32_t packed[4] = {0, 0, 0, 0};
 #pragma unroll
         for (int c = 0; c < 3; ++c) {
@@ -87,8 +105,8 @@ __global__ __launch_bounds__(256) void noise_kernel(const NoiseParams p) {
                 const uint32_t pix = (uint32_t)((c * p.H + y) * p.W + x4 * 4);   // multiple of 4
                 const uint32_t grp = pix >> 2;
                 uint32_t hi[4];
-                philox4x32_10(grp, sample, p.image, p.phase * 2u, p.key0, p.key1, hi);
-                const uint32_t px4 = *(const uint32_t *)(p.x + pix);
+                philox4x32_10(grp, sample, image_id, p.phase * 2u, p.key0, p.key1, hi);
+                const uint32_t px4 = *(const uint32_t *)(xim + pix);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const uint32_t u = hi[j];
@@ -97,7 +115,7 @@ __global__ __launch_bounds__(256) void noise_kernel(const NoiseParams p) {
                     cnt += t0 < u;
                     // common case: at most one threshold below u in the bucket and no tie
                     if ((t0 < u ? t1 : t0) <= u)
-                        cnt = threshold_count_slow(t, n, u, grp, sample, p.image, p.phase, p.key0, p.key1, j);
+                        cnt = threshold_count_slow(t, n, u, grp, sample, image_id, p.phase, p.key0, p.key1, j);
                     int v = (int)((px4 >> (8 * j)) & 0xFF) + dmin + cnt;
                     v = (v < 0 ? 0 : (v > 255 ? 255 : v)) - 128;
                     packed[j] |= (uint32_t)(v & 0xFF) << (8 * c);
@@ -105,17 +123,25 @@ __global__ __launch_bounds__(256) void noise_kernel(const NoiseParams p) {
             }
         }
         v4i o = {(int)packed[0], (int)packed[1], (int)packed[2], (int)packed[3]};
-        *(v4i *)(p.out + ((long)s_local * groups_per_sample + rem) * 16) = o;
+        *(v4i *)(p.out + ((out_copy0 + s_local) * groups_per_sample + rem) * 16) = o;
     }
 }
 
 hipError_t launch_noise(const NoiseParams &p, hipStream_t st) {
     if (p.count == 0) return hipSuccess;
     if (p.C < 1 || p.C > 3 || (p.W & 3) != 0) return hipErrorInvalidValue;
-    long total = (long)p.H * (p.W >> 2) * p.count;
+    unsigned rows = 1;
+    uint32_t per_row = p.count;
+    if (p.items) {
+        if (p.n_per_item == 0 || p.item_count == 0 || p.item_count > 65535) return hipErrorInvalidValue;
+        rows = p.item_count;
+        if (p.n_per_item < per_row) per_row = p.n_per_item;
+    }
+    long total = (long)p.H * (p.W >> 2) * per_row;
     long blocks = (total + 255) / 256;
-    if (blocks > 256 * 4) blocks = 256 * 4;   // the table is staged into LDS once per workgroup
-    hipLaunchKernelGGL(noise_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p);
+    const long cap = rows >= 4 ? 256 : 256 * 4;   // the table is staged into LDS once per workgroup
+    if (blocks > cap) blocks = cap;
+    hipLaunchKernelGGL(noise_kernel, dim3((unsigned)blocks, rows), dim3(256), 0, st, p);
     return hipGetLastError();
 }
 
@@ -279,11 +305,14 @@ __global__ __launch_bounds__(256) void fc_vote_kernel(const FcParams p) {
         }
         if (lane == 0) {
             if (p.argmax) p.argmax[s] = best_idx;
-            if (p.counts) atomicAdd(&hist[best_idx], 1u);
+            if (p.counts) {
+                if (p.n_per_item) atomicAdd(&p.counts[(p.slot_begin + (uint64_t)s) / p.n_per_item * p.classes + best_idx], 1u);
+                else atomicAdd(&hist[best_idx], 1u);
+            }
         }
     }
     __syncthreads();
-    if (p.counts)
+    if (p.counts && !p.n_per_item)
         for (int i = threadIdx.x; i < p.classes; i += 256)
             if (hist[i]) atomicAdd(&p.counts[i], hist[i]);
 }

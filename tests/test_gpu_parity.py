@@ -402,6 +402,75 @@ def test_every_conv_tile_against_the_oracle(isr, tile):
         _check_all_tensors(isr, blob, x, 64)
 
 
+# ---- many (image, sigma) pairs in one pass -------------------------------------
+
+def _check_batch_against_oracle(isr, m, om, xs, items, n0, n, seed):
+    res, c0, c1 = isr.isr_certify_batch(m, xs, items, n0, n, ALPHA, seed=seed)
+    want = oracle.certify_batch(om, xs, items, n0, n, ALPHA, seed=seed)
+    for i, (cls, rad, p_l, k, oc0, oc1) in enumerate(want):
+        assert np.array_equal(c0[i], oc0) and np.array_equal(c1[i], oc1), (i, items[i])
+        assert res[i].cls == cls and res[i].n_top == k
+        assert res[i].p_lower == pytest.approx(p_l, rel=1e-12)
+        assert res[i].radius == pytest.approx(rad, rel=1e-9)
+    pres, pc = isr.isr_predict_batch(m, xs, items, n, ALPHA, seed=seed + 1)
+    pwant = oracle.predict_batch(om, xs, items, n, ALPHA, seed=seed + 1)
+    for i, (cls, pv, n_a, n_b, opc) in enumerate(pwant):
+        assert np.array_equal(pc[i], opc), (i, items[i])
+        assert (pres[i].cls, pres[i].n_top, pres[i].n_second) == (cls, n_a, n_b)
+        assert pres[i].p_lower == pytest.approx(pv, rel=1e-9, abs=1e-300)
+    return res, c0, c1
+
+
+@pytest.mark.parametrize("chunk", [64, 1000])
+def test_batched_pairs_config0(isr, chunk):
+    """Six (image, sigma) pairs over five images, four noise levels, one image used
+    twice: chunks smaller than a pair's run (64) and chunks spanning several pairs
+    (1000), n0 and n no multiples of either.  Every pair against the oracle, and
+    against the single-pair entry point."""
+    _say(f"batched certify / predict, tiny net, chunk {chunk}")
+    blob = synth.build_model(0)
+    om = oracle.Model(blob)
+    m = _load(isr, blob, chunk)
+    xs = np.stack([synth.make_image(0, i) for i in range(1, 6)])
+    items = [(0, 32, 0), (1, 64, 7), (0, 128, 3), (4, 32, 9), (2, 1024, 11), (3, 64, 0)]
+    res, c0, c1 = _check_batch_against_oracle(isr, m, om, xs, items, 37, 250, seed=5)
+    for i, (img, sigma, image_id) in enumerate(items):
+        one, s0, s1 = isr.isr_certify(m, xs[img], sigma, 37, 250, ALPHA, seed=5, image_id=image_id)
+        assert np.array_equal(s0, c0[i]) and np.array_equal(s1, c1[i])
+        assert (one.cls, one.n_top, one.radius, one.p_lower) == (res[i].cls, res[i].n_top, res[i].radius, res[i].p_lower)
+    m.close()
+
+
+def test_batched_pairs_resnet20_small_n(isr):
+    """Prediction-sized runs (n = 100) of eight pairs in chunks of 512 on ResNet-20:
+    five pairs share a chunk; a second call with fewer pairs reuses the buffers."""
+    _say("batched certify / predict, resnet20")
+    blob = synth.build_model(1)
+    om = oracle.Model(blob)
+    m = _load(isr, blob, 512)
+    xs = np.stack([synth.make_image(1, i) for i in range(1, 5)])
+    items = [(i % 4, (32, 64, 128)[i % 3], i) for i in range(8)]
+    _check_batch_against_oracle(isr, m, om, xs, items, 20, 100, seed=0)
+    _check_batch_against_oracle(isr, m, om, xs, items[5:7], 10, 33, seed=2)
+    m.close()
+
+
+def test_batched_call_argument_errors(isr):
+    blob = synth.build_model(0)
+    m = _load(isr, blob, 32)
+    xs = np.stack([synth.make_image(0, i) for i in range(1, 3)])
+    for items in ([(2, 32, 0)], [(0, 0, 0)], [(0, 1025, 0)], [(0, s, 0) for s in range(1, 10)]):
+        with pytest.raises(isr.IsrError) as e:
+            isr.isr_predict_batch(m, xs, items, 10, ALPHA)
+        assert e.value.status == isr.ISR_ERR_ARG
+    with pytest.raises(isr.IsrError):
+        isr.isr_certify_batch(m, xs, [(0, 32, 0)], 0, 10, ALPHA)
+    # eight distinct noise levels are the limit and work
+    res, c = isr.isr_predict_batch(m, xs, [(1, s, 3) for s in (1, 2, 3, 4, 5, 6, 7, 8)], 40, ALPHA)
+    assert all(int(row.sum()) == 40 for row in c)
+    m.close()
+
+
 # ---- argument handling --------------------------------------------------------
 
 def test_error_paths(isr):

@@ -153,3 +153,26 @@ def test_discrete_quantile_matches_the_oracle():
         isr.isr_discrete_quantile(0, 0.9)
     with pytest.raises(isr.IsrError):
         isr.isr_discrete_quantile(32, 1.5)
+
+
+def test_certified_metrics_match_the_oracle():
+    """CP and CA of the paper's evaluation section: library against the oracle on random
+    result lists, plus the empty-denominator and argument cases."""
+    rng = np.random.default_rng(17)
+    for trial in range(20):
+        L = int(rng.integers(1, 60))
+        labels = rng.integers(0, 5, size=L)
+        classes = np.where(rng.random(L) < 0.6, labels, rng.integers(0, 5, size=L))
+        classes = np.where(rng.random(L) < (0.3 if trial else 1.0), ostats.ABSTAIN, classes)
+        radii = np.where(classes == ostats.ABSTAIN, 0.0, np.round(rng.random(L) * 50, 1))
+        results = [isr.Result(int(c), float(r), 0.9, 10, 0) for c, r in zip(classes, radii)]
+        grid = [0.0, 0.1, 5.0, 25.0, 49.9, 50.0, 60.0]
+        cp, ca = isr.isr_certified_metrics(results, labels, grid)
+        assert cp == ostats.certified_percentage(classes)
+        for r, a in zip(grid, ca):
+            assert a == ostats.certified_accuracy(classes, radii, labels, r)
+    cp, ca = isr.isr_certified_metrics([isr.Result(1, 2.0, 0.9, 5, 0)], [1], [])
+    assert cp == 1.0 and ca.size == 0
+    res = (isr.Result * 1)(isr.Result(1, 2.0, 0.9, 5, 0))
+    assert isr.lib().isr_certified_metrics(res, None, 0, None, 0, None, None) == isr.ISR_ERR_ARG
+    assert isr.lib().isr_certified_metrics(res, None, 1, None, 2, None, None) == isr.ISR_ERR_ARG

@@ -131,3 +131,40 @@ def test_predict_decision_rule():
     assert stats.predict_decision([0, 10, 0], ALPHA)[0] == stats.ABSTAIN
     # runner-up is the second largest count, not the second index
     assert stats.predict_decision([5, 80, 1, 14], ALPHA)[2:] == (80, 14)
+
+
+def test_certified_percentage_and_accuracy_worked_example():
+    """Section "Evaluation Metrics": five inputs counted by hand.  Input 1 abstains;
+    input 3 certifies the wrong class; the radii of the correct ones are 0.5, 1.2, 0.1."""
+    classes = [1, stats.ABSTAIN, 2, 0, 2]
+    radii = [0.5, 0.0, 1.2, 0.3, 0.1]
+    labels = [1, 3, 2, 1, 2]
+    assert stats.certified_percentage(classes) == 4 / 5
+    assert stats.certified_accuracy(classes, radii, labels, 0.0) == 3 / 4
+    assert stats.certified_accuracy(classes, radii, labels, 0.2) == 2 / 4
+    assert stats.certified_accuracy(classes, radii, labels, 0.5) == 2 / 4      # radius == r counts
+    assert stats.certified_accuracy(classes, radii, labels, 0.51) == 1 / 4
+    assert stats.certified_accuracy(classes, radii, labels, 1.3) == 0.0
+    # a wrong class never counts, however large its radius
+    assert stats.certified_accuracy([0], [9.0], [1], 0.0) == 0.0
+    # nobody certified: CP 0 and CA defined as 0
+    assert stats.certified_percentage([stats.ABSTAIN] * 3) == 0.0
+    assert stats.certified_accuracy([stats.ABSTAIN] * 3, [0.0] * 3, [0, 1, 2], 0.0) == 0.0
+
+
+def test_certified_accuracy_is_a_decreasing_step_function_of_the_radius():
+    rng = np.random.default_rng(3)
+    L = 200
+    labels = rng.integers(0, 10, size=L)
+    classes = np.where(rng.random(L) < 0.7, labels, rng.integers(0, 10, size=L))
+    classes = np.where(rng.random(L) < 0.2, stats.ABSTAIN, classes)
+    radii = np.where(classes == stats.ABSTAIN, 0.0, rng.random(L) * 100)
+    cp = stats.certified_percentage(classes)
+    assert cp == np.mean(classes != stats.ABSTAIN)
+    grid = np.linspace(0, 110, 23)
+    ca = [stats.certified_accuracy(classes, radii, labels, r) for r in grid]
+    assert all(a >= b for a, b in zip(ca, ca[1:])) and ca[-1] == 0.0
+    # CA(r) * CP is the share of the whole set that is certified, correct and has radius >= r
+    for r, a in zip(grid, ca):
+        whole = np.mean((classes != stats.ABSTAIN) & (classes == labels) & (radii >= r))
+        assert a * cp == pytest.approx(whole, rel=1e-12, abs=1e-15)
