@@ -12,9 +12,10 @@ LIB = os.path.join(HERE, "libisr.so")
 SOURCES = ["api.cpp", "model_parse.cpp", "noise_table.cpp", "host_stats.cpp", "kernels.hip", "conv_igemm.hip", "stem_pool.hip", "basic_block.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
-# kernels: gfx950 only; packed-FP32 instruction selection is switched off
+# kernels: gfx950 only; packed-FP32 instruction selection is switched off; MFMA results go to
+# ordinary VGPRs (no accumulator-register copies in front of the epilogue arithmetic)
 HIP_FLAGS = ["--offload-arch=gfx950", "-x", "hip", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-             "-Wno-unknown-attributes"]
+             "-mllvm", "-amdgpu-mfma-vgpr-form=1", "-Wno-unknown-attributes"]
 # host-only sources: plain C++ against the HIP runtime headers
 HOST_FLAGS = ["-x", "c++", "-D__HIP_PLATFORM_AMD__", "-I", "/opt/rocm/include"]
 

@@ -75,45 +75,89 @@ __global__ __launch_bounds__(256) void basic_block_kernel(const BlockParams p) {
     // `emit(image, pixel, m fragment, accumulators)` consumes each fragment.
     const int mf = wave % MSPLIT;                    // this wave's M fragment
     auto conv = [&](const int8_t (*src)[P * P * C], int cv, const int8_t *w, auto emit) {
-        v4i fa[KS];                                  // the wave's weight fragments, all K steps
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) fa[ks] = *(const v4i *)(w + (long)(mf * MT + l) * KP + (ks * CPS + kg) * 16);
         acc_t binit;
 #pragma unroll
         for (int i = 0; i < ACC; ++i) binit[i] = prm[cv][0][mf * MT + ocl + i];
-        for (int f = wave / MSPLIT; f < NI * NF; f += 4 / MSPLIT) {
-            const int im = f / NF, pix = (f % NF) * MT + l;
-            const int y = pix / S, x = pix % S;
-            const int8_t *base = &src[im][(y * P + x) * C];   // tap (0, 0) of this pixel in the padded tile
-            acc_t acc = binit;
+        if constexpr (C == 16) {
+            // 16 channels: a K step of v_mfma_i32_16x16x64_i8 is one kernel row -- lane group kg holds
+            // tap (ky = step, kx = kg), the fourth group zero weights -- and a wave walks down 16 rows
+            // of a 16-pixel column strip: the operands of rows y+1, y+2 of one output row are those of
+            // rows y, y+1 of the next, so each output fragment costs one new LDS read instead of three.
+            static_assert(S == 32 && NI == 1, "walk assumes two 16-pixel strips and one image");
+            const int strip = wave & 1, row0 = (wave >> 1) * 16, kx = kg < 3 ? kg : 0;
+            v4i fa[3];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const int j = ks * CPS + kg;              // 16-byte K chunk: tap j / CH, channel chunk j % CH
-                int tap = j / CH;
-                const int cc = j % CH;
-                if (tap > 8) tap = 0;                     // K padding: zero weights, any readable address
-                const v4i fb = *(const v4i *)(base + ((tap / 3) * P + tap % 3) * C + cc * 16);
-                if constexpr (MT == 16) acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[ks], fb, acc, 0, 0, 0);
-                else acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[ks], fb, acc, 0, 0, 0);
+            for (int ky = 0; ky < 3; ++ky) {
+                fa[ky] = *(const v4i *)(w + (long)l * KP + (ky * 3 + kx) * 16);
+                if (kg == 3) fa[ky] = v4i{0, 0, 0, 0};
             }
-            emit(im, pix, mf, acc);
+            const int x = 16 * strip + l;
+            const int8_t *col = &src[0][(row0 * P + x + kx) * C];   // padded (row0, x + kx) = tap (0, kx) of output (row0, x)
+            v4i b0 = *(const v4i *)col, b1 = *(const v4i *)(col + P * C);
+#pragma unroll 4
+            for (int r = 0; r < 16; ++r) {
+                const v4i b2 = *(const v4i *)(col + (r + 2) * P * C);
+                acc_t acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[0], b0, binit, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[1], b1, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[2], b2, acc, 0, 0, 0);
+                emit(0, (row0 + r) * S + x, 0, acc);
+                b0 = b1;
+                b1 = b2;
+            }
+        } else {
+            v4i fa[KS];                                  // the wave's weight fragments, all K steps
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) fa[ks] = *(const v4i *)(w + (long)(mf * MT + l) * KP + (ks * CPS + kg) * 16);
+            for (int f = wave / MSPLIT; f < NI * NF; f += 4 / MSPLIT) {
+                const int im = f / NF, pix = (f % NF) * MT + l;
+                const int y = pix / S, x = pix % S;
+                const int8_t *base = &src[im][(y * P + x) * C];   // tap (0, 0) of this pixel in the padded tile
+                acc_t acc = binit;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const int j = ks * CPS + kg;              // 16-byte K chunk: tap j / CH, channel chunk j % CH
+                    int tap = j / CH;
+                    const int cc = j % CH;
+                    if (tap > 8) tap = 0;                     // K padding: zero weights, any readable address
+                    const v4i fb = *(const v4i *)(base + ((tap / 3) * P + tap % 3) * C + cc * 16);
+                    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[ks], fb, acc, 0, 0, 0);
+                }
+                emit(im, pix, mf, acc);
+            }
         }
+    };
+
+    // Per-channel requantisation constants of the lane's ACC output channels, held in registers
+    // across the pixel loop (the lane's channels do not change): re-reading them from LDS for every
+    // fragment would cost more LDS bandwidth than the operands.
+    struct Req { int m0[ACC], chi[ACC], shm1[ACC]; };
+    auto load_req = [&](int cv) {
+        Req r;
+#pragma unroll
+        for (int i = 0; i < ACC; ++i) {
+            r.m0[i] = prm[cv][1][mf * MT + ocl + i];
+            r.chi[i] = prm[cv][2][mf * MT + ocl + i];
+            r.shm1[i] = prm[cv][3][mf * MT + ocl + i];
+        }
+        return r;
     };
 
     // ---- first convolution: requantise, clamp, into the interior of T ----
     const int lo1 = p.relu1 ? p.zp_t : -128;
-    conv(X, 0, p.w1, [&](int im, int pix, int mf, const acc_t &a) {
-        const int c0 = mf * MT + ocl;
-        int q[ACC];
+    {
+        const Req rq = load_req(0);
+        conv(X, 0, p.w1, [&](int im, int pix, int mf, const acc_t &a) {
+            const int c0 = mf * MT + ocl;
+            int q[ACC];
 #pragma unroll
-        for (int i = 0; i < ACC; ++i)
-            q[i] = clamp3(requant_q<TF>(a[i], prm[0][1][c0 + i], prm[0][2][c0 + i], prm[0][3][c0 + i]), lo1, 127);
-        int8_t *dst = &T[im][((pix / S + 1) * P + pix % S + 1) * C + c0];
-        if constexpr (MT == 16) *(uint32_t *)dst = pack4(q[0], q[1], q[2], q[3]);
-        else
-            *(v4i *)dst = v4i{(int)pack4(q[0], q[1], q[2], q[3]), (int)pack4(q[4], q[5], q[6], q[7]),
-                              (int)pack4(q[8], q[9], q[10], q[11]), (int)pack4(q[12], q[13], q[14], q[15])};
-    });
+            for (int i = 0; i < ACC; ++i) q[i] = clamp3(requant_q<TF>(a[i], rq.m0[i], rq.chi[i], rq.shm1[i]), lo1, 127);
+            int8_t *dst = &T[im][((pix / S + 1) * P + pix % S + 1) * C + c0];
+            if constexpr (MT == 16) *(uint32_t *)dst = pack4(q[0], q[1], q[2], q[3]);
+            else
+                *(v4i *)dst = v4i{(int)pack4(q[0], q[1], q[2], q[3]), (int)pack4(q[4], q[5], q[6], q[7]),
+                                  (int)pack4(q[8], q[9], q[10], q[11]), (int)pack4(q[12], q[13], q[14], q[15])};
+        });
+    }
     __syncthreads();
 
     // ---- second convolution: requantise, clamp, add the residual x, store ----
@@ -121,6 +165,7 @@ __global__ __launch_bounds__(256) void basic_block_kernel(const BlockParams p) {
     ConvParams ap{};   // the fused add reads its constants from here
     ap.add_mul_self = p.add_mul_self; ap.add_mul_res = p.add_mul_res; ap.add_c0 = p.add_c0; ap.add_k = p.add_k;
     ap.add_sh = p.add_sh; ap.add_lo = p.add_lo;
+    const Req rq2 = load_req(1);
     conv(T, 1, p.w2, [&](int im, int pix, int mf, const acc_t &a) {
         const int c0 = mf * MT + ocl;
         const long g = img0 + im;
@@ -135,7 +180,7 @@ __global__ __launch_bounds__(256) void basic_block_kernel(const BlockParams p) {
         }
 #pragma unroll
         for (int i = 0; i < ACC; ++i) {
-            const int qc = clamp3(requant_q<TF>(a[i], prm[1][1][c0 + i], prm[1][2][c0 + i], prm[1][3][c0 + i]), lo2, 127);
+            const int qc = clamp3(requant_q<TF>(a[i], rq2.m0[i], rq2.chi[i], rq2.shm1[i]), lo2, 127);
             const int r8 = (int)(int8_t)(rw[i >> 2] >> (8 * (i & 3)));
             q[i] = fused_add<TF>(qc, r8, ap);
         }
