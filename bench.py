@@ -41,7 +41,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=4)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="resnet50", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="resnet50", choices=sorted(WORKLOADS) + ["noisebank"])
     ap.add_argument("--chunk", type=int, default=0, help="noisy copies per device chunk (0 = default)")
     ap.add_argument("--n", type=int, default=0, help="override estimation samples per step")
     ap.add_argument("--mode", default="certify", choices=["certify", "predict"],
@@ -66,6 +66,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.workload == "noisebank":
+        return bench_noise_bank(args, isr, torch)
     cfg_id, chunk, oracle_samples = WORKLOADS[args.workload]
     cfg = synth.CONFIGS[cfg_id]
     chunk = args.chunk or chunk
@@ -196,6 +198,47 @@ def main():
         "last_result": {"cls": results[-1].cls, "radius": results[-1].radius, "n_top": results[-1].n_top},
     }
     print(json.dumps(out))
+
+
+def bench_noise_bank(args, isr, torch):
+    """Stored training noise: one step = a bank of --n (default 50000) tensors of 3x32x32
+    discrete-Gaussian draws (int16) at sigma 32, written to HBM."""
+    count, d, sigma = args.n or 50000, 3 * 32 * 32, 32
+    out = torch.empty((count, d), dtype=torch.int16, device="cuda")
+    for k in range(args.warmup):
+        isr.isr_noise_bank(sigma, 0, k, 0, count, d, out=out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        isr.isr_noise_bank(sigma, 0, 100 + k, 0, count, d, out=out)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    values = args.steps * count * d
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        sample = 2000
+        t1 = time.perf_counter()
+        oracle.noise_bank(sigma, 0, 100, 0, sample, d)
+        cdt = time.perf_counter() - t1
+        cpu = {"value": round(sample * d / cdt, 1), "unit": "draws/s", "cores": 1, "kind": "oracle",
+               "sample": f"{sample} tensors of {d} draws ({cdt:.1f} s, one thread)"}
+    # executed VALU instructions per 4 draws of one lane, from the committed rocprofv3 counter run
+    # (SQ_INSTS_VALU / (draws / 4 / 64), profiles/noise_bank_kernel.md); peak = 256 CUs x 64 lanes x 2.4 GHz
+    valu_per_group, alu_peak = 137.0, 256 * 64 * 2.4e9 / 1e12
+    tops = values / 4 * valu_per_group / dt / 1e12
+    print(json.dumps({
+        "metric": "stored discrete-Gaussian noise draws/sec", "value": round(values / dt, 1), "unit": "draws/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int16", "data": "synthetic",
+        "config": {"workload": f"noise bank: {count} tensors x {d} draws (3x32x32), sigma {sigma}, int16, whole call "
+                               f"(table build + upload + kernel + synchronisation)"},
+        "roofline": {"bound": "alu", "kernel": "noise_bank_kernel", "achieved": round(tops, 2), "peak": round(alu_peak, 2),
+                     "unit": "T lane-instructions/s", "frac": round(tops / alu_peak, 4), "traffic": None,
+                     "note": "137 executed VALU instructions per lane per 4 draws (rocprofv3 SQ_INSTS_VALU) over the "
+                             "whole-call time; the 2 bytes written per draw are "
+                             f"{values * 2 / dt / 1e9:.0f} GB/s"},
+        "cpu_baseline": cpu}))
 
 
 if __name__ == "__main__":

@@ -130,6 +130,20 @@ int isr_predict_batch(isr_model *m, const uint8_t *x_device, uint32_t n_images, 
                       uint32_t n_items, uint32_t n, double alpha, uint64_t seed, isr_result *out_host,
                       uint32_t *counts_host);
 
+/* ---- noise stored ahead of training ---------------------------------------- */
+
+/* Training with discrete-Gaussian data augmentation (section "Quantization Aware Training
+ * with ...": noise for a batch is sampled once, stored, then shuffled and added to inputs):
+ * fills out_device with count tensors of d draws each from N_Z(0, sigma^2) (Def. 3.3), int16,
+ * [count][d], device memory.  Draw p of tensor first + t is the table sampler of
+ * isr_noise_table applied to the uniform 64-bit word of counter (p >> 2, first + t, bank_id,
+ * 4 | half), word p & 3, key = seed: the inference sampler's stream with phase 2, unsaturated
+ * (|draw| <= R <= 9216).  Needs no model; enqueued on hip_stream (NULL = default) and
+ * synchronised before returning.  ISR_ERR_ARG unless 1 <= sigma <= 1024, d a positive
+ * multiple of 4, first + count <= 2^32. */
+int isr_noise_bank(uint32_t sigma, uint64_t seed, uint32_t bank_id, uint32_t first, uint32_t count, uint32_t d,
+                   int16_t *out_device, void *hip_stream);
+
 /* ---- parity / resume hooks (sample-index ranges are reproducible) -------- */
 
 /* Noisy copies for sample indices [sample_begin, sample_begin+count) of one

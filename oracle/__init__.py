@@ -43,6 +43,9 @@ def lib():
         L.isr_oracle_noisy.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_uint64,
                                        C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p]
         L.isr_oracle_noisy.restype = None
+        L.isr_oracle_noise_bank.argtypes = [C.c_void_p, C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32,
+                                            C.c_uint32, C.c_void_p]
+        L.isr_oracle_noise_bank.restype = None
         L.isr_oracle_load.argtypes = [C.c_void_p, C.c_size_t]
         L.isr_oracle_load.restype = C.c_void_p
         L.isr_oracle_free.argtypes = [C.c_void_p]
@@ -102,6 +105,14 @@ def noisy(x: np.ndarray, sigma: int, seed: int, image: int, phase: int, sample: 
     T, R = noise_table(sigma)
     out = np.zeros(x.shape, dtype=np.int8)
     lib().isr_oracle_noisy(_ptr(x), x.size, _ptr(T), R, C.c_uint64(seed), image, phase, sample, _ptr(out))
+    return out
+
+
+def noise_bank(sigma: int, seed: int, bank: int, first: int, count: int, d: int) -> np.ndarray:
+    """int16 [count][d]: stored training noise, draws of N_Z(0, sigma^2) on the phase-2 stream."""
+    T, R = noise_table(sigma)
+    out = np.zeros((count, d), dtype=np.int16)
+    lib().isr_oracle_noise_bank(_ptr(T), R, C.c_uint64(seed), bank, first, count, d, _ptr(out))
     return out
 
 

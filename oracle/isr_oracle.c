@@ -140,6 +140,17 @@ void isr_oracle_noisy(const uint8_t *x, uint32_t npix, const uint64_t *T, uint32
     }
 }
 
+/* Noise stored ahead of training (training section: the noise of a batch is     */
+/* sampled once and kept): draw p of tensor first + t is the table sampler on the */
+/* 64-bit word of the stream with the tensor index as sample, the bank id as      */
+/* image and phase 2; no image is added and nothing saturates.                    */
+void isr_oracle_noise_bank(const uint64_t *T, uint32_t R, uint64_t seed, uint32_t bank, uint32_t first,
+                           uint32_t count, uint32_t d, int16_t *out) {
+    for (uint32_t t = 0; t < count; ++t)
+        for (uint32_t p = 0; p < d; ++p)
+            out[(size_t)t * d + p] = (int16_t)isr_oracle_delta(T, R, isr_oracle_uniform64(seed, bank, 2u, first + t, p));
+}
+
 /* ------------------------------------------------------------------------ */
 /* Quantized network: parse the ISRM blob, run the integer forward pass.     */
 

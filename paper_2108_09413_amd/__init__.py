@@ -23,7 +23,7 @@ EXPORTS = [
     "isr_set_workspace", "isr_certify", "isr_predict", "isr_debug_noisy", "isr_debug_forward",
     "isr_debug_tensor", "isr_noise_table", "isr_cp_lower", "isr_normal_quantile", "isr_binom_pvalue",
     "isr_decide_certify", "isr_decide_predict", "isr_discrete_quantile", "isr_set_fusion", "isr_set_conv_tile", "isr_profile", "isr_profile_read", "isr_strerror",
-    "isr_last_device_error", "isr_certify_batch", "isr_predict_batch", "isr_certified_metrics",
+    "isr_last_device_error", "isr_certify_batch", "isr_predict_batch", "isr_certified_metrics", "isr_noise_bank",
 ]
 
 
@@ -88,6 +88,7 @@ def lib():
         L.isr_certify_batch.argtypes = [vp, vp, u32, C.POINTER(Item), u32, u32, u32, dbl, u64, C.POINTER(Result), vp, vp]
         L.isr_predict_batch.argtypes = [vp, vp, u32, C.POINTER(Item), u32, u32, dbl, u64, C.POINTER(Result), vp]
         L.isr_certified_metrics.argtypes = [C.POINTER(Result), vp, u32, vp, u32, C.POINTER(dbl), vp]
+        L.isr_noise_bank.argtypes = [u32, u64, u32, u32, u32, u32, vp, vp]
         L.isr_set_fusion.argtypes = [vp, C.c_int]
         L.isr_set_conv_tile.argtypes = [vp, C.c_int]
         L.isr_profile.argtypes = [vp, u32]
@@ -262,6 +263,18 @@ def isr_predict(model: Model, x, sigma: int, n: int, alpha: float, seed: int = 0
     _check(lib().isr_predict(model.handle, C.c_void_p(x.data_ptr()), sigma, n, alpha, C.c_uint64(seed), image_id,
                              C.byref(res), _np_ptr(c)), "isr_predict")
     return res, c
+
+
+def isr_noise_bank(sigma: int, seed: int, bank_id: int, first: int, count: int, d: int, out=None):
+    """int16 [count][d] torch tensor (device) of discrete-Gaussian draws for stored training noise."""
+    import torch
+    if out is None:
+        out = torch.empty((count, d), dtype=torch.int16, device="cuda")
+    assert out.dtype == torch.int16 and out.is_cuda and out.is_contiguous() and out.numel() == count * d
+    st = torch.cuda.current_stream()
+    _check(lib().isr_noise_bank(sigma, C.c_uint64(seed), bank_id, first, count, d, C.c_void_p(out.data_ptr()),
+                                C.c_void_p(st.cuda_stream)), "isr_noise_bank")
+    return out
 
 
 def _dev_images(xs):

@@ -758,6 +758,43 @@ int isr_discrete_quantile(uint32_t sigma, double p_lower, int32_t *t_out, uint64
     return ISR_OK;
 }
 
+int isr_noise_bank(uint32_t sigma, uint64_t seed, uint32_t bank_id, uint32_t first, uint32_t count, uint32_t d,
+                   int16_t *out_device, void *hip_stream) {
+    if (sigma < 1 || sigma > 1024 || !out_device || d == 0 || (d & 3) != 0) return ISR_ERR_ARG;
+    if ((uint64_t)first + count > (1ull << 32)) return ISR_ERR_ARG;
+    if (count == 0) return ISR_OK;
+    std::vector<uint64_t> T;
+    uint32_t R = 0;
+    if (!build_noise_table(sigma, T, R)) return ISR_ERR_ARG;
+    const size_t n = T.size();
+    // device form: high words, low words, guide table (as 32-bit words so that one upload carries all)
+    const size_t guide_words = (NOISE_GUIDE_SIZE + 2) / 2;
+    std::vector<uint32_t> host(2 * n + guide_words, 0);
+    for (size_t j = 0; j < n; ++j) { host[j] = (uint32_t)(T[j] >> 32); host[n + j] = (uint32_t)T[j]; }
+    uint16_t *guide = (uint16_t *)(host.data() + 2 * n);
+    size_t j = 0;
+    for (uint32_t b = 0; b <= NOISE_GUIDE_SIZE; ++b) {
+        const uint64_t start = (uint64_t)b << (32 - NOISE_GUIDE_BITS);
+        while (j < n && (uint64_t)host[j] < start) ++j;
+        guide[b] = (uint16_t)j;
+    }
+    hipStream_t st = (hipStream_t)hip_stream;
+    uint32_t *dev = nullptr;
+    HIP_TRY(hipMalloc((void **)&dev, host.size() * 4));
+    hipError_t e = hipMemcpyAsync(dev, host.data(), host.size() * 4, hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) {
+        NoiseBankParams p;
+        p.thi = dev; p.tlo = dev + n; p.guide = (const uint16_t *)(dev + 2 * n);
+        p.n = (int32_t)n; p.R = (int32_t)R; p.out = out_device; p.d = d;
+        p.key0 = (uint32_t)seed; p.key1 = (uint32_t)(seed >> 32); p.bank = bank_id; p.first = first; p.count = count;
+        e = launch_noise_bank(p, st);
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(st);   // the staging vector and the table die with this call
+    (void)hipFree(dev);
+    if (e != hipSuccess) { g_last_hip_error = (int)e; return ISR_ERR_DEVICE; }
+    return ISR_OK;
+}
+
 int isr_set_conv_tile(isr_model *m, int tile) {
     if (!m || tile < 0 || tile > 4) return ISR_ERR_ARG;
     m->conv_tile = tile;

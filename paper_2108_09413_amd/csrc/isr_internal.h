@@ -179,7 +179,18 @@ struct NoiseParams {
     uint64_t slot_begin;
 };
 
+// Stored-noise generator: count tensors of d draws each, int16.
+struct NoiseBankParams {
+    const uint32_t *thi, *tlo;   // [n] high / low words of the ascending thresholds (device)
+    const uint16_t *guide;       // [NOISE_GUIDE_SIZE + 2]: #{j : thi[j] < (b << (32 - NOISE_GUIDE_BITS))} (device)
+    int32_t n, R;                // n = 2R thresholds; draw = #{j : T[j] <= u} - R
+    int16_t *out;                // [count][d]
+    uint32_t d;                  // draws per tensor, a multiple of 4
+    uint32_t key0, key1, bank, first, count;
+};
+
 // Kernel launchers (kernels.hip / conv_igemm.hip).  All asynchronous on `st`.
+hipError_t launch_noise_bank(const NoiseBankParams &p, hipStream_t st);
 hipError_t launch_noise(const NoiseParams &p, hipStream_t st);
 hipError_t launch_conv(const ConvParams &p, hipStream_t st);
 hipError_t launch_stem_pool(const StemPoolParams &p, hipStream_t st);

@@ -146,6 +146,75 @@ hipError_t launch_noise(const NoiseParams &p, hipStream_t st) {
 }
 
 // ---------------------------------------------------------------------------
+// Noise bank: the discrete-Gaussian draws themselves (no image, no saturation), int16, for
+// noise that is sampled ahead of training and stored.  Same generator and counter layout as
+// above with the tensor index in the sample word, the bank id in the image word and phase 2;
+// the whole threshold table (2R entries) is searched, bucketed by a guide table on the top
+// 12 bits; the guide and the high words are staged into LDS (dynamic, 4 bytes per threshold),
+// the low words stay in global memory (read on a tie of the high words only).
+
+// #{j < n : T[j] <= u} when the guide bucket of u holds more than one candidate or the high
+// word ties with a threshold (rare): binary search inside the bucket, then the low words.
+__device__ __noinline__ int bank_count_slow(const uint32_t *thi_s, const uint16_t *guide, const NoiseBankParams &p,
+                                            uint32_t u, uint32_t grp, uint32_t tensor, int word) {
+    const uint32_t b = u >> (32 - NOISE_GUIDE_BITS);
+    int a = guide[b], e = guide[b + 1];              // thresholds with a high word below u end before guide[b + 1]
+    while (a < e) {                                  // first index whose high word is >= u
+        const int mid = (a + e) >> 1;
+        if (thi_s[mid] < u) a = mid + 1; else e = mid;
+    }
+    int c = a;
+    if (c < p.n && thi_s[c] == u) {                  // equal high words: the low words decide
+        uint32_t lo[4];
+        philox4x32_10(grp, tensor, p.bank, 5u, p.key0, p.key1, lo);
+        while (c < p.n && thi_s[c] == u && p.tlo[c] <= lo[word & 3]) ++c;
+    }
+    return c;
+}
+
+__global__ __launch_bounds__(256) void noise_bank_kernel(const NoiseBankParams p) {
+    __shared__ uint16_t guide[NOISE_GUIDE_SIZE + 2];
+    extern __shared__ uint32_t thi_s[];              // n high words, then two entries of 0xFFFFFFFF
+    for (int i = threadIdx.x; i < (int)(NOISE_GUIDE_SIZE + 2) / 2; i += 256)
+        ((uint32_t *)guide)[i] = ((const uint32_t *)p.guide)[i];
+    for (int i = threadIdx.x; i < p.n + 2; i += 256) thi_s[i] = i < p.n ? p.thi[i] : 0xFFFFFFFFu;
+    __syncthreads();
+    const uint64_t groups_per_tensor = p.d >> 2, total = groups_per_tensor * p.count;
+    for (uint64_t g = (uint64_t)blockIdx.x * 256 + threadIdx.x; g < total; g += (uint64_t)gridDim.x * 256) {
+        const uint32_t t = (uint32_t)(g / groups_per_tensor), grp = (uint32_t)(g - (uint64_t)t * groups_per_tensor);
+        const uint32_t tensor = p.first + t;
+        uint32_t hi[4];
+        philox4x32_10(grp, tensor, p.bank, 4u, p.key0, p.key1, hi);
+        int d4[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t u = hi[j];
+            int c = guide[u >> (32 - NOISE_GUIDE_BITS)];
+            const uint32_t t0 = thi_s[c], t1 = thi_s[c + 1];
+            c += t0 < u;
+            // common case: at most one threshold below u in the bucket and no tie
+            if ((t0 < u ? t1 : t0) <= u) c = bank_count_slow(thi_s, guide, p, u, grp, tensor, j);
+            d4[j] = c - p.R;
+        }
+        const uint32_t w0 = (uint32_t)(d4[0] & 0xFFFF) | ((uint32_t)d4[1] << 16), w1 = (uint32_t)(d4[2] & 0xFFFF) | ((uint32_t)d4[3] << 16);
+        *(uint2 *)(p.out + ((uint64_t)t * p.d + 4ull * grp)) = make_uint2(w0, w1);
+    }
+}
+
+hipError_t launch_noise_bank(const NoiseBankParams &p, hipStream_t st) {
+    if (p.count == 0) return hipSuccess;
+    if (p.d == 0 || (p.d & 3) != 0 || p.n < 2 || p.n > 32768 || !p.thi || !p.tlo || !p.guide || !p.out) return hipErrorInvalidValue;
+    const uint64_t total = (uint64_t)(p.d >> 2) * p.count;
+    uint64_t blocks = (total + 255) / 256;
+    if (blocks > 256 * 8) blocks = 256 * 8;
+    const size_t lds = ((size_t)p.n + 2) * 4;   // at most 128 KiB plus the 8 KiB guide: within the 160 KiB of a CU (sigma 1024 needs 72 KiB)
+    hipError_t e = hipFuncSetAttribute((const void *)noise_bank_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(noise_bank_kernel, dim3((unsigned)blocks), dim3(256), lds, st, p);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // Residual add of two int8 tensors with requantisation:
 //   out = clamp(z_o + RHA((qa - za) Ma + (qb - zb) Mb, shift), relu ? z_o : -128, 127)
 

@@ -60,6 +60,25 @@ def test_noisy_copies_224_shape_and_extreme_pixels(isr):
     m.close()
 
 
+@pytest.mark.parametrize("sigma", [1, 32, 256, 1024])
+def test_stored_training_noise_bank(isr, sigma):
+    """Unsaturated int16 draws for noise sampled ahead of training: bit-exact against
+    the oracle for a range of tensors that does not start at 0, a tensor size that
+    leaves the last workgroup ragged, and a tiny tensor."""
+    _say(f"noise bank parity sigma={sigma}")
+    for seed, bank, first, count, d in ((3, 2, 4094, 5, 3 * 32 * 32), (0xFFFFFFFF00000001, 9, 0, 3, 12)):
+        got = isr.isr_noise_bank(sigma, seed, bank, first, count, d).cpu().numpy()
+        want = oracle.noise_bank(sigma, seed, bank, first, count, d)
+        assert got.dtype == np.int16 and np.array_equal(got, want), (sigma, seed)
+    import ctypes
+    import torch
+    buf = torch.empty(64, dtype=torch.int16, device="cuda")
+    for bad_sigma, bad_d in ((0, 8), (1025, 8), (sigma, 6), (sigma, 0)):
+        rc = isr.lib().isr_noise_bank(bad_sigma, ctypes.c_uint64(0), 0, 0, 1, bad_d, ctypes.c_void_p(buf.data_ptr()), None)
+        assert rc == isr.ISR_ERR_ARG
+    assert isr.lib().isr_noise_bank(sigma, ctypes.c_uint64(0), 0, 0, 1, 8, None, None) == isr.ISR_ERR_ARG
+
+
 # ---- S3-S6: layer tensors ----------------------------------------------------
 
 def _check_all_tensors(isr, blob, x, sigma, seed=3, image=1, phase=1, sample=17, chunk=4):

@@ -177,3 +177,50 @@ def test_table_argument_domain():
         oracle.noise_table(1025)
     T, R = oracle.noise_table(1024)
     assert len(T) == 2 * R
+
+
+def test_noise_bank_counter_layout_and_range():
+    """Stored training noise: tensor index in the sample word, bank id in the image word,
+    phase 2 (counter word 4 | half), unsaturated draws.  Checked through the Philox routine
+    (pinned above by known answers) and a sorted-table lookup."""
+    sigma, seed, bank, first, count, d = 256, 0xFEDCBA9876543210, 5, 1000, 3, 64
+    T, R = oracle.noise_table(sigma)
+    got = oracle.noise_bank(sigma, seed, bank, first, count, d)
+    assert got.shape == (count, d) and got.dtype == np.int16
+    key = [seed & 0xFFFFFFFF, seed >> 32]
+    for t in range(count):
+        for p in range(d):
+            hi = oracle.philox4x32_10([p >> 2, first + t, bank, 4], key)
+            lo = oracle.philox4x32_10([p >> 2, first + t, bank, 5], key)
+            u = (int(hi[p & 3]) << 32) | int(lo[p & 3])
+            assert int(got[t, p]) == int(np.searchsorted(T, np.uint64(u), side="right")) - R
+    assert np.abs(got).max() > 255            # nothing saturates at the pixel range
+    # disjoint from the inference streams (phases 0 and 1) and from other banks / tensors
+    for phase in (0, 1):
+        other = np.array([oracle.delta(T, R, oracle.uniform64(seed, bank, phase, first, p)) for p in range(d)])
+        assert not np.array_equal(other, got[0])
+    assert not np.array_equal(oracle.noise_bank(sigma, seed, bank + 1, first, 1, d)[0], got[0])
+    assert not np.array_equal(got[0], got[1])
+    # a range of tensors is reproducible piecewise
+    assert np.array_equal(oracle.noise_bank(sigma, seed, bank, first + 1, 2, d), got[1:])
+
+
+@pytest.mark.parametrize("sigma", [2, 32])
+def test_noise_bank_empirical_law(sigma):
+    """Mean 0, variance sigma^2 and a chi-square of a stored bank against Def. 3.3."""
+    T, R = oracle.noise_table(sigma)
+    bank = oracle.noise_bank(sigma, 7, 1, 0, 64, 3072).astype(np.float64).reshape(-1)
+    n = bank.size
+    assert abs(bank.mean()) < 4 * sigma / np.sqrt(n)
+    assert abs(bank.var() / sigma ** 2 - 1) < 0.02
+    pmf, _ = _exact_pmf(sigma, R)
+    step = max(1, sigma // 4)
+    edges = list(range(-3 * sigma, 3 * sigma + 1, step))
+    obs = np.histogram(bank, bins=[-1e9] + [e - 0.5 for e in edges] + [1e9])[0]
+    probs, lo = [], -10 ** 6
+    for e in edges + [10 ** 6]:
+        probs.append(float(sum(pmf[abs(k)] for k in range(max(lo, -R - 300), min(e, R + 301)))))
+        lo = e
+    exp = np.array(probs) * n
+    chi2 = ((obs - exp) ** 2 / exp).sum()
+    assert chi2 < 70.0   # 25 degrees of freedom: P[chi2 > 70] ~ 4e-6
