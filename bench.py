@@ -131,7 +131,7 @@ def main():
     if conv_ms > 0:
         achieved = conv_ops / (conv_ms * 1e-3) / 1e12
         roofline = {
-            "bound": "mfma", "kernel": "conv_dma_kernel + conv_igemm_kernel (all tile variants)",
+            "bound": "mfma", "kernel": "all convolution kernels: conv_dma_kernel (all tiles), bottleneck_kernel, stem_pool_kernel",
             "achieved": round(achieved, 2), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
             "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4), "traffic": None,
             "launches_timed": conv_launches,

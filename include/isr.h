@@ -208,7 +208,9 @@ int isr_certified_metrics(const isr_result *results, const int32_t *labels, uint
 /* Kernel-variant switch for parity checks: enable != 0 (the default) lets the
  * library fuse ops of the blob into one kernel where it can (a residual add into
  * the convolution before it; the first convolution with the max pooling after
- * it; a 1x1 convolution that only feeds a residual add into that add's kernel);
+ * it; a 1x1 convolution that only feeds a residual add into that add's kernel;
+ * whole residual blocks of the narrow nets; the convolutions of a bottleneck block
+ * with 64 middle channels);
  * 0 runs every op of the blob as its own kernel.  Results are identical either
  * way; tensors that a fused kernel never stores are served by the unfused plan
  * in isr_debug_tensor. */

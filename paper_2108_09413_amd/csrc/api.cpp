@@ -38,7 +38,9 @@ struct DevOp {
     ConvParams conv{};
     int stem_pool = 0;                  // conv fused with the max pooling after it (out = the pooled tensor)
     int block = 0;                      // identity residual block: this conv, conv2 and the add in one kernel
+    int bneck = 0;                      // 1: this 1x1 conv and the 3x3 conv2 in one kernel; 2: plus conv3 (1x1 + residual add)
     ConvParams conv2{};
+    ConvParams conv3{};
     AddParams add{};
     PoolParams pool{};
     GapParams gap{};
@@ -68,7 +70,7 @@ struct Plan {
 struct isr_model {
     ParsedModel pm;
     std::vector<DevOp> ops;             // one descriptor per op of the blob
-    Plan plan[2];                       // [0] op by op, [1] residual adds fused into the preceding conv
+    Plan plan[2];                       // [0] op by op, [1] with every fusion the kernels cover
     int use_fused = 1;
     int conv_tile = 0;                  // forced conv output tile (0 = automatic)
     uint8_t *dconst = nullptr;          // weights and per-channel tables
@@ -254,6 +256,46 @@ void fuse_basic_blocks(const ParsedModel &pm, std::vector<DevOp> &ops) {
         a.bytes_per_sample = (double)pm.tensors[a.a].C * ca.H * ca.W + (double)pm.tensors[b.out].C * ca.H * ca.W;
         a.out = b.out;
         ops.erase(ops.begin() + i + 1);
+    }
+}
+
+// Folds conv1x1 (-> 64 channels) -> conv3x3 (64 -> 64) of a bottleneck block into one kernel,
+// and with them the closing conv1x1 + residual add when the residual is the block input.
+// Runs on the list in which the adds are already folded into their convolutions.
+void fuse_bottlenecks(const ParsedModel &pm, std::vector<DevOp> &ops) {
+    std::vector<int> uses(pm.tensors.size(), 0);
+    for (const DevOp &d : ops) {
+        if (d.a >= 0) uses[d.a]++;
+        if (d.b >= 0) uses[d.b]++;
+    }
+    auto plain = [](const DevOp &d) { return d.type == OP_CONV && !d.stem_pool && !d.block && !d.bneck && !d.conv.c4 && d.conv.fast_requant; };
+    for (size_t i = 0; i + 1 < ops.size(); ++i) {
+        DevOp &a = ops[i];
+        const DevOp &b = ops[i + 1];
+        if (!plain(a) || !plain(b) || a.conv.fuse_add || b.conv.fuse_add) continue;
+        const ConvParams &c1 = a.conv, &c2 = b.conv;
+        if (c1.k != 1 || c1.stride != 1 || c1.pad != 0 || c1.Kp != c1.Cin_p || c1.Cout_p != 64) continue;
+        if (c2.k != 3 || c2.stride != 1 || c2.pad != 1 || c2.Cin_p != 64 || c2.Cout_p != 64 || c2.Kp != 576) continue;
+        if (b.a != a.out || uses[a.out] != 1 || !bottleneck_supported(c1.Cin_p, 64, 0, 0)) continue;
+        a.bneck = 1;
+        a.conv2 = c2;
+        a.ops_per_sample += b.ops_per_sample;
+        a.bytes_per_sample = (double)pm.tensors[a.a].C * c1.H * c1.W + (double)pm.tensors[b.out].C * c1.H * c1.W;
+        a.out = b.out;
+        ops.erase(ops.begin() + i + 1);
+        if (i + 1 < ops.size()) {
+            const DevOp &c = ops[i + 1];
+            const ConvParams &c3 = c.conv;
+            if (plain(c) && c3.fuse_add == 1 && c3.k == 1 && c3.stride == 1 && c3.pad == 0 && c3.Cin_p == 64 && c3.Kp == 64 &&
+                c.a == a.out && c.b == a.a && uses[a.out] == 1 && bottleneck_supported(c1.Cin_p, 64, c3.Cout_p, 1)) {
+                a.bneck = 2;
+                a.conv3 = c3;
+                a.ops_per_sample += c.ops_per_sample;
+                a.bytes_per_sample = 2.0 * pm.tensors[a.a].C * c1.H * c1.W;
+                a.out = c.out;
+                ops.erase(ops.begin() + i + 1);
+            }
+        }
     }
 }
 
@@ -545,6 +587,30 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
                         HIP_TRY(launch_basic_block(bp, m->stream));
                         break;
                     }
+                    if (d.bneck) {
+                        const ConvParams &c1 = d.conv, &c2 = d.conv2, &c3 = d.conv3;
+                        BneckParams bp{};
+                        bp.in = (const int8_t *)(ws + pl.toff[d.a]);
+                        bp.out = (int8_t *)(ws + pl.toff[d.out]);
+                        bp.w1 = c1.w; bp.bias1 = c1.bias; bp.m0s1 = c1.m0s; bp.chi1 = c1.chi; bp.shm11 = c1.shm1;
+                        bp.w2 = c2.w; bp.bias2 = c2.bias; bp.m0s2 = c2.m0s; bp.chi2 = c2.chi; bp.shm12 = c2.shm1;
+                        bp.zpad = c1.zpad;
+                        bp.Cin_p = c1.Cin_p; bp.H = c1.H; bp.W = c1.W; bp.B = (int32_t)cnt; bp.tail = d.bneck == 2;
+                        bp.zp_t1 = c1.zp_out;
+                        bp.lo1 = c1.relu ? c1.zp_out : -128;
+                        bp.lo2 = c2.relu ? c2.zp_out : -128;
+                        bp.tie_free = c1.tie_free && c2.tie_free;
+                        if (bp.tail) {
+                            bp.w3 = c3.w; bp.bias3 = c3.bias; bp.m0s3 = c3.m0s; bp.chi3 = c3.chi; bp.shm13 = c3.shm1;
+                            bp.Cout_p = c3.Cout_p;
+                            bp.lo3 = c3.relu ? c3.zp_out : -128;
+                            bp.add_mul_self = c3.add_mul_self; bp.add_mul_res = c3.add_mul_res; bp.add_c0 = c3.add_c0;
+                            bp.add_k = c3.add_k; bp.add_sh = c3.add_sh; bp.add_lo = c3.add_lo;
+                            bp.tie_free = bp.tie_free && c3.tie_free && c3.add_tie_free;
+                        }
+                        HIP_TRY(launch_bottleneck(bp, m->stream));
+                        break;
+                    }
                     ConvParams c = d.conv;
                     c.in = (const int8_t *)(ws + pl.toff[d.a]);
                     c.out = (int8_t *)(ws + pl.toff[d.out]);
@@ -733,6 +799,7 @@ int isr_load_model(const void *blob_host, size_t bytes, isr_model **out) {
     fuse_adds(m->pm, m->ops, m->plan[1].ops);
     fuse_stem_pool(m->pm, m->plan[1].ops);
     fuse_basic_blocks(m->pm, m->plan[1].ops);
+    fuse_bottlenecks(m->pm, m->plan[1].ops);
     *out = m;
     return ISR_OK;
 }

@@ -79,6 +79,16 @@ __device__ __forceinline__ uint32_t pack4(int a, int b, int c, int d) {
     return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
 }
 
+// 16 bytes per lane from global memory into LDS: lane l of the wave writes bytes
+// [16 l, 16 l + 16) after the wave-uniform LDS address `lptr`.
+#define ISR_GLOBAL_TO_LDS16(gptr, lptr)                                                             \
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gptr),        \
+                                     (__attribute__((address_space(3))) void *)(lptr), 16, 0, 0)
+
+// The compiler does not order LDS reads after loads that write LDS; this wait does.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
 }  // namespace isr
 
 #endif

@@ -322,16 +322,6 @@ __global__ __launch_bounds__(256, MINW) void conv_igemm_kernel(const ConvParams 
 
 // ---- direct-to-LDS kernel ---------------------------------------------------
 
-// 16 bytes per lane from global memory into LDS: lane l of the wave writes bytes
-// [16 l, 16 l + 16) after the wave-uniform LDS address `lptr`.
-#define ISR_GLOBAL_TO_LDS16(gptr, lptr)                                                             \
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gptr),        \
-                                     (__attribute__((address_space(3))) void *)(lptr), 16, 0, 0)
-
-// The compiler does not order LDS reads after loads that write LDS; this wait does.
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
-
 // FUSE: 0 plain, 1 residual add with the residual read from memory, 2 residual add with the
 // residual computed here by a second (1x1, stride 1) convolution.
 template <int BM, int BN, int KB, int NST, int FUSE, int MINB, bool TF>

@@ -124,6 +124,25 @@ struct BlockParams {
     int32_t tie_free;            // both convolutions and the add are free of rounding ties
 };
 
+// Bottleneck block with 64 middle channels in one kernel (bottleneck.hip): conv1x1 -> conv3x3
+// [-> conv1x1 + residual add with the block input when tail != 0].
+struct BneckParams {
+    const int8_t *in;        // [B][H][W][Cin_p] block input x (also the residual of the tail)
+    int8_t *out;             // tail: [B][H][W][Cout_p]; else the 3x3 output [B][H][W][64]
+    const int8_t *w1;        // [>= 64][Cin_p] rows in MFMA row order
+    const int8_t *w2;        // [>= 64][576], K = (tap, channel)
+    const int8_t *w3;        // [>= Cout_p][64] (tail)
+    const int32_t *bias1, *m0s1, *chi1, *shm11;   // as in ConvParams, per convolution
+    const int32_t *bias2, *m0s2, *chi2, *shm12;
+    const int32_t *bias3, *m0s3, *chi3, *shm13;
+    const int8_t *zpad;      // 16 readable bytes (source of halo pixels outside the image)
+    int32_t Cin_p, Cout_p, H, W, B, tail;
+    int32_t zp_t1;           // zero-point of the first convolution's output (padding value of the 3x3)
+    int32_t lo1, lo2, lo3;   // lower clamps of the three int8 results
+    int32_t add_mul_self, add_mul_res, add_c0, add_k, add_sh, add_lo;   // as in ConvParams
+    int32_t tie_free;        // every requantisation (and the add) is free of rounding ties
+};
+
 struct AddParams {
     const int8_t *a, *b;
     int8_t *out;
@@ -198,6 +217,8 @@ bool stem_pool_supported(int k, int stride, int pad, int cout_p, int H, int W, i
                          int pool_stride, int pool_pad);
 hipError_t launch_basic_block(const BlockParams &p, hipStream_t st);
 bool basic_block_supported(int channels, int size);
+hipError_t launch_bottleneck(const BneckParams &p, hipStream_t st);
+bool bottleneck_supported(int cin_p, int cmid_p, int cout_p, int tail);
 hipError_t launch_add(const AddParams &p, hipStream_t st);
 hipError_t launch_maxpool(const PoolParams &p, hipStream_t st);
 hipError_t launch_gap(const GapParams &p, hipStream_t st);

@@ -199,6 +199,48 @@ def test_identity_residual_blocks_in_one_kernel(isr):
     m.close()
 
 
+@pytest.mark.parametrize("shape", [(30, 20), (28, 28), (5, 40)])
+def test_bottleneck_blocks_in_one_kernel(isr, shape):
+    """conv1x1 -> conv3x3 (64 middle channels) [-> conv1x1 + add with the block input] as one
+    kernel working on 14 x 14 pixel tiles: images that leave ragged tiles in both directions,
+    one exactly two tiles wide and one lower than a tile; block widths 64 / 128 / 256 (one to
+    four K steps); zero-points on every tensor, ReLU on and off, a block with power-of-two
+    multipliers (rounding ties), a block whose residual comes from a projection (head only)."""
+    h, w = shape
+    _say(f"layer parity fused bottleneck blocks {h}x{w}")
+    b = NetBuilder(rng=np.random.default_rng(81), in_shape=(3, h, w), num_classes=5)
+    t = b.conv(b.tensor(3, h, w, 0, 74.0), 64, 3, 1, 1, True)
+    def block(x, cx, z1, z2, z3, zo, relu12=True, relu_out=True, pow2=False, project=False):
+        kw = dict(m0=np.full(64, 1 << 30, dtype=np.int64), sh=np.full(64, 9)) if pow2 else {}
+        u = b.conv(x, 64, 1, 1, 0, relu12, zp_out=z1, **kw)
+        u = b.conv(u, 64, 3, 1, 1, relu12, zp_out=z2, **kw)
+        if project:
+            r = b.conv(x, cx, 1, 1, 0, False, zp_out=5)
+            u = b.conv(u, cx, 1, 1, 0, False, zp_out=z3)
+            return b.add(r, u, relu_out, zp_out=zo)
+        u = b.conv(u, cx, 1, 1, 0, False, zp_out=z3)
+        if pow2:
+            return b.add(x, u, relu_out, ma=1 << 19, mb=1 << 19, sh=20, zp_out=zo)
+        return b.add(x, u, relu_out, zp_out=zo)
+    t = block(t, 64, -128, -128, 0, -128)
+    t = block(t, 256, -100, 7, 3, -128, project=True)
+    t = block(t, 256, -128, -128, 0, -128)
+    t = block(t, 256, 9, -20, -6, 11, relu12=False, relu_out=False)
+    t = block(t, 256, -128, -128, 4, -128, pow2=True)
+    t = b.conv(t, 128, 1, 1, 0, True)
+    t = block(t, 128, -128, -90, 0, -128)
+    b.fc(b.gap(t), 5)
+    blob = b.blob()
+    x = np.random.default_rng(12).integers(0, 256, size=(3, h, w)).astype(np.uint8)
+    _check_all_tensors(isr, blob, x, 64, sample=2, chunk=3)
+    m = _load(isr, blob, 5)
+    om = oracle.Model(blob)
+    lg, am, cnt = isr.isr_debug_forward(m, x, 64, 3, 1, 1, 50, 5)
+    olg, oam, ocnt = om.mc(x, 64, 3, 1, 1, 50, 5)
+    assert np.array_equal(lg, olg) and np.array_equal(cnt, ocnt)
+    m.close()
+
+
 def test_residual_computed_by_a_second_convolution(isr):
     """Projection-shortcut pattern: the residual of an add is the output of a 1x1
     convolution issued right before the add's other convolution; the fused plan then
@@ -330,9 +372,10 @@ def test_resnet20_logits_and_votes(isr):
         lg, am, cnt = isr.isr_debug_forward(m, x, sigma, 0, item, 0, 0, 100)
         olg, oam, ocnt = om.mc(x, sigma, 0, item, 0, 0, 100)
         assert np.array_equal(lg, olg) and np.array_equal(am, oam) and np.array_equal(cnt, ocnt)
-        lg, am, cnt = isr.isr_debug_forward(m, x, sigma, 0, item, 1, 99700, 300)
-        olg, oam, ocnt = om.mc(x, sigma, 0, item, 1, 99700, 300)
-        assert np.array_equal(lg, olg) and np.array_equal(am, oam) and np.array_equal(cnt, ocnt)
+        for begin, count in ((0, 1000), (99700, 300)):     # first and last estimation samples of n = 100000
+            lg, am, cnt = isr.isr_debug_forward(m, x, sigma, 0, item, 1, begin, count)
+            olg, oam, ocnt = om.mc(x, sigma, 0, item, 1, begin, count)
+            assert np.array_equal(lg, olg) and np.array_equal(am, oam) and np.array_equal(cnt, ocnt)
     m.close()
 
 
@@ -342,8 +385,8 @@ def test_resnet110_logits(isr):
     om = oracle.Model(blob)
     m = _load(isr, blob, 64)
     x = synth.make_image(2, 1)
-    lg, am, cnt = isr.isr_debug_forward(m, x, 64, 0, 1, 1, 500, 96)
-    olg, oam, ocnt = om.mc(x, 64, 0, 1, 1, 500, 96)
+    lg, am, cnt = isr.isr_debug_forward(m, x, 64, 0, 1, 1, 500, 256)
+    olg, oam, ocnt = om.mc(x, 64, 0, 1, 1, 500, 256)
     assert np.array_equal(lg, olg) and np.array_equal(am, oam) and np.array_equal(cnt, ocnt)
     m.close()
 
@@ -356,7 +399,7 @@ def test_resnet50_full_size_logits(isr):
     om = oracle.Model(blob)
     m = _load(isr, blob, 8)
     x = synth.make_image(3, 1)
-    for sigma, phase, begin, count in ((64, 0, 0, 6), (128, 1, 99994, 6)):
+    for sigma, phase, begin, count in ((64, 0, 0, 12), (128, 1, 99988, 12), (32, 1, 50000, 8), (256, 0, 92, 8)):
         _say(f"  sigma={sigma} phase={phase} begin={begin}")
         lg, am, cnt = isr.isr_debug_forward(m, x, sigma, 0, 1, phase, begin, count)
         olg, oam, ocnt = om.mc(x, sigma, 0, 1, phase, begin, count)
