@@ -37,7 +37,9 @@ struct DevOp {
     double ops_per_sample = 0.0, bytes_per_sample = 0.0;   // algorithmic, for the timing report
     ConvParams conv{};
     int stem_pool = 0;                  // conv fused with the max pooling after it (out = the pooled tensor)
+    int stem16 = 0;                     // first 3x3 convolution into 16 channels: the LDS-resident kernel
     int block = 0;                      // identity residual block: this conv, conv2 and the add in one kernel
+    int trans = 0;                      // down-sampling block: this conv (3x3/2), conv2 (3x3) and conv3 (1x1/2 + add) in one kernel
     int bneck = 0;                      // 1: this 1x1 conv and the 3x3 conv2 in one kernel; 2: plus conv3 (1x1 + residual add)
     ConvParams conv2{};
     ConvParams conv3{};
@@ -259,6 +261,41 @@ void fuse_basic_blocks(const ParsedModel &pm, std::vector<DevOp> &ops) {
     }
 }
 
+// Folds the down-sampling block of the narrow nets -- conv3x3 stride 2, conv3x3, and the 1x1
+// stride-2 projection that carries the residual add -- into one kernel for the shapes that fit LDS.
+void fuse_trans_blocks(const ParsedModel &pm, std::vector<DevOp> &ops) {
+    std::vector<int> uses(pm.tensors.size(), 0);
+    for (const DevOp &d : ops) {
+        if (d.a >= 0) uses[d.a]++;
+        if (d.b >= 0) uses[d.b]++;
+    }
+    auto plain = [](const DevOp &d) {
+        return d.type == OP_CONV && !d.stem_pool && !d.stem16 && !d.block && !d.bneck && !d.trans && !d.conv.c4 && d.conv.fast_requant;
+    };
+    for (size_t i = 0; i + 2 < ops.size(); ++i) {
+        DevOp &a = ops[i];
+        const DevOp &b = ops[i + 1], &c = ops[i + 2];
+        if (!plain(a) || !plain(b) || !plain(c) || a.conv.fuse_add || b.conv.fuse_add || c.conv.fuse_add != 1) continue;
+        const ConvParams &c1 = a.conv, &c2 = b.conv, &cp = c.conv;
+        const int C = c1.Cout_p, S = c1.Ho;
+        if (c1.k != 3 || c1.stride != 2 || c1.pad != 1 || c2.k != 3 || c2.stride != 1 || c2.pad != 1 || cp.k != 1 ||
+            cp.stride != 2 || cp.pad != 0)
+            continue;
+        if (2 * c1.Cin_p != C || c2.Cin_p != C || c2.Cout_p != C || cp.Cin_p != c1.Cin_p || cp.Cout_p != C || c1.H != 2 * S ||
+            c1.W != 2 * S || c1.Wo != S || cp.Ho != S || cp.Wo != S || !trans_block_supported(C, S))
+            continue;
+        if (c1.Kp != (9 * c1.Cin_p + 63) / 64 * 64 || c2.Kp != (9 * C + 63) / 64 * 64 || cp.Kp != 64) continue;
+        if (b.a != a.out || c.a != a.a || c.b != b.out || uses[a.out] != 1 || uses[b.out] != 1) continue;
+        a.trans = 1;
+        a.conv2 = c2;
+        a.conv3 = cp;
+        a.ops_per_sample += b.ops_per_sample + c.ops_per_sample;
+        a.bytes_per_sample = (double)pm.tensors[a.a].C * c1.H * c1.W + (double)pm.tensors[c.out].C * S * S;
+        a.out = c.out;
+        ops.erase(ops.begin() + i + 1, ops.begin() + i + 3);
+    }
+}
+
 // Folds conv1x1 (-> 64 channels) -> conv3x3 (64 -> 64) of a bottleneck block into one kernel,
 // and with them the closing conv1x1 + residual add when the residual is the block input.
 // Runs on the list in which the adds are already folded into their convolutions.
@@ -268,7 +305,9 @@ void fuse_bottlenecks(const ParsedModel &pm, std::vector<DevOp> &ops) {
         if (d.a >= 0) uses[d.a]++;
         if (d.b >= 0) uses[d.b]++;
     }
-    auto plain = [](const DevOp &d) { return d.type == OP_CONV && !d.stem_pool && !d.block && !d.bneck && !d.conv.c4 && d.conv.fast_requant; };
+    auto plain = [](const DevOp &d) {
+        return d.type == OP_CONV && !d.stem_pool && !d.stem16 && !d.block && !d.trans && !d.bneck && !d.conv.c4 && d.conv.fast_requant;
+    };
     for (size_t i = 0; i + 1 < ops.size(); ++i) {
         DevOp &a = ops[i];
         const DevOp &b = ops[i + 1];
@@ -571,6 +610,17 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
                         HIP_TRY(launch_stem_pool(sp, m->stream));
                         break;
                     }
+                    if (d.stem16) {
+                        const ConvParams &c = d.conv;
+                        Stem16Params sp;
+                        sp.in = (const int8_t *)(ws + pl.toff[d.a]);
+                        sp.out = (int8_t *)(ws + pl.toff[d.out]);
+                        sp.w = c.w; sp.bias = c.bias; sp.m0s = c.m0s; sp.chi = c.chi; sp.shm1 = c.shm1;
+                        sp.H = c.H; sp.W = c.W; sp.B = (int32_t)cnt; sp.zp_in = c.zp_in;
+                        sp.lo = c.relu ? c.zp_out : -128; sp.tie_free = c.tie_free;
+                        HIP_TRY(launch_stem16(sp, m->stream));
+                        break;
+                    }
                     if (d.block) {
                         const ConvParams &c1 = d.conv, &c2 = d.conv2;
                         BlockParams bp;
@@ -585,6 +635,25 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
                         bp.add_k = c2.add_k; bp.add_sh = c2.add_sh; bp.add_lo = c2.add_lo;
                         bp.tie_free = c1.tie_free && c2.tie_free && c2.add_tie_free;
                         HIP_TRY(launch_basic_block(bp, m->stream));
+                        break;
+                    }
+                    if (d.trans) {
+                        const ConvParams &c1 = d.conv, &c2 = d.conv2, &cp = d.conv3;
+                        TransParams tp{};
+                        tp.in = (const int8_t *)(ws + pl.toff[d.a]);
+                        tp.out = (int8_t *)(ws + pl.toff[d.out]);
+                        tp.w1 = c1.w; tp.bias1 = c1.bias; tp.m0s1 = c1.m0s; tp.chi1 = c1.chi; tp.shm11 = c1.shm1;
+                        tp.w2 = c2.w; tp.bias2 = c2.bias; tp.m0s2 = c2.m0s; tp.chi2 = c2.chi; tp.shm12 = c2.shm1;
+                        tp.wp = cp.w; tp.biasp = cp.bias; tp.m0sp = cp.m0s; tp.chip = cp.chi; tp.shm1p = cp.shm1;
+                        tp.C = c1.Cout_p; tp.S = c1.Ho; tp.B = (int32_t)cnt;
+                        tp.zp_x = c1.zp_in; tp.zp_t = c1.zp_out;
+                        tp.lo1 = c1.relu ? c1.zp_out : -128;
+                        tp.lo2 = c2.relu ? c2.zp_out : -128;
+                        tp.lop = cp.relu ? cp.zp_out : -128;
+                        tp.add_mul_self = cp.add_mul_self; tp.add_mul_res = cp.add_mul_res; tp.add_c0 = cp.add_c0;
+                        tp.add_k = cp.add_k; tp.add_sh = cp.add_sh; tp.add_lo = cp.add_lo;
+                        tp.tie_free = c1.tie_free && c2.tie_free && cp.tie_free && cp.add_tie_free;
+                        HIP_TRY(launch_trans_block(tp, m->stream));
                         break;
                     }
                     if (d.bneck) {
@@ -798,7 +867,15 @@ int isr_load_model(const void *blob_host, size_t bytes, isr_model **out) {
     m->plan[0].ops = m->ops;
     fuse_adds(m->pm, m->ops, m->plan[1].ops);
     fuse_stem_pool(m->pm, m->plan[1].ops);
+    if (!m->plan[1].ops.empty()) {
+        DevOp &f = m->plan[1].ops[0];
+        const ConvParams &c = f.conv;
+        if (f.type == OP_CONV && c.c4 && !c.fuse_add && !f.stem_pool && c.Kp == 64 &&
+            stem16_supported(c.k, c.stride, c.pad, c.Cout_p, c.H, c.W, c.fast_requant))
+            f.stem16 = 1;
+    }
     fuse_basic_blocks(m->pm, m->plan[1].ops);
+    fuse_trans_blocks(m->pm, m->plan[1].ops);
     fuse_bottlenecks(m->pm, m->plan[1].ops);
     *out = m;
     return ISR_OK;

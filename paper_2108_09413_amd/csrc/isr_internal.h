@@ -109,6 +109,16 @@ struct StemPoolParams {
     int32_t zp_in, zp_out, relu, tie_free, B;
 };
 
+// First convolution of the narrow small-image nets: 3x3 stride 1 pad 1 on the NHWC4 image
+// into 16 stored channels (stem16.hip).
+struct Stem16Params {
+    const int8_t *in;        // [B][H][W][4]
+    int8_t *out;             // [B][H][W][16]
+    const int8_t *w;         // [16][64], K = (ky, kx padded to 4, channel padded to 4)
+    const int32_t *bias, *m0s, *chi, *shm1;
+    int32_t H, W, B, zp_in, lo, tie_free;
+};
+
 // Identity residual block in one kernel: t = conv3x3(x), y = add(conv3x3(t), x); both
 // convolutions C -> C channels, stride 1, pad 1, on S x S images (basic_block.hip).
 struct BlockParams {
@@ -141,6 +151,22 @@ struct BneckParams {
     int32_t lo1, lo2, lo3;   // lower clamps of the three int8 results
     int32_t add_mul_self, add_mul_res, add_c0, add_k, add_sh, add_lo;   // as in ConvParams
     int32_t tie_free;        // every requantisation (and the add) is free of rounding ties
+};
+
+// Down-sampling residual block in one kernel (trans_block.hip): t = conv3x3/2(x), u = conv3x3(t),
+// r = conv1x1/2(x), y = add(r, u); x has C/2 channels on 2S x 2S pixels.
+struct TransParams {
+    const int8_t *in;        // [B][2S][2S][C/2]
+    int8_t *out;             // [B][S][S][C]
+    const int8_t *w1, *w2, *wp;   // weight rows in MFMA row order: [C][9 C/2 -> 64-multiple], [C][9 C -> 64-multiple], [C][64]
+    const int32_t *bias1, *m0s1, *chi1, *shm11;   // as in ConvParams, per convolution
+    const int32_t *bias2, *m0s2, *chi2, *shm12;
+    const int32_t *biasp, *m0sp, *chip, *shm1p;
+    int32_t C, S, B;
+    int32_t zp_x, zp_t;      // zero-points of x and t (their padding values)
+    int32_t lo1, lo2, lop;   // lower clamps of t, u, r
+    int32_t add_mul_self, add_mul_res, add_c0, add_k, add_sh, add_lo;   // as in ConvParams; "self" is the projection r
+    int32_t tie_free;
 };
 
 struct AddParams {
@@ -215,10 +241,14 @@ hipError_t launch_conv(const ConvParams &p, hipStream_t st);
 hipError_t launch_stem_pool(const StemPoolParams &p, hipStream_t st);
 bool stem_pool_supported(int k, int stride, int pad, int cout_p, int H, int W, int fast_requant, int pool_k,
                          int pool_stride, int pool_pad);
+hipError_t launch_stem16(const Stem16Params &p, hipStream_t st);
+bool stem16_supported(int k, int stride, int pad, int cout_p, int H, int W, int fast_requant);
 hipError_t launch_basic_block(const BlockParams &p, hipStream_t st);
 bool basic_block_supported(int channels, int size);
 hipError_t launch_bottleneck(const BneckParams &p, hipStream_t st);
 bool bottleneck_supported(int cin_p, int cmid_p, int cout_p, int tail);
+hipError_t launch_trans_block(const TransParams &p, hipStream_t st);
+bool trans_block_supported(int cout, int size_out);
 hipError_t launch_add(const AddParams &p, hipStream_t st);
 hipError_t launch_maxpool(const PoolParams &p, hipStream_t st);
 hipError_t launch_gap(const GapParams &p, hipStream_t st);

@@ -145,6 +145,31 @@ def test_first_layer_7x7_stride2(isr):
     _check_all_tensors(isr, b.blob(), x, 32)
 
 
+@pytest.mark.parametrize("shape", [(32, 32), (48, 16), (7, 64)])
+def test_first_layer_3x3_into_16_channels(isr, shape):
+    """The LDS-resident first layer of the narrow nets (3x3, stride 1, pad 1, 16 stored
+    channels): 13 real channels, ReLU off with a non-trivial output zero-point, one variant
+    with power-of-two multipliers (rounding ties), 6 copies (ragged against 4 images per
+    workgroup); image sizes with one, two and four 16-pixel strips."""
+    h, w = shape
+    _say(f"layer parity first 3x3 layer {h}x{w}")
+    for pow2 in (False, True):
+        b = NetBuilder(rng=np.random.default_rng(91), in_shape=(3, h, w), num_classes=4)
+        kw = dict(m0=np.full(13, 1 << 30, dtype=np.int64), sh=np.full(13, 7)) if pow2 else {}
+        t1 = b.conv(b.tensor(3, h, w, 0, 74.0), 13, 3, 1, 1, pow2, zp_out=-128 if pow2 else 9, **kw)
+        t2 = b.conv(t1, 32, 3, 2, 1, True)
+        b.fc(b.gap(t2), 4)
+        blob = b.blob()
+        x = np.random.default_rng(13).integers(0, 256, size=(3, h, w)).astype(np.uint8)
+        _check_all_tensors(isr, blob, x, 64, sample=1, chunk=3)
+        m = _load(isr, blob, 6)
+        om = oracle.Model(blob)
+        lg, am, cnt = isr.isr_debug_forward(m, x, 128, 5, 2, 0, 7, 6)
+        olg, oam, ocnt = om.mc(x, 128, 5, 2, 0, 7, 6)
+        assert np.array_equal(lg, olg) and np.array_equal(cnt, ocnt)
+        m.close()
+
+
 @pytest.mark.parametrize("shape", [(224, 224), (64, 64), (37, 28), (30, 44), (9, 8)])
 def test_first_layer_fused_with_max_pooling(isr, shape):
     """7x7/2 convolution into 64 channels followed by 3x3/2 max pooling (one fused kernel):
@@ -197,6 +222,37 @@ def test_identity_residual_blocks_in_one_kernel(isr):
     olg, oam, ocnt = om.mc(x, 64, 2, 1, 1, 100, 7)
     assert np.array_equal(lg, olg) and np.array_equal(cnt, ocnt)
     m.close()
+
+
+def test_downsampling_residual_blocks_in_one_kernel(isr):
+    """conv3x3 stride 2 -> conv3x3 with a 1x1 stride-2 projection shortcut and the add, at
+    the two shapes that run as one LDS-resident kernel (16 -> 32 channels at 32x32 -> 16x16,
+    32 -> 64 at 16x16 -> 8x8): zero-points on every tensor, ReLU on and off, a variant with
+    power-of-two multipliers (rounding ties), 5 copies (ragged against 2 images per workgroup)."""
+    _say("layer parity fused down-sampling blocks")
+    for pow2 in (False, True):
+        b = NetBuilder(rng=np.random.default_rng(101), in_shape=(3, 32, 32), num_classes=6)
+        t = b.conv(b.tensor(3, 32, 32, 0, 74.0), 16, 3, 1, 1, True, zp_out=-128 if not pow2 else -90)
+        def down(x, ch, z1, z2, zp, zo, relu1, relu_out):
+            kw = dict(m0=np.full(ch, 1 << 30, dtype=np.int64), sh=np.full(ch, 8)) if pow2 else {}
+            u = b.conv(x, ch, 3, 2, 1, relu1, zp_out=z1, **kw)
+            u = b.conv(u, ch, 3, 1, 1, False, zp_out=z2, **kw)
+            r = b.conv(x, ch, 1, 2, 0, False, zp_out=zp)
+            if pow2:
+                return b.add(u, r, relu_out, ma=1 << 19, mb=1 << 19, sh=20, zp_out=zo)
+            return b.add(u, r, relu_out, zp_out=zo)
+        t = down(t, 32, -128, 0, 0, -128, True, True)
+        t = down(t, 64, 11, -7, 5, 3, False, False)
+        b.fc(b.gap(t), 6)
+        blob = b.blob()
+        x = np.random.default_rng(14).integers(0, 256, size=(3, 32, 32)).astype(np.uint8)
+        _check_all_tensors(isr, blob, x, 64, sample=3, chunk=3)
+        m = _load(isr, blob, 5)
+        om = oracle.Model(blob)
+        lg, am, cnt = isr.isr_debug_forward(m, x, 32, 6, 1, 1, 40, 5)
+        olg, oam, ocnt = om.mc(x, 32, 6, 1, 1, 40, 5)
+        assert np.array_equal(lg, olg) and np.array_equal(cnt, ocnt)
+        m.close()
 
 
 @pytest.mark.parametrize("shape", [(30, 20), (28, 28), (5, 40)])
