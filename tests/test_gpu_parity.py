@@ -488,6 +488,30 @@ def test_resnet50_in_the_benchmarked_launch_configuration(isr):
     m.close()
 
 
+@pytest.mark.parametrize("cfg,chunk", [(1, 8192), (2, 4096)])
+def test_cifar_nets_in_the_benchmarked_launch_configuration(isr, cfg, chunk):
+    """bench.py's configuration for the narrow nets: one full chunk (8192 / 4096 noisy
+    copies) through the LDS-resident block kernels.  Votes must add up, sampled copies
+    (first, last, and a few in between) are checked by the oracle one by one, and the
+    op-by-op plan must give the same logits for the whole chunk."""
+    _say(f"config {cfg} parity at chunk {chunk}")
+    blob = synth.build_model(cfg)
+    om = oracle.Model(blob)
+    m = _load(isr, blob, chunk)
+    x = synth.make_image(cfg, 3)
+    begin = 100000 - chunk                      # the last chunk of an n = 100000 run
+    lg, am, cnt = isr.isr_debug_forward(m, x, 64, 0, 3, 1, begin, chunk)
+    assert int(cnt.sum()) == chunk and np.array_equal(np.bincount(am, minlength=len(cnt)), cnt)
+    assert np.array_equal(am, np.argmax(lg, axis=1))
+    for i in (0, 1, 4095, chunk // 2 + 1, chunk - 2, chunk - 1):
+        olg, oam, _ = om.mc(x, 64, 0, 3, 1, begin + i, 1)
+        assert np.array_equal(lg[i], olg[0]) and am[i] == oam[0], i
+    isr.isr_set_fusion(m, False)
+    lg2, am2, cnt2 = isr.isr_debug_forward(m, x, 64, 0, 3, 1, begin, chunk)
+    assert np.array_equal(lg2, lg) and np.array_equal(cnt2, cnt)
+    m.close()
+
+
 @pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
 def test_every_conv_tile_against_the_oracle(isr, tile):
     """Layers deep enough for 128-byte K steps and for every output tile of the
