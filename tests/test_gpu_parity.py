@@ -435,6 +435,27 @@ def test_resnet20_logits_and_votes(isr):
     m.close()
 
 
+def test_resnet20_certify_and_predict_end_to_end(isr):
+    """Alg. 1 and Alg. 2 as whole calls on ResNet-20 (n0 = 100, n = 1500; chunk 700 leaves a
+    ragged last chunk): tallies, selected class, bound and radius against the oracle."""
+    _say("resnet20 end-to-end certify / predict")
+    blob = synth.build_model(1)
+    om = oracle.Model(blob)
+    m = _load(isr, blob, 700)
+    x = synth.make_image(1, 4)
+    res, c0, c1 = isr.isr_certify(m, x, 64, 100, 1500, ALPHA, seed=11, image_id=4)
+    cls, rad, p_l, k, oc0, oc1 = oracle.certify(om, x, 64, 100, 1500, ALPHA, seed=11, image=4)
+    assert np.array_equal(c0, oc0) and np.array_equal(c1, oc1)
+    assert res.cls == cls and res.n_top == k
+    assert res.p_lower == pytest.approx(p_l, rel=1e-12)
+    assert res.radius == pytest.approx(rad, rel=1e-9)
+    pres, pc = isr.isr_predict(m, x, 128, 333, ALPHA, seed=12, image_id=4)
+    pcls, pv, n_a, n_b, opc = oracle.predict(om, x, 128, 333, ALPHA, seed=12, image=4)
+    assert np.array_equal(pc, opc) and (pres.cls, pres.n_top, pres.n_second) == (pcls, n_a, n_b)
+    assert pres.p_lower == pytest.approx(pv, rel=1e-9, abs=1e-300)
+    m.close()
+
+
 def test_resnet110_logits(isr):
     _say("resnet110 logits parity")
     blob = synth.build_model(2)
