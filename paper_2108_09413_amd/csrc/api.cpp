@@ -491,15 +491,16 @@ int build_device_ops(isr_model *m, ConstArena &arena) {
             break; }
         case OP_FC: {
             const TensorDesc &ti = pm.tensors[o.a];
-            const int hw = ti.H * ti.W, Kp = hw * ti.Cp, classes = pm.classes;
-            std::vector<int8_t> w((size_t)classes * Kp, 0);
+            const int hw = ti.H * ti.W, Kp = hw * ti.Cp, classes = pm.classes, classes_p = (classes + 3) & ~3;
+            std::vector<int8_t> w((size_t)classes_p * Kp, 0);
             std::vector<int32_t> bias(classes, 0);
             for (int c = 0; c < classes; ++c) {
                 int64_t wsum = 0;
                 for (int ch = 0; ch < ti.C; ++ch)
                     for (int s = 0; s < hw; ++s) {
                         int8_t v = o.w[(size_t)c * ti.C * hw + (size_t)ch * hw + s];
-                        w[(size_t)c * Kp + (size_t)s * ti.Cp + ch] = v;
+                        const size_t k = (size_t)s * ti.Cp + ch;
+                        w[((k >> 4) * classes_p + c) * 16 + (k & 15)] = v;
                         wsum += v;
                     }
                 int64_t b = (int64_t)o.bias[c] - (int64_t)ti.zp * wsum;
@@ -509,7 +510,7 @@ int build_device_ops(isr_model *m, ConstArena &arena) {
             FcParams &f = d.fc;
             f.w = (const int8_t *)arena.put(w.data(), w.size());
             f.bias = (const int32_t *)arena.put(bias.data(), bias.size() * 4);
-            f.Kp = Kp; f.classes = classes;
+            f.Kp = Kp; f.classes = classes; f.classes_p = classes_p;
             d.kclass = KC_FC;
             d.ops_per_sample = 2.0 * classes * ti.C * hw;
             d.bytes_per_sample = (double)ti.C * hw;

@@ -191,9 +191,9 @@ struct GapParams {
 
 struct FcParams {
     const int8_t *in;        // [B][Kp]
-    const int8_t *w;         // [classes][Kp]
+    const int8_t *w;         // [Kp / 16][classes_p][16]: 16-byte K chunks, class-contiguous
     const int32_t *bias;     // [classes], bias - z_in * sum(w)
-    int32_t Kp, classes, B;
+    int32_t Kp, classes, classes_p, B;   // classes_p: classes rounded up to a multiple of 4
     int32_t *logits;         // [B][classes] or null
     int32_t *argmax;         // [B] or null
     uint32_t *counts;        // [classes] (accumulated) or null; [items][classes] in batch mode

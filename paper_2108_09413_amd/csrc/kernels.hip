@@ -356,10 +356,12 @@ __global__ __launch_bounds__(256) void fc_vote_kernel(const FcParams p) {
         const int8_t *a = p.in + s * p.Kp;
         int best = INT32_MIN, best_idx = 0x7FFFFFFF;
         for (int c = lane; c < p.classes; c += 64) {
-            const int8_t *w = p.w + (long)c * p.Kp;
+            // weights are stored [K / 16][classes_p][16]: the 64 classes of a pass read 1 KiB contiguous
+            const int8_t *w = p.w + (long)c * 16;
             int acc = p.bias[c];
+#pragma unroll 4
             for (int k = 0; k < p.Kp; k += 16) {
-                v4i va = *(const v4i *)(a + k), vw = *(const v4i *)(w + k);
+                v4i va = *(const v4i *)(a + k), vw = *(const v4i *)(w + (long)(k >> 4) * p.classes_p * 16);
 #pragma unroll
                 for (int d = 0; d < 4; ++d) acc = __builtin_amdgcn_sdot4(va[d], vw[d], acc, false);
             }
@@ -388,7 +390,7 @@ __global__ __launch_bounds__(256) void fc_vote_kernel(const FcParams p) {
 
 hipError_t launch_fc(const FcParams &p, hipStream_t st) {
     if (p.B <= 0) return hipSuccess;
-    if (p.classes < 1 || p.classes > FC_MAX_CLASSES || p.Kp % 16 != 0) return hipErrorInvalidValue;
+    if (p.classes < 1 || p.classes > FC_MAX_CLASSES || p.Kp % 16 != 0 || p.classes_p < p.classes) return hipErrorInvalidValue;
     long blocks = ((long)p.B + 3) / 4;
     if (blocks > 256 * 8) blocks = 256 * 8;
     hipLaunchKernelGGL(fc_vote_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p);
