@@ -39,6 +39,8 @@ struct DevOp {
     int stem_pool = 0;                  // conv fused with the max pooling after it (out = the pooled tensor)
     int stem16 = 0;                     // first 3x3 convolution into 16 channels: the LDS-resident kernel
     int block = 0;                      // identity residual block: this conv, conv2 and the add in one kernel
+    std::vector<std::pair<ConvParams, ConvParams>> chain;   // block != 0: the blocks of the chain this op runs (each feeds the next)
+    size_t chain_off = 0;               // first BlockDesc of the chain in the model's device array
     int trans = 0;                      // down-sampling block: this conv (3x3/2), conv2 (3x3) and conv3 (1x1/2 + add) in one kernel
     int bneck = 0;                      // 1: this 1x1 conv and the 3x3 conv2 in one kernel; 2: plus conv3 (1x1 + residual add)
     ConvParams conv2{};
@@ -82,6 +84,7 @@ struct isr_model {
     int table_next = 0;
     uint32_t *dcounts = nullptr;        // 2 * classes
     uint32_t *hcounts = nullptr;        // pinned, 2 * classes
+    BlockDesc *dblocks = nullptr;       // descriptors of the identity-block chains of plan[1]
     // batched calls: item descriptors and per-item vote counters, grown on demand
     NoiseItem *ditems = nullptr, *hitems = nullptr;
     uint32_t *dcounts_b = nullptr, *hcounts_b = nullptr;   // 2 * items_cap * classes each
@@ -254,10 +257,36 @@ void fuse_basic_blocks(const ParsedModel &pm, std::vector<DevOp> &ops) {
             continue;
         a.block = 1;
         a.conv2 = cb;
+        a.chain.assign(1, {ca, cb});
         a.ops_per_sample += b.ops_per_sample;
         a.bytes_per_sample = (double)pm.tensors[a.a].C * ca.H * ca.W + (double)pm.tensors[b.out].C * ca.H * ca.W;
         a.out = b.out;
         ops.erase(ops.begin() + i + 1);
+    }
+}
+
+// Joins consecutive identity-block ops of one shape, each read by the next alone, into one op:
+// the kernel then keeps the images in LDS from the first block to the last.
+void chain_basic_blocks(const ParsedModel &pm, std::vector<DevOp> &ops) {
+    std::vector<int> uses(pm.tensors.size(), 0);
+    for (const DevOp &d : ops) {
+        if (d.a >= 0) uses[d.a]++;
+        if (d.b >= 0) uses[d.b]++;
+    }
+    auto tf = [](const DevOp &d) { return d.conv.tie_free && d.conv2.tie_free && d.conv2.add_tie_free; };
+    for (size_t i = 0; i + 1 < ops.size();) {
+        DevOp &a = ops[i];
+        const DevOp &b = ops[i + 1];
+        if (a.block && b.block && b.a == a.out && uses[a.out] == 1 && a.conv.Cout_p == b.conv.Cout_p && a.conv.H == b.conv.H &&
+            tf(a) == tf(b) && a.chain.size() < 64) {
+            a.chain.insert(a.chain.end(), b.chain.begin(), b.chain.end());
+            a.ops_per_sample += b.ops_per_sample;
+            a.bytes_per_sample = (a.bytes_per_sample + b.bytes_per_sample) / 2;   // one read of the first input, one write of the last output
+            a.out = b.out;
+            ops.erase(ops.begin() + i + 1);
+        } else {
+            ++i;
+        }
     }
 }
 
@@ -623,18 +652,13 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
                         break;
                     }
                     if (d.block) {
-                        const ConvParams &c1 = d.conv, &c2 = d.conv2;
-                        BlockParams bp;
+                        BlockParams bp{};
                         bp.in = (const int8_t *)(ws + pl.toff[d.a]);
                         bp.out = (int8_t *)(ws + pl.toff[d.out]);
-                        bp.w1 = c1.w; bp.bias1 = c1.bias; bp.m0s1 = c1.m0s; bp.chi1 = c1.chi; bp.shm11 = c1.shm1;
-                        bp.w2 = c2.w; bp.bias2 = c2.bias; bp.m0s2 = c2.m0s; bp.chi2 = c2.chi; bp.shm12 = c2.shm1;
-                        bp.C = c1.Cout_p; bp.S = c1.H; bp.B = (int32_t)cnt;
-                        bp.zp_x = c1.zp_in; bp.zp_t = c1.zp_out; bp.relu1 = c1.relu;
-                        bp.zp_u = c2.zp_out; bp.relu2 = c2.relu;
-                        bp.add_mul_self = c2.add_mul_self; bp.add_mul_res = c2.add_mul_res; bp.add_c0 = c2.add_c0;
-                        bp.add_k = c2.add_k; bp.add_sh = c2.add_sh; bp.add_lo = c2.add_lo;
-                        bp.tie_free = c1.tie_free && c2.tie_free && c2.add_tie_free;
+                        bp.blocks = m->dblocks + d.chain_off;
+                        bp.nblocks = (int32_t)d.chain.size();
+                        bp.C = d.conv.Cout_p; bp.S = d.conv.H; bp.B = (int32_t)cnt;
+                        bp.tie_free = d.conv.tie_free && d.conv2.tie_free && d.conv2.add_tie_free;
                         HIP_TRY(launch_basic_block(bp, m->stream));
                         break;
                     }
@@ -876,8 +900,32 @@ int isr_load_model(const void *blob_host, size_t bytes, isr_model **out) {
             f.stem16 = 1;
     }
     fuse_basic_blocks(m->pm, m->plan[1].ops);
+    chain_basic_blocks(m->pm, m->plan[1].ops);
     fuse_trans_blocks(m->pm, m->plan[1].ops);
     fuse_bottlenecks(m->pm, m->plan[1].ops);
+    {   // descriptors of the identity-block chains, in device memory
+        std::vector<BlockDesc> descs;
+        for (DevOp &d : m->plan[1].ops) {
+            if (!d.block) continue;
+            d.chain_off = descs.size();
+            for (const auto &blk : d.chain) {
+                const ConvParams &c1 = blk.first, &c2 = blk.second;
+                BlockDesc b{};
+                b.w1 = c1.w; b.bias1 = c1.bias; b.m0s1 = c1.m0s; b.chi1 = c1.chi; b.shm11 = c1.shm1;
+                b.w2 = c2.w; b.bias2 = c2.bias; b.m0s2 = c2.m0s; b.chi2 = c2.chi; b.shm12 = c2.shm1;
+                b.zp_x = c1.zp_in; b.zp_t = c1.zp_out; b.relu1 = c1.relu;
+                b.zp_u = c2.zp_out; b.relu2 = c2.relu;
+                b.add_mul_self = c2.add_mul_self; b.add_mul_res = c2.add_mul_res; b.add_c0 = c2.add_c0;
+                b.add_k = c2.add_k; b.add_sh = c2.add_sh; b.add_lo = c2.add_lo;
+                descs.push_back(b);
+            }
+        }
+        if (!descs.empty()) {
+            e = hipMalloc((void **)&m->dblocks, descs.size() * sizeof(BlockDesc));
+            if (e == hipSuccess) e = hipMemcpy(m->dblocks, descs.data(), descs.size() * sizeof(BlockDesc), hipMemcpyHostToDevice);
+            if (e != hipSuccess) { g_last_hip_error = (int)e; return cleanup(ISR_ERR_DEVICE); }
+        }
+    }
     *out = m;
     return ISR_OK;
 }
@@ -977,6 +1025,7 @@ int isr_free_model(isr_model *m) {
     if (m->htables) (void)hipHostFree(m->htables);
     if (m->dcounts) (void)hipFree(m->dcounts);
     if (m->hcounts) (void)hipHostFree(m->hcounts);
+    if (m->dblocks) (void)hipFree(m->dblocks);
     if (m->ditems) (void)hipFree(m->ditems);
     if (m->hitems) (void)hipHostFree(m->hitems);
     if (m->dcounts_b) (void)hipFree(m->dcounts_b);

@@ -9,6 +9,10 @@
 // channels the two M fragments are split over the waves so that they fit.  The 16 K-bytes
 // of an MFMA operand lane are 16 channels of one tap: one aligned 128-bit LDS read at
 // (pixel + tap offset) * C, no gather through the texture path.  C = 16 uses v_mfma_i32_16x16x64_i8, C = 32 / 64 v_mfma_i32_32x32x32_i8.
+// A launch runs a CHAIN of such blocks (same shape, each feeding the next): the output of a
+// block overwrites x in LDS in place -- a lane reads the residual at its own pixel and writes
+// the sum there, the second convolution itself reads only t -- so a run of identity blocks
+// reads its input from HBM once and writes once.
 #include "conv_device.h"
 
 namespace isr {
@@ -36,15 +40,7 @@ __global__ __launch_bounds__(256) void basic_block_kernel(const BlockParams p) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const long img0 = (long)blockIdx.x * NI;
 
-    // ---- stage per-channel constants, the images and the borders ----
-    for (int i = tid; i < 2 * C; i += 256) {
-        const int cv = i / C, c = i % C;
-        prm[cv][0][c] = (cv ? p.bias2 : p.bias1)[c];
-        prm[cv][1][c] = (cv ? p.m0s2 : p.m0s1)[c];
-        prm[cv][2][c] = (cv ? p.chi2 : p.chi1)[c];
-        prm[cv][3][c] = (cv ? p.shm12 : p.shm11)[c];
-    }
-    const uint32_t zx = (uint32_t)(p.zp_x & 0xFF) * 0x01010101u, zt = (uint32_t)(p.zp_t & 0xFF) * 0x01010101u;
+    // ---- the images ----
     for (int i = tid; i < NI * S * S * CH; i += 256) {
         const int im = i / (S * S * CH), j = i % (S * S * CH), pix = j / CH, c = j % CH;
         const int y = pix / S, x = pix % S;
@@ -52,19 +48,29 @@ __global__ __launch_bounds__(256) void basic_block_kernel(const BlockParams p) {
         if (g >= p.B) g = p.B - 1;                   // images past the end repeat the last one; never stored
         *(v4i *)(&X[im][((y + 1) * P + x + 1) * C + c * 16]) = *(const v4i *)(p.in + (g * S * S + pix) * C + c * 16);
     }
-    for (int i = tid; i < NI * (4 * P - 4) * CH; i += 256) {
-        const int im = i / ((4 * P - 4) * CH), j = i % ((4 * P - 4) * CH), b = j / CH, c = j % CH;
-        // border pixel b: top row, bottom row, then the left and right columns without the corners
-        int y, x;
-        if (b < P) { y = 0; x = b; }
-        else if (b < 2 * P) { y = P - 1; x = b - P; }
-        else if (b < 3 * P - 2) { y = b - 2 * P + 1; x = 0; }
-        else { y = b - (3 * P - 2) + 1; x = P - 1; }
-        const int off = (y * P + x) * C + c * 16;
-        *(v4i *)(&X[im][off]) = v4i{(int)zx, (int)zx, (int)zx, (int)zx};
-        *(v4i *)(&T[im][off]) = v4i{(int)zt, (int)zt, (int)zt, (int)zt};
-    }
-    __syncthreads();
+    // per block: per-channel constants and the two padding rings (zero-points of x and t)
+    auto stage_block = [&](const BlockDesc &d) {
+        for (int i = tid; i < 2 * C; i += 256) {
+            const int cv = i / C, c = i % C;
+            prm[cv][0][c] = (cv ? d.bias2 : d.bias1)[c];
+            prm[cv][1][c] = (cv ? d.m0s2 : d.m0s1)[c];
+            prm[cv][2][c] = (cv ? d.chi2 : d.chi1)[c];
+            prm[cv][3][c] = (cv ? d.shm12 : d.shm11)[c];
+        }
+        const uint32_t zx = (uint32_t)(d.zp_x & 0xFF) * 0x01010101u, zt = (uint32_t)(d.zp_t & 0xFF) * 0x01010101u;
+        for (int i = tid; i < NI * (4 * P - 4) * CH; i += 256) {
+            const int im = i / ((4 * P - 4) * CH), j = i % ((4 * P - 4) * CH), b = j / CH, c = j % CH;
+            // border pixel b: top row, bottom row, then the left and right columns without the corners
+            int y, x;
+            if (b < P) { y = 0; x = b; }
+            else if (b < 2 * P) { y = P - 1; x = b - P; }
+            else if (b < 3 * P - 2) { y = b - 2 * P + 1; x = 0; }
+            else { y = b - (3 * P - 2) + 1; x = P - 1; }
+            const int off = (y * P + x) * C + c * 16;
+            *(v4i *)(&X[im][off]) = v4i{(int)zx, (int)zx, (int)zx, (int)zx};
+            *(v4i *)(&T[im][off]) = v4i{(int)zt, (int)zt, (int)zt, (int)zt};
+        }
+    };
 
     // lane's place in an MFMA operand: pixel / weight row `l`, 16-byte K chunk `kg` of the step
     const int l = lane & (MT - 1), kg = lane / MT;
@@ -142,55 +148,64 @@ __global__ __launch_bounds__(256) void basic_block_kernel(const BlockParams p) {
         return r;
     };
 
-    // ---- first convolution: requantise, clamp, into the interior of T ----
-    const int lo1 = p.relu1 ? p.zp_t : -128;
-    {
-        const Req rq = load_req(0);
-        conv(X, 0, p.w1, [&](int im, int pix, int mf, const acc_t &a) {
-            const int c0 = mf * MT + ocl;
-            int q[ACC];
+    for (int blk = 0; blk < p.nblocks; ++blk) {
+        const BlockDesc d = p.blocks[blk];
+        const bool last = blk + 1 == p.nblocks;
+        if (blk) __syncthreads();   // every wave is done with the previous block's constants and has written its part of x
+        stage_block(d);
+        __syncthreads();
+
+        // ---- first convolution: requantise, clamp, into the interior of T ----
+        const int lo1 = d.relu1 ? d.zp_t : -128;
+        {
+            const Req rq = load_req(0);
+            conv(X, 0, d.w1, [&](int im, int pix, int mf, const acc_t &a) {
+                const int c0 = mf * MT + ocl;
+                int q[ACC];
 #pragma unroll
-            for (int i = 0; i < ACC; ++i) q[i] = clamp3(requant_q<TF>(a[i], rq.m0[i], rq.chi[i], rq.shm1[i]), lo1, 127);
-            int8_t *dst = &T[im][((pix / S + 1) * P + pix % S + 1) * C + c0];
+                for (int i = 0; i < ACC; ++i) q[i] = clamp3(requant_q<TF>(a[i], rq.m0[i], rq.chi[i], rq.shm1[i]), lo1, 127);
+                int8_t *dst = &T[im][((pix / S + 1) * P + pix % S + 1) * C + c0];
+                if constexpr (MT == 16) *(uint32_t *)dst = pack4(q[0], q[1], q[2], q[3]);
+                else
+                    *(v4i *)dst = v4i{(int)pack4(q[0], q[1], q[2], q[3]), (int)pack4(q[4], q[5], q[6], q[7]),
+                                      (int)pack4(q[8], q[9], q[10], q[11]), (int)pack4(q[12], q[13], q[14], q[15])};
+            });
+        }
+        __syncthreads();
+
+        // ---- second convolution: requantise, clamp, add the residual x; the sum replaces x in LDS
+        // (next block of the chain) or goes to memory (last block) ----
+        const int lo2 = d.relu2 ? d.zp_u : -128;
+        ConvParams ap{};   // the fused add reads its constants from here
+        ap.add_mul_self = d.add_mul_self; ap.add_mul_res = d.add_mul_res; ap.add_c0 = d.add_c0; ap.add_k = d.add_k;
+        ap.add_sh = d.add_sh; ap.add_lo = d.add_lo;
+        const Req rq2 = load_req(1);
+        conv(T, 1, d.w2, [&](int im, int pix, int mf, const acc_t &a) {
+            const int c0 = mf * MT + ocl;
+            const long g = img0 + im;
+            int8_t *res = &X[im][((pix / S + 1) * P + pix % S + 1) * C + c0];
+            int q[ACC];
+            uint32_t rw[ACC / 4];
+            if constexpr (MT == 16) rw[0] = *(const uint32_t *)res;
+            else {
+                const v4i rv = *(const v4i *)res;
+#pragma unroll
+                for (int d4 = 0; d4 < 4; ++d4) rw[d4] = (uint32_t)rv[d4];
+            }
+#pragma unroll
+            for (int i = 0; i < ACC; ++i) {
+                const int qc = clamp3(requant_q<TF>(a[i], rq2.m0[i], rq2.chi[i], rq2.shm1[i]), lo2, 127);
+                const int r8 = (int)(int8_t)(rw[i >> 2] >> (8 * (i & 3)));
+                q[i] = fused_add<TF>(qc, r8, ap);
+            }
+            if (last && g >= p.B) return;
+            int8_t *dst = last ? p.out + (g * S * S + pix) * C + c0 : res;
             if constexpr (MT == 16) *(uint32_t *)dst = pack4(q[0], q[1], q[2], q[3]);
             else
                 *(v4i *)dst = v4i{(int)pack4(q[0], q[1], q[2], q[3]), (int)pack4(q[4], q[5], q[6], q[7]),
                                   (int)pack4(q[8], q[9], q[10], q[11]), (int)pack4(q[12], q[13], q[14], q[15])};
         });
     }
-    __syncthreads();
-
-    // ---- second convolution: requantise, clamp, add the residual x, store ----
-    const int lo2 = p.relu2 ? p.zp_u : -128;
-    ConvParams ap{};   // the fused add reads its constants from here
-    ap.add_mul_self = p.add_mul_self; ap.add_mul_res = p.add_mul_res; ap.add_c0 = p.add_c0; ap.add_k = p.add_k;
-    ap.add_sh = p.add_sh; ap.add_lo = p.add_lo;
-    const Req rq2 = load_req(1);
-    conv(T, 1, p.w2, [&](int im, int pix, int mf, const acc_t &a) {
-        const int c0 = mf * MT + ocl;
-        const long g = img0 + im;
-        const int8_t *res = &X[im][((pix / S + 1) * P + pix % S + 1) * C + c0];
-        int q[ACC];
-        uint32_t rw[ACC / 4];
-        if constexpr (MT == 16) rw[0] = *(const uint32_t *)res;
-        else {
-            const v4i rv = *(const v4i *)res;
-#pragma unroll
-            for (int d = 0; d < 4; ++d) rw[d] = (uint32_t)rv[d];
-        }
-#pragma unroll
-        for (int i = 0; i < ACC; ++i) {
-            const int qc = clamp3(requant_q<TF>(a[i], rq2.m0[i], rq2.chi[i], rq2.shm1[i]), lo2, 127);
-            const int r8 = (int)(int8_t)(rw[i >> 2] >> (8 * (i & 3)));
-            q[i] = fused_add<TF>(qc, r8, ap);
-        }
-        if (g >= p.B) return;
-        int8_t *dst = p.out + (g * S * S + pix) * C + c0;
-        if constexpr (MT == 16) *(uint32_t *)dst = pack4(q[0], q[1], q[2], q[3]);
-        else
-            *(v4i *)dst = v4i{(int)pack4(q[0], q[1], q[2], q[3]), (int)pack4(q[4], q[5], q[6], q[7]),
-                              (int)pack4(q[8], q[9], q[10], q[11]), (int)pack4(q[12], q[13], q[14], q[15])};
-    });
 }
 
 template <int C, int S, int NI>
@@ -211,7 +226,7 @@ bool basic_block_supported(int channels, int size) {
 
 hipError_t launch_basic_block(const BlockParams &p, hipStream_t st) {
     if (p.B <= 0) return hipSuccess;
-    if (!p.in || !p.out || !p.w1 || !p.w2 || !basic_block_supported(p.C, p.S)) return hipErrorInvalidValue;
+    if (!p.in || !p.out || !p.blocks || p.nblocks < 1 || !basic_block_supported(p.C, p.S)) return hipErrorInvalidValue;
     if (p.C == 16) return launch_shape<16, 32, 1>(p, st);
     if (p.C == 32) return launch_shape<32, 16, 2>(p, st);
     return launch_shape<64, 8, 4>(p, st);

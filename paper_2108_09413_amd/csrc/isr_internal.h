@@ -121,17 +121,22 @@ struct Stem16Params {
 
 // Identity residual block in one kernel: t = conv3x3(x), y = add(conv3x3(t), x); both
 // convolutions C -> C channels, stride 1, pad 1, on S x S images (basic_block.hip).
-struct BlockParams {
-    const int8_t *in;        // [B][S][S][C] block input x (also the residual)
-    int8_t *out;             // [B][S][S][C]
+struct BlockDesc {           // one block of a chain, stored in device memory
     const int8_t *w1, *w2;   // [>= C][Kp] each, K = (tap, channel), Kp = 9 C rounded up to 64
     const int32_t *bias1, *m0s1, *chi1, *shm11;   // first convolution, as in ConvParams
     const int32_t *bias2, *m0s2, *chi2, *shm12;   // second convolution
-    int32_t C, S, B;
     int32_t zp_x, zp_t, relu1;   // zero-points of x and t; lower clamp of t is zp_t when relu1
     int32_t zp_u, relu2;         // the same for the second convolution's own int8 result
     int32_t add_mul_self, add_mul_res, add_c0, add_k, add_sh, add_lo;   // as in ConvParams
-    int32_t tie_free;            // both convolutions and the add are free of rounding ties
+    int32_t pad_;
+};
+struct BlockParams {
+    const int8_t *in;        // [B][S][S][C] input x of the first block
+    int8_t *out;             // [B][S][S][C] output of the last block
+    const BlockDesc *blocks; // [nblocks] (device): a chain of blocks of one shape, each feeding the next
+    int32_t nblocks;
+    int32_t C, S, B;
+    int32_t tie_free;        // every convolution and add of the chain is free of rounding ties
 };
 
 // Bottleneck block with 64 middle channels in one kernel (bottleneck.hip): conv1x1 -> conv3x3
