@@ -8,6 +8,7 @@
 #include <new>
 
 #include "isr_internal.h"
+#include "plan.h"
 
 using namespace isr;
 
@@ -26,50 +27,7 @@ thread_local int g_last_hip_error = 0;
 
 constexpr int TABLE_SLOTS = 8;
 
-enum KernelClass { KC_NOISE, KC_CONV16, KC_CONV32, KC_CONV64, KC_CONV128, KC_ADD, KC_POOL, KC_GAP, KC_FC, KC_COUNT };
-const char *const KC_NAMES[KC_COUNT] = {"noise", "conv_m16", "conv_m32", "conv_m64", "conv_m128",
-                                        "add", "maxpool", "gap", "fc_vote"};
-
-struct DevOp {
-    OpType type;
-    int a = -1, b = -1, out = -1;
-    int kclass = 0;
-    double ops_per_sample = 0.0, bytes_per_sample = 0.0;   // algorithmic, for the timing report
-    ConvParams conv{};
-    int stem_pool = 0;                  // conv fused with the max pooling after it (out = the pooled tensor)
-    int stem16 = 0;                     // first 3x3 convolution into 16 channels: the LDS-resident kernel
-    int block = 0;                      // identity residual block: this conv, conv2 and the add in one kernel
-    std::vector<std::pair<ConvParams, ConvParams>> chain;   // block != 0: the blocks of the chain this op runs (each feeds the next)
-    size_t chain_off = 0;               // first BlockDesc of the chain in the model's device array
-    int trans = 0;                      // down-sampling block: this conv (3x3/2), conv2 (3x3) and conv3 (1x1/2 + add) in one kernel
-    int bneck = 0;                      // 1: this 1x1 conv and the 3x3 conv2 in one kernel; 2: plus conv3 (1x1 + residual add)
-    ConvParams conv2{};
-    ConvParams conv3{};
-    AddParams add{};
-    PoolParams pool{};
-    GapParams gap{};
-    FcParams fc{};
-};
-
-size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-
-// MFMA 32x32 accumulator row r of lane half h, register i is 8*(i/4) + 4*h + i%4;
-// weights of output channel 16*h + i go to that row so that a lane ends up
-// holding 16 consecutive channels.
-int mfma32_row_of_channel(int oc_local) {
-    int h = oc_local >> 4, a = (oc_local & 15) >> 2, b = oc_local & 3;
-    return 8 * a + 4 * h + b;
-}
-
 }  // namespace
-
-// An executable op list plus where each tensor lives in the workspace.
-struct Plan {
-    std::vector<DevOp> ops;
-    std::vector<size_t> toff;           // per tensor offset inside the workspace
-    std::vector<char> has;              // tensor is produced by this plan
-    size_t logits_off = 0, argmax_off = 0, bytes = 0;
-};
 
 struct isr_model {
     ParsedModel pm;
@@ -102,459 +60,6 @@ struct isr_model {
 };
 
 namespace {
-
-// Offsets of every tensor for a chunk of B samples; buffers are reused once the
-// last op reading a tensor has been issued (stream order makes that safe).
-void plan_workspace(const ParsedModel &pm, uint32_t B, Plan &pl) {
-    const int nt = (int)pm.tensors.size();
-    std::vector<int> last_use(nt, -1);
-    for (int i = 0; i < (int)pl.ops.size(); ++i) {
-        const DevOp &o = pl.ops[i];
-        if (o.a >= 0) last_use[o.a] = i;
-        if (o.b >= 0) last_use[o.b] = i;
-    }
-    auto tbytes = [&](int t) {
-        const TensorDesc &d = pm.tensors[t];
-        return round_up((size_t)B * d.H * d.W * d.Cp + 64, 256);
-    };
-    struct Block { size_t off, size; };
-    std::vector<Block> freelist;
-    size_t top = 0;
-    auto alloc = [&](size_t n) {
-        for (size_t i = 0; i < freelist.size(); ++i)
-            if (freelist[i].size >= n) {
-                size_t off = freelist[i].off;
-                freelist[i].off += n;
-                freelist[i].size -= n;
-                if (freelist[i].size == 0) freelist.erase(freelist.begin() + i);
-                return off;
-            }
-        size_t off = top;
-        top += n;
-        return off;
-    };
-    auto release = [&](size_t off, size_t n) {
-        freelist.push_back({off, n});
-        std::sort(freelist.begin(), freelist.end(), [](const Block &x, const Block &y) { return x.off < y.off; });
-        for (size_t i = 0; i + 1 < freelist.size();)
-            if (freelist[i].off + freelist[i].size == freelist[i + 1].off) {
-                freelist[i].size += freelist[i + 1].size;
-                freelist.erase(freelist.begin() + i + 1);
-            } else {
-                ++i;
-            }
-    };
-    pl.toff.assign(nt, 0);
-    pl.has.assign(nt, 0);
-    pl.toff[0] = alloc(tbytes(0));
-    pl.has[0] = 1;
-    for (int i = 0; i < (int)pl.ops.size(); ++i) {
-        const DevOp &o = pl.ops[i];
-        if (o.type != OP_FC) { pl.toff[o.out] = alloc(tbytes(o.out)); pl.has[o.out] = 1; }
-        for (int t : {o.a, o.b})
-            if (t >= 0 && last_use[t] == i && !(t == o.b && o.a == o.b)) release(pl.toff[t], tbytes(t));
-    }
-    pl.logits_off = round_up(top, 256);
-    pl.argmax_off = pl.logits_off + round_up((size_t)B * pm.classes * 4, 256);
-    pl.bytes = pl.argmax_off + round_up((size_t)B * 4, 256);
-}
-
-// Folds each residual ADD into the convolution issued right before it when that
-// convolution produces one of the add's inputs for the add alone and the sum
-// fits 32 bits: the convolution then reads the other input in its epilogue and
-// writes the add's output (the two roundings are kept).
-void fuse_adds(const ParsedModel &pm, const std::vector<DevOp> &plain, std::vector<DevOp> &fused) {
-    std::vector<int> uses(pm.tensors.size(), 0);
-    for (const DevOp &d : plain) {
-        if (d.a >= 0) uses[d.a]++;
-        if (d.b >= 0) uses[d.b]++;
-    }
-    fused.clear();
-    for (size_t i = 0; i < plain.size(); ++i) {
-        const DevOp &d = plain[i];
-        if (d.type == OP_ADD && !fused.empty() && fused.back().type == OP_CONV && !fused.back().conv.fuse_add &&
-            fused.back().conv.fast_requant && d.a != d.b &&
-            (fused.back().out == d.a || fused.back().out == d.b) && uses[fused.back().out] == 1) {
-            DevOp &c = fused.back();
-            const bool conv_is_a = c.out == d.a;
-            const int res = conv_is_a ? d.b : d.a;
-            const AddParams &a = d.add;
-            const int64_t m_self = conv_is_a ? a.Ma : a.Mb, m_res = conv_is_a ? a.Mb : a.Ma;
-            const int64_t z_self = conv_is_a ? a.za : a.zb, z_res = conv_is_a ? a.zb : a.za;
-            const int64_t c0 = -z_self * m_self - z_res * m_res;
-            const int64_t k = (a.sh >= 1 ? (1ll << (a.sh - 1)) : 0) + (int64_t)a.zo * (1ll << a.sh);
-            auto mag = [](int64_t v) { return v < 0 ? -v : v; };
-            const int64_t bound = 255 * (mag(m_self) + mag(m_res)) + mag(k) + 1;
-            if (a.sh >= 1 && a.sh <= 30 && mag(m_self) < (1 << 23) && mag(m_res) < (1 << 23) && bound < (1ll << 31)) {
-                c.conv.fuse_add = 1;
-                c.conv.add_mul_self = (int32_t)m_self;
-                c.conv.add_mul_res = (int32_t)m_res;
-                c.conv.add_c0 = (int32_t)c0;
-                c.conv.add_k = (int32_t)k;
-                c.conv.add_sh = a.sh;
-                c.conv.add_lo = a.relu ? a.zo : -128;
-                // v = q Ms + r Mr + c0 over all int8 pairs: is a negative exact half of 2^sh ever met?
-                bool add_ties = false;
-                const int64_t halfbit = 1ll << (a.sh - 1), mask = (1ll << a.sh) - 1;
-                for (int q = -128; q <= 127 && !add_ties; ++q)
-                    for (int r = -128; r <= 127; ++r) {
-                        const int64_t v = q * m_self + r * m_res + c0;
-                        if (v < 0 && (v & mask) == halfbit) { add_ties = true; break; }
-                    }
-                c.conv.add_tie_free = add_ties ? 0 : 1;
-                c.b = res;
-                c.out = d.out;
-                c.bytes_per_sample += d.bytes_per_sample / 3.0;   // the residual read
-                // The residual is the output of the 1x1 convolution issued right before, read by this
-                // add alone: compute it inside the same kernel instead of round-tripping it through memory.
-                if (fused.size() >= 2) {
-                    const DevOp &r = fused[fused.size() - 2];
-                    const ConvParams &rc = r.conv;
-                    const bool direct = c.conv.fast_requant && !c.conv.c4 && c.conv.Cout_p >= 64;
-                    if (direct && r.type == OP_CONV && r.out == res && uses[res] == 1 && !rc.fuse_add && rc.fast_requant &&
-                        !rc.c4 && rc.ktab == nullptr && rc.Cin_p % 64 == 0 && rc.Kp == rc.Cin_p &&
-                        rc.Cout_p == c.conv.Cout_p && rc.Mp == c.conv.Mp && rc.Ho == c.conv.Ho && rc.Wo == c.conv.Wo) {
-                        DevOp merged = c;
-                        merged.conv.fuse_add = 2;
-                        merged.conv.w2 = rc.w; merged.conv.bias2 = rc.bias; merged.conv.m0s2 = rc.m0s;
-                        merged.conv.chi2 = rc.chi; merged.conv.shm12 = rc.shm1;
-                        merged.conv.Cin2_p = rc.Cin_p;
-                        merged.conv.lo2 = rc.relu ? rc.zp_out : -128;
-                        merged.conv.tie_free2 = rc.tie_free;
-                        merged.b = r.a;   // second input tensor (kept alive until this op is issued)
-                        merged.ops_per_sample += r.ops_per_sample;
-                        merged.bytes_per_sample += r.bytes_per_sample - 2.0 * d.bytes_per_sample / 3.0;   // no residual write + read
-                        fused.pop_back();
-                        fused.pop_back();
-                        fused.push_back(merged);
-                    }
-                }
-                continue;
-            }
-        }
-        fused.push_back(d);
-    }
-}
-
-// Folds conv3x3 -> conv3x3 -> add-with-the-block-input (identity residual block) into one
-// kernel for the shapes that fit LDS whole.  Runs on the list in which the add is already
-// folded into the second convolution.
-void fuse_basic_blocks(const ParsedModel &pm, std::vector<DevOp> &ops) {
-    std::vector<int> uses(pm.tensors.size(), 0);
-    for (const DevOp &d : ops) {
-        if (d.a >= 0) uses[d.a]++;
-        if (d.b >= 0) uses[d.b]++;
-    }
-    for (size_t i = 0; i + 1 < ops.size(); ++i) {
-        DevOp &a = ops[i];
-        const DevOp &b = ops[i + 1];
-        if (a.type != OP_CONV || b.type != OP_CONV || a.stem_pool || a.block || a.conv.fuse_add || b.conv.fuse_add != 1) continue;
-        const ConvParams &ca = a.conv, &cb = b.conv;
-        auto is3x3 = [](const ConvParams &c) { return c.k == 3 && c.stride == 1 && c.pad == 1 && !c.c4 && c.fast_requant; };
-        if (!is3x3(ca) || !is3x3(cb) || b.a != a.out || b.b != a.a || uses[a.out] != 1) continue;
-        if (ca.Cin_p != ca.Cout_p || cb.Cin_p != ca.Cout_p || cb.Cout_p != ca.Cout_p || ca.H != ca.W || ca.Ho != ca.H ||
-            !basic_block_supported(ca.Cout_p, ca.H))
-            continue;
-        a.block = 1;
-        a.conv2 = cb;
-        a.chain.assign(1, {ca, cb});
-        a.ops_per_sample += b.ops_per_sample;
-        a.bytes_per_sample = (double)pm.tensors[a.a].C * ca.H * ca.W + (double)pm.tensors[b.out].C * ca.H * ca.W;
-        a.out = b.out;
-        ops.erase(ops.begin() + i + 1);
-    }
-}
-
-// Joins consecutive identity-block ops of one shape, each read by the next alone, into one op:
-// the kernel then keeps the images in LDS from the first block to the last.
-void chain_basic_blocks(const ParsedModel &pm, std::vector<DevOp> &ops) {
-    std::vector<int> uses(pm.tensors.size(), 0);
-    for (const DevOp &d : ops) {
-        if (d.a >= 0) uses[d.a]++;
-        if (d.b >= 0) uses[d.b]++;
-    }
-    auto tf = [](const DevOp &d) { return d.conv.tie_free && d.conv2.tie_free && d.conv2.add_tie_free; };
-    for (size_t i = 0; i + 1 < ops.size();) {
-        DevOp &a = ops[i];
-        const DevOp &b = ops[i + 1];
-        if (a.block && b.block && b.a == a.out && uses[a.out] == 1 && a.conv.Cout_p == b.conv.Cout_p && a.conv.H == b.conv.H &&
-            tf(a) == tf(b) && a.chain.size() < 64) {
-            a.chain.insert(a.chain.end(), b.chain.begin(), b.chain.end());
-            a.ops_per_sample += b.ops_per_sample;
-            a.bytes_per_sample = (a.bytes_per_sample + b.bytes_per_sample) / 2;   // one read of the first input, one write of the last output
-            a.out = b.out;
-            ops.erase(ops.begin() + i + 1);
-        } else {
-            ++i;
-        }
-    }
-}
-
-// Folds the down-sampling block of the narrow nets -- conv3x3 stride 2, conv3x3, and the 1x1
-// stride-2 projection that carries the residual add -- into one kernel for the shapes that fit LDS.
-void fuse_trans_blocks(const ParsedModel &pm, std::vector<DevOp> &ops) {
-    std::vector<int> uses(pm.tensors.size(), 0);
-    for (const DevOp &d : ops) {
-        if (d.a >= 0) uses[d.a]++;
-        if (d.b >= 0) uses[d.b]++;
-    }
-    auto plain = [](const DevOp &d) {
-        return d.type == OP_CONV && !d.stem_pool && !d.stem16 && !d.block && !d.bneck && !d.trans && !d.conv.c4 && d.conv.fast_requant;
-    };
-    for (size_t i = 0; i + 2 < ops.size(); ++i) {
-        DevOp &a = ops[i];
-        const DevOp &b = ops[i + 1], &c = ops[i + 2];
-        if (!plain(a) || !plain(b) || !plain(c) || a.conv.fuse_add || b.conv.fuse_add || c.conv.fuse_add != 1) continue;
-        const ConvParams &c1 = a.conv, &c2 = b.conv, &cp = c.conv;
-        const int C = c1.Cout_p, S = c1.Ho;
-        if (c1.k != 3 || c1.stride != 2 || c1.pad != 1 || c2.k != 3 || c2.stride != 1 || c2.pad != 1 || cp.k != 1 ||
-            cp.stride != 2 || cp.pad != 0)
-            continue;
-        if (2 * c1.Cin_p != C || c2.Cin_p != C || c2.Cout_p != C || cp.Cin_p != c1.Cin_p || cp.Cout_p != C || c1.H != 2 * S ||
-            c1.W != 2 * S || c1.Wo != S || cp.Ho != S || cp.Wo != S || !trans_block_supported(C, S))
-            continue;
-        if (c1.Kp != (9 * c1.Cin_p + 63) / 64 * 64 || c2.Kp != (9 * C + 63) / 64 * 64 || cp.Kp != 64) continue;
-        if (b.a != a.out || c.a != a.a || c.b != b.out || uses[a.out] != 1 || uses[b.out] != 1) continue;
-        a.trans = 1;
-        a.conv2 = c2;
-        a.conv3 = cp;
-        a.ops_per_sample += b.ops_per_sample + c.ops_per_sample;
-        a.bytes_per_sample = (double)pm.tensors[a.a].C * c1.H * c1.W + (double)pm.tensors[c.out].C * S * S;
-        a.out = c.out;
-        ops.erase(ops.begin() + i + 1, ops.begin() + i + 3);
-    }
-}
-
-// Folds conv1x1 (-> 64 channels) -> conv3x3 (64 -> 64) of a bottleneck block into one kernel,
-// and with them the closing conv1x1 + residual add when the residual is the block input.
-// Runs on the list in which the adds are already folded into their convolutions.
-void fuse_bottlenecks(const ParsedModel &pm, std::vector<DevOp> &ops) {
-    std::vector<int> uses(pm.tensors.size(), 0);
-    for (const DevOp &d : ops) {
-        if (d.a >= 0) uses[d.a]++;
-        if (d.b >= 0) uses[d.b]++;
-    }
-    auto plain = [](const DevOp &d) {
-        return d.type == OP_CONV && !d.stem_pool && !d.stem16 && !d.block && !d.trans && !d.bneck && !d.conv.c4 && d.conv.fast_requant;
-    };
-    for (size_t i = 0; i + 1 < ops.size(); ++i) {
-        DevOp &a = ops[i];
-        const DevOp &b = ops[i + 1];
-        if (!plain(a) || !plain(b) || a.conv.fuse_add || b.conv.fuse_add) continue;
-        const ConvParams &c1 = a.conv, &c2 = b.conv;
-        if (c1.k != 1 || c1.stride != 1 || c1.pad != 0 || c1.Kp != c1.Cin_p || c1.Cout_p != 64) continue;
-        if (c2.k != 3 || c2.stride != 1 || c2.pad != 1 || c2.Cin_p != 64 || c2.Cout_p != 64 || c2.Kp != 576) continue;
-        if (b.a != a.out || uses[a.out] != 1 || !bottleneck_supported(c1.Cin_p, 64, 0, 0)) continue;
-        a.bneck = 1;
-        a.conv2 = c2;
-        a.ops_per_sample += b.ops_per_sample;
-        a.bytes_per_sample = (double)pm.tensors[a.a].C * c1.H * c1.W + (double)pm.tensors[b.out].C * c1.H * c1.W;
-        a.out = b.out;
-        ops.erase(ops.begin() + i + 1);
-        if (i + 1 < ops.size()) {
-            const DevOp &c = ops[i + 1];
-            const ConvParams &c3 = c.conv;
-            if (plain(c) && c3.fuse_add == 1 && c3.k == 1 && c3.stride == 1 && c3.pad == 0 && c3.Cin_p == 64 && c3.Kp == 64 &&
-                c.a == a.out && c.b == a.a && uses[a.out] == 1 && bottleneck_supported(c1.Cin_p, 64, c3.Cout_p, 1)) {
-                a.bneck = 2;
-                a.conv3 = c3;
-                a.ops_per_sample += c.ops_per_sample;
-                a.bytes_per_sample = 2.0 * pm.tensors[a.a].C * c1.H * c1.W;
-                a.out = c.out;
-                ops.erase(ops.begin() + i + 1);
-            }
-        }
-    }
-}
-
-// Folds the max pooling that follows the first convolution into it when the fused
-// kernel covers the geometry and the convolution output has no other reader.
-void fuse_stem_pool(const ParsedModel &pm, std::vector<DevOp> &ops) {
-    std::vector<int> uses(pm.tensors.size(), 0);
-    for (const DevOp &d : ops) {
-        if (d.a >= 0) uses[d.a]++;
-        if (d.b >= 0) uses[d.b]++;
-    }
-    for (size_t i = 0; i + 1 < ops.size(); ++i) {
-        DevOp &c = ops[i];
-        const DevOp &q = ops[i + 1];
-        if (c.type != OP_CONV || !c.conv.c4 || c.conv.fuse_add || q.type != OP_MAXPOOL || q.a != c.out || uses[c.out] != 1)
-            continue;
-        if (c.conv.Kp != 256) continue;   // K = 7 rows x 8 taps x 4 channels
-        if (!stem_pool_supported(c.conv.k, c.conv.stride, c.conv.pad, c.conv.Cout_p, c.conv.H, c.conv.W, c.conv.fast_requant,
-                                 q.pool.k, q.pool.stride, q.pool.pad))
-            continue;
-        c.stem_pool = 1;
-        c.bytes_per_sample = (double)pm.tensors[c.a].C * c.conv.H * c.conv.W +
-                             (double)pm.tensors[q.out].C * pm.tensors[q.out].H * pm.tensors[q.out].W;
-        c.out = q.out;
-        ops.erase(ops.begin() + i + 1);
-        return;
-    }
-}
-
-struct ConstArena {
-    std::vector<uint8_t> host;
-    size_t put(const void *src, size_t n) {
-        size_t off = round_up(host.size(), 256);
-        host.resize(off + round_up(n, 16), 0);
-        if (src) std::memcpy(host.data() + off, src, n);
-        return off;
-    }
-};
-
-// Builds device descriptors; pointers into the constant arena are stored as
-// offsets first and rebased after the upload.
-int build_device_ops(isr_model *m, ConstArena &arena) {
-    const ParsedModel &pm = m->pm;
-    for (const HostOp &o : pm.ops) {
-        DevOp d;
-        d.type = o.type; d.a = o.a; d.b = o.b; d.out = o.out;
-        switch (o.type) {
-        case OP_CONV: {
-            const TensorDesc &ti = pm.tensors[o.a], &to = pm.tensors[o.out];
-            const bool c4 = o.a == 0;
-            const int cin_p = ti.Cp, cout_p = to.Cp, k = o.k;
-            const int kwp = (k + 3) & ~3;
-            const int kreal = c4 ? k * kwp * 4 : k * k * cin_p;
-            bool fast = true;
-            for (int oc = 0; oc < to.C; ++oc) fast = fast && o.shift[oc] >= 2 && o.shift[oc] <= 22;
-            const int kb = conv_k_step(kreal, c4 ? 0 : cin_p, cout_p, fast ? 1 : 0);
-            const int Kp = (int)round_up((size_t)kreal, (size_t)kb), Mp = (int)round_up((size_t)cout_p, 128);
-            const bool perm = conv_tile_m(cout_p) != 16;
-            std::vector<int8_t> w((size_t)Mp * Kp, 0);
-            std::vector<int32_t> bias(Mp, 0);
-            bool tie_free = fast;
-            const int64_t maxdev = std::max<int64_t>(127 - ti.zp, ti.zp + 128);   // |q - z_in| of an int8 input
-            std::vector<uint32_t> m0x2(Mp, 0x80000000u), rlo(Mp, 0), rhi(Mp, 1), sh(Mp, 1);
-            std::vector<int32_t> m0s(Mp, 1 << 30), chi(Mp, 1 + 2 * to.zp), shm1(Mp, 1);
-            for (int oc = 0; oc < to.C; ++oc) {
-                int row = perm ? (oc & ~31) + mfma32_row_of_channel(oc & 31) : oc;
-                int64_t wsum = 0, wabs = 0;
-                for (int ic = 0; ic < ti.C; ++ic)
-                    for (int ky = 0; ky < k; ++ky)
-                        for (int kx = 0; kx < k; ++kx) {
-                            int8_t v = o.w[(((size_t)oc * ti.C + ic) * k + ky) * k + kx];
-                            int kk = c4 ? (ky * kwp + kx) * 4 + ic : (ky * k + kx) * cin_p + ic;
-                            w[(size_t)row * Kp + kk] = v;
-                            wsum += v;
-                            wabs += v < 0 ? -v : v;
-                        }
-                {
-                    // acc * M0 is an exact half of 2^(31 + shift) only if acc = (odd) * 2^(30 + shift - tz(M0))
-                    const int64_t accmax = std::llabs((int64_t)o.bias[oc]) + maxdev * wabs;
-                    const int need = 30 + o.shift[oc] - __builtin_ctz((unsigned)o.M0[oc]);
-                    if (need < 40 && accmax >= (1ll << need)) tie_free = false;
-                }
-                int64_t b = (int64_t)o.bias[oc] - (int64_t)ti.zp * wsum;
-                if (b < INT32_MIN || b > INT32_MAX) return ISR_ERR_UNSUPPORTED;
-                bias[oc] = (int32_t)b;
-                m0x2[oc] = (uint32_t)o.M0[oc] << 1;
-                uint64_t rnd = 1ull << (31 + o.shift[oc]);
-                rlo[oc] = (uint32_t)rnd; rhi[oc] = (uint32_t)(rnd >> 32); sh[oc] = (uint32_t)o.shift[oc];
-                if (o.shift[oc] >= 2 && o.shift[oc] <= 22) {
-                    m0s[oc] = o.M0[oc];
-                    chi[oc] = (1 << (o.shift[oc] - 2)) + to.zp * (1 << (o.shift[oc] - 1));
-                    shm1[oc] = o.shift[oc] - 1;
-                }
-            }
-            const bool flat = !c4 && k == 1 && o.stride == 1 && o.pad == 0 && cin_p % 64 == 0;
-            std::vector<uint32_t> ktab(Kp / 16, 0xFFFFFFFFu);
-            std::vector<int32_t> ktoff(Kp / 16, 0);
-            for (int j = 0; j < Kp / 16; ++j) {
-                if (c4) {
-                    int per_row = kwp / 4, ky = j / per_row, kx0 = (j % per_row) * 4;
-                    if (ky < k) { ktab[j] = (uint32_t)ky | ((uint32_t)kx0 << 8); ktoff[j] = (ky * ti.W + kx0) * 4; }
-                } else {
-                    int k0 = j * 16, tap = k0 / cin_p, ic = k0 % cin_p;
-                    if (tap < k * k) {
-                        ktab[j] = (uint32_t)(tap / k) | ((uint32_t)(tap % k) << 8);
-                        ktoff[j] = ((tap / k) * ti.W + (tap % k)) * cin_p + ic;
-                    }
-                }
-            }
-            ConvParams &c = d.conv;
-            c.w = (const int8_t *)arena.put(w.data(), w.size());
-            c.bias = (const int32_t *)arena.put(bias.data(), bias.size() * 4);
-            c.m0x2 = (const uint32_t *)arena.put(m0x2.data(), m0x2.size() * 4);
-            c.rnd_lo = (const uint32_t *)arena.put(rlo.data(), rlo.size() * 4);
-            c.rnd_hi = (const uint32_t *)arena.put(rhi.data(), rhi.size() * 4);
-            c.shift = (const uint32_t *)arena.put(sh.data(), sh.size() * 4);
-            c.m0s = (const int32_t *)arena.put(m0s.data(), m0s.size() * 4);
-            c.chi = (const int32_t *)arena.put(chi.data(), chi.size() * 4);
-            c.shm1 = (const int32_t *)arena.put(shm1.data(), shm1.size() * 4);
-            c.fast_requant = fast ? 1 : 0;
-            c.tie_free = tie_free ? 1 : 0;
-            const std::vector<int8_t> zfill(16, (int8_t)ti.zp);
-            c.zpad = (const int8_t *)arena.put(zfill.data(), zfill.size());
-            c.ktab = flat ? (const uint32_t *)~(uintptr_t)0 : (const uint32_t *)arena.put(ktab.data(), ktab.size() * 4);
-            c.ktoff = flat ? (const int32_t *)~(uintptr_t)0 : (const int32_t *)arena.put(ktoff.data(), ktoff.size() * 4);
-            c.H = ti.H; c.W = ti.W; c.Cin_p = cin_p; c.Ho = to.H; c.Wo = to.W; c.Cout_p = cout_p;
-            c.k = k; c.stride = o.stride; c.pad = o.pad; c.Kp = Kp; c.Mp = Mp; c.kb = kb;
-            c.zp_in = ti.zp; c.zp_out = to.zp; c.relu = o.relu; c.c4 = c4 ? 1 : 0;
-            int tm = conv_tile_m(cout_p);
-            d.kclass = tm == 16 ? KC_CONV16 : tm == 32 ? KC_CONV32 : tm == 64 ? KC_CONV64 : KC_CONV128;
-            d.ops_per_sample = 2.0 * to.C * to.H * to.W * ti.C * k * k;
-            d.bytes_per_sample = (double)ti.C * ti.H * ti.W + (double)to.C * to.H * to.W;
-            break; }
-        case OP_ADD: {
-            AddParams &a = d.add;
-            a.za = pm.tensors[o.a].zp; a.zb = pm.tensors[o.b].zp; a.zo = pm.tensors[o.out].zp;
-            a.Ma = o.Ma; a.Mb = o.Mb; a.sh = o.sh; a.relu = o.relu;
-            d.kclass = KC_ADD;
-            d.bytes_per_sample = 3.0 * pm.tensors[o.out].C * pm.tensors[o.out].H * pm.tensors[o.out].W;
-            break; }
-        case OP_MAXPOOL: {
-            const TensorDesc &ti = pm.tensors[o.a], &to = pm.tensors[o.out];
-            PoolParams &p = d.pool;
-            p.H = ti.H; p.W = ti.W; p.Cp = ti.Cp; p.Ho = to.H; p.Wo = to.W; p.k = o.k; p.stride = o.stride; p.pad = o.pad;
-            d.kclass = KC_POOL;
-            d.bytes_per_sample = (double)ti.C * ti.H * ti.W + (double)to.C * to.H * to.W;
-            break; }
-        case OP_GAP: {
-            const TensorDesc &ti = pm.tensors[o.a], &to = pm.tensors[o.out];
-            GapParams &g = d.gap;
-            g.HW = ti.H * ti.W; g.Cp = ti.Cp; g.zp_in = ti.zp; g.zp_out = to.zp; g.M0 = o.Ma; g.sh = o.sh;
-            d.kclass = KC_GAP;
-            d.bytes_per_sample = (double)ti.C * ti.H * ti.W + (double)to.C;
-            break; }
-        case OP_FC: {
-            const TensorDesc &ti = pm.tensors[o.a];
-            const int hw = ti.H * ti.W, Kp = hw * ti.Cp, classes = pm.classes, classes_p = (classes + 3) & ~3;
-            std::vector<int8_t> w((size_t)classes_p * Kp, 0);
-            std::vector<int32_t> bias(classes, 0);
-            for (int c = 0; c < classes; ++c) {
-                int64_t wsum = 0;
-                for (int ch = 0; ch < ti.C; ++ch)
-                    for (int s = 0; s < hw; ++s) {
-                        int8_t v = o.w[(size_t)c * ti.C * hw + (size_t)ch * hw + s];
-                        const size_t k = (size_t)s * ti.Cp + ch;
-                        w[((k >> 4) * classes_p + c) * 16 + (k & 15)] = v;
-                        wsum += v;
-                    }
-                int64_t b = (int64_t)o.bias[c] - (int64_t)ti.zp * wsum;
-                if (b < INT32_MIN || b > INT32_MAX) return ISR_ERR_UNSUPPORTED;
-                bias[c] = (int32_t)b;
-            }
-            FcParams &f = d.fc;
-            f.w = (const int8_t *)arena.put(w.data(), w.size());
-            f.bias = (const int32_t *)arena.put(bias.data(), bias.size() * 4);
-            f.Kp = Kp; f.classes = classes; f.classes_p = classes_p;
-            d.kclass = KC_FC;
-            d.ops_per_sample = 2.0 * classes * ti.C * hw;
-            d.bytes_per_sample = (double)ti.C * hw;
-            break; }
-        }
-        m->ops.push_back(d);
-    }
-    return ISR_OK;
-}
-
-template <typename T>
-void rebase(const T *&p, const uint8_t *base) {
-    if ((uintptr_t)p == ~(uintptr_t)0) { p = nullptr; return; }
-    p = (const T *)(base + (uintptr_t)p);
-}
 
 int get_table(isr_model *m, uint32_t sigma, const DeviceNoiseTable **out) {
     for (int i = 0; i < TABLE_SLOTS; ++i)
@@ -869,7 +374,7 @@ int isr_load_model(const void *blob_host, size_t bytes, isr_model **out) {
     if (rc != ISR_OK) { delete m; return rc; }
     ConstArena arena;
     arena.put(nullptr, 256);  // offset 0 is never a valid table
-    rc = build_device_ops(m, arena);
+    rc = build_device_ops(m->pm, m->ops, arena);
     if (rc != ISR_OK) { delete m; return rc; }
     auto cleanup = [&](int code) { isr_free_model(m); return code; };
     hipError_t e = hipMalloc((void **)&m->dconst, arena.host.size());
@@ -879,30 +384,9 @@ int isr_load_model(const void *blob_host, size_t bytes, isr_model **out) {
     if (e == hipSuccess) e = hipMalloc((void **)&m->dcounts, sizeof(uint32_t) * 2 * m->pm.classes);
     if (e == hipSuccess) e = hipHostMalloc((void **)&m->hcounts, sizeof(uint32_t) * 2 * m->pm.classes, hipHostMallocDefault);
     if (e != hipSuccess) { g_last_hip_error = (int)e; return cleanup(ISR_ERR_DEVICE); }
-    for (DevOp &d : m->ops) {
-        if (d.type == OP_CONV) {
-            rebase(d.conv.w, m->dconst); rebase(d.conv.bias, m->dconst); rebase(d.conv.m0x2, m->dconst);
-            rebase(d.conv.rnd_lo, m->dconst); rebase(d.conv.rnd_hi, m->dconst); rebase(d.conv.shift, m->dconst);
-            rebase(d.conv.ktab, m->dconst); rebase(d.conv.ktoff, m->dconst); rebase(d.conv.zpad, m->dconst);
-            rebase(d.conv.m0s, m->dconst); rebase(d.conv.chi, m->dconst); rebase(d.conv.shm1, m->dconst);
-        } else if (d.type == OP_FC) {
-            rebase(d.fc.w, m->dconst); rebase(d.fc.bias, m->dconst);
-        }
-    }
+    rebase_device_ops(m->ops, m->dconst);
     m->plan[0].ops = m->ops;
-    fuse_adds(m->pm, m->ops, m->plan[1].ops);
-    fuse_stem_pool(m->pm, m->plan[1].ops);
-    if (!m->plan[1].ops.empty()) {
-        DevOp &f = m->plan[1].ops[0];
-        const ConvParams &c = f.conv;
-        if (f.type == OP_CONV && c.c4 && !c.fuse_add && !f.stem_pool && c.Kp == 64 &&
-            stem16_supported(c.k, c.stride, c.pad, c.Cout_p, c.H, c.W, c.fast_requant))
-            f.stem16 = 1;
-    }
-    fuse_basic_blocks(m->pm, m->plan[1].ops);
-    chain_basic_blocks(m->pm, m->plan[1].ops);
-    fuse_trans_blocks(m->pm, m->plan[1].ops);
-    fuse_bottlenecks(m->pm, m->plan[1].ops);
+    build_fused_plan(m->pm, m->ops, m->plan[1].ops);
     {   // descriptors of the identity-block chains, in device memory
         std::vector<BlockDesc> descs;
         for (DevOp &d : m->plan[1].ops) {
