@@ -79,6 +79,40 @@ def test_stored_training_noise_bank(isr, sigma):
     assert isr.lib().isr_noise_bank(sigma, ctypes.c_uint64(0), 0, 0, 1, 8, None, None) == isr.ISR_ERR_ARG
 
 
+@pytest.mark.parametrize("sigma", [2, 32])
+def test_device_sampler_law_at_scale(isr, sigma):
+    """1.5e8 draws of the device sampler (a full stored-noise bank) against Def. 3.3 itself:
+    mean, variance and a chi-square over 50 cells with the exact cell probabilities
+    (50-digit arithmetic) -- a property of the law, not of the oracle's code."""
+    import mpmath as mp
+    import torch
+    _say(f"sampler law at scale sigma={sigma}")
+    count, d = 50000, 3072
+    bank = isr.isr_noise_bank(sigma, 12345, 7, 0, count, d)
+    n = count * d
+    x = bank.to(torch.float64)
+    mean, var = float(x.mean()), float(x.var(unbiased=False))
+    assert abs(mean) < 5 * sigma / np.sqrt(n)
+    assert abs(var / sigma ** 2 - 1) < 5 * np.sqrt(2.0 / n) + 1e-9      # the discrete law's variance is sigma^2 to < 1e-13 for sigma >= 2
+    mp.mp.dps = 50
+    K = 12 * sigma
+    w = [mp.e ** (-(mp.mpf(k) ** 2) / (2 * mp.mpf(sigma) ** 2)) for k in range(0, K + 1)]
+    Z = w[0] + 2 * sum(w[1:])
+    pmf = lambda k: w[abs(k)] / Z if abs(k) <= K else mp.mpf(0)
+    step = max(1, sigma // 8)
+    edges = list(range(-3 * sigma, 3 * sigma + 1, step))                 # cells [e_i, e_{i+1}) plus the two tails
+    obs = torch.histc(x, bins=len(edges) - 1, min=edges[0] - 0.5, max=edges[-1] - 0.5).cpu().numpy()
+    lo_tail = float((x < edges[0] - 0.5).sum()); hi_tail = float((x > edges[-1] - 0.5).sum())
+    obs = np.concatenate([[lo_tail], obs, [hi_tail]])
+    probs = [float(sum(pmf(k) for k in range(-K, edges[0])))]
+    probs += [float(sum(pmf(k) for k in range(a, b))) for a, b in zip(edges, edges[1:])]
+    probs += [float(sum(pmf(k) for k in range(edges[-1], K + 1)))]
+    assert abs(sum(probs) - 1) < 1e-12 and int(obs.sum()) == n
+    exp = np.array(probs) * n
+    chi2 = float(((obs - exp) ** 2 / exp).sum())
+    assert chi2 < 110.0, chi2          # 49 degrees of freedom: P[chi2 > 110] ~ 1e-6
+
+
 # ---- S3-S6: layer tensors ----------------------------------------------------
 
 def _check_all_tensors(isr, blob, x, sigma, seed=3, image=1, phase=1, sample=17, chunk=4):
