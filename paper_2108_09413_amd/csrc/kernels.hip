@@ -388,9 +388,66 @@ __global__ __launch_bounds__(256) void fc_vote_kernel(const FcParams p) {
             if (hist[i]) atomicAdd(&p.counts[i], hist[i]);
 }
 
+// The same for long feature vectors, with the four waves of a workgroup on ONE sample: each wave
+// sums a quarter of K for all classes (lane = class) with 16 independent weight loads in
+// flight, the partial sums meet in LDS.  The one-wave form above waits for memory 128 times in
+// a row at K = 2048.  Integer sums, so the order of the additions is free.
+__global__ __launch_bounds__(256) void fc_vote_ksplit_kernel(const FcParams p) {
+    __shared__ int part[4][FC_MAX_CLASSES];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int kq = p.Kp >> 2;                        // K bytes per wave, a multiple of 256
+    for (long s = blockIdx.x; s < p.B; s += gridDim.x) {
+        const int8_t *a = p.in + s * p.Kp + wave * kq;
+        for (int c = lane; c < p.classes; c += 64) {
+            const int8_t *w = p.w + ((long)(wave * kq >> 4) * p.classes_p + c) * 16;
+            int acc = 0;
+            for (int k0 = 0; k0 < kq; k0 += 256) {
+                v4i vw[16];
+#pragma unroll
+                for (int j = 0; j < 16; ++j) vw[j] = *(const v4i *)(w + (long)((k0 >> 4) + j) * p.classes_p * 16);
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const v4i va = *(const v4i *)(a + k0 + 16 * j);
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) acc = __builtin_amdgcn_sdot4(va[d], vw[j][d], acc, false);
+                }
+            }
+            part[wave][c] = acc;
+        }
+        __syncthreads();
+        if (wave == 0) {
+            int best = INT32_MIN, best_idx = 0x7FFFFFFF;
+            for (int c = lane; c < p.classes; c += 64) {
+                const int acc = p.bias[c] + part[0][c] + part[1][c] + part[2][c] + part[3][c];
+                if (p.logits) p.logits[s * p.classes + c] = acc;
+                if (acc > best) { best = acc; best_idx = c; }   // ascending c keeps the lowest index
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                int ob = __shfl_xor(best, off, 64), oi = __shfl_xor(best_idx, off, 64);
+                if (ob > best || (ob == best && oi < best_idx)) { best = ob; best_idx = oi; }
+            }
+            if (lane == 0) {
+                if (p.argmax) p.argmax[s] = best_idx;
+                if (p.counts) {
+                    const uint64_t row = p.n_per_item ? (p.slot_begin + (uint64_t)s) / p.n_per_item : 0;
+                    atomicAdd(&p.counts[row * p.classes + best_idx], 1u);
+                }
+            }
+        }
+        __syncthreads();   // part is free for the next sample
+    }
+}
+
 hipError_t launch_fc(const FcParams &p, hipStream_t st) {
     if (p.B <= 0) return hipSuccess;
     if (p.classes < 1 || p.classes > FC_MAX_CLASSES || p.Kp % 16 != 0 || p.classes_p < p.classes) return hipErrorInvalidValue;
+    if (p.Kp % 1024 == 0) {
+        long blocks = p.B;
+        if (blocks > 256 * 16) blocks = 256 * 16;
+        hipLaunchKernelGGL(fc_vote_ksplit_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p);
+        return hipGetLastError();
+    }
     long blocks = ((long)p.B + 3) / 4;
     if (blocks > 256 * 8) blocks = 256 * 8;
     hipLaunchKernelGGL(fc_vote_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p);
