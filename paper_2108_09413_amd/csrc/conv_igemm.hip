@@ -513,18 +513,27 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
 #pragma unroll
             for (int fn = 0; fn < FN; ++fn) acc[fm][fn] = init;
         }
+        // every buffer is free at the start: the first NST steps are all fetched at once
 #pragma unroll
-        for (int s = 0; s < NST - 1; ++s)
+        for (int s = 0; s < NST; ++s)
             if (s < steps) fetch(s, s);
-        int cur = 0, fill = NST - 1;   // buffer computed on now / buffer filled next
+        int cur = 0, fill = 0;   // buffer computed on now / buffer refilled next (the one of step ks - 1)
         for (int ks = 0; ks < steps; ++ks) {
-            // This wave's loads of step ks have landed once at most the loads of the steps
-            // after it (min(steps - 1 - ks, NST - 2) of them, L each) are still in flight.
-            if (NST == 3 && ks + 1 < steps) wait_vmcnt<L>();
+            // This wave's loads of step ks have landed once at most the loads of the steps after it
+            // (L each) are still in flight: min(steps, NST) - 1 of them at step 0, then
+            // min(steps - 1 - ks, NST - 2).
+            if (ks == 0) {
+                if (NST == 3 && steps >= 3) wait_vmcnt<2 * L>();
+                else if (steps >= 2) wait_vmcnt<L>();
+                else wait_vmcnt<0>();
+            } else if (NST == 3 && ks + 1 < steps) wait_vmcnt<L>();
             else wait_vmcnt<0>();
             __builtin_amdgcn_s_barrier();   // every wave's loads of step ks landed; every wave is done with step ks - 1
-            if (ks + NST - 1 < steps) fetch(ks + NST - 1, fill);
-            else if (FUSE == 1 && with_residual_tile && ks + 1 == steps && steps > 1) issue_residual(fill);
+            if (ks >= 1) {
+                if (ks + NST - 1 < steps) fetch(ks + NST - 1, fill);
+                else if (FUSE == 1 && with_residual_tile && ks + 1 == steps) issue_residual(fill);
+                fill = fill + 1 == NST ? 0 : fill + 1;
+            }
             const int8_t *base = Ls[cur];
 #pragma unroll
             for (int ksub = 0; ksub < KS; ++ksub) {
@@ -540,7 +549,6 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
                         acc[fm][fn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[fm], fb[fn], acc[fm][fn], 0, 0, 0);
             }
             cur = cur + 1 == NST ? 0 : cur + 1;
-            fill = fill + 1 == NST ? 0 : fill + 1;
         }
     };
 
