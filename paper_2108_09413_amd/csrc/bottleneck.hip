@@ -107,10 +107,12 @@ __global__ __launch_bounds__(256, 2) void bottleneck_kernel(const BneckParams p)
     }
     const int nk = p.Cin_p / KB;
     issue(0, 0);
+    if (nk > 1) issue(1, 1);            // both stages are free at the start
     for (int ks = 0; ks < nk; ++ks) {
-        wait_vmcnt<0>();
+        if (ks == 0 && nk > 1) wait_vmcnt<5>();   // step 0 landed; the 5 loads of step 1 may still be in flight
+        else wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();   // every wave's loads of step ks landed; every wave is done with step ks - 1
-        if (ks + 1 < nk) issue(ks + 1, (ks + 1) & 1);
+        if (ks >= 1 && ks + 1 < nk) issue(ks + 1, (ks + 1) & 1);
         const int8_t *base = &Ls[(ks & 1) * STAGE];
 #pragma unroll
         for (int ksub = 0; ksub < 2; ++ksub) {
