@@ -367,26 +367,6 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
     // the chunk a lane fetches is the same for all of its rows
     const int cl = col ^ swz<CPR>(row0);
 
-    if (!flat)
-        for (int i = tid; i < nk * CPR; i += NT) {
-            const uint32_t g = p.ktab[i];
-            const int chan = p.ktoff[i] - (int)((g & 0xFF) * p.W + ((g >> 8) & 0xFF)) * p.Cin_p;
-            ktg_s[i] = g == 0xFFFFFFFFu ? g : (g | ((uint32_t)chan << 16));
-        }
-    for (int i = tid; i < BM; i += NT) {
-        const bool in = m0 + i < p.Mp;
-        prm_s[0][i] = in ? p.bias[m0 + i] : 0;
-        prm_s[1][i] = in ? p.m0s[m0 + i] : 0;
-        prm_s[2][i] = in ? p.chi[m0 + i] : 0;
-        prm_s[3][i] = in ? p.shm1[m0 + i] : 1;
-        if constexpr (FUSE == 2) {
-            prm2_s[0][i] = in ? p.bias2[m0 + i] : 0;
-            prm2_s[1][i] = in ? p.m0s2[m0 + i] : 0;
-            prm2_s[2][i] = in ? p.chi2[m0 + i] : 0;
-            prm2_s[3][i] = in ? p.shm12[m0 + i] : 1;
-        }
-    }
-
     int pixoff[NB];
     int iy0[NB], ix0[NB];
     bool rvalid[NB];
@@ -485,6 +465,42 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
     if constexpr (FUSE == 1)
         if (nk == 1) issue_residual(1);   // the second buffer is never used by a K step
 
+    // The first GEMM's first steps are fetched before the per-channel constants are staged, when
+    // their addresses need nothing from LDS (plain 1x1 GEMM; the residual convolution always is one):
+    // the two memory latencies then overlap.  Every buffer is free at the start.
+    bool prefetched = false;
+    if constexpr (FUSE == 2) {
+#pragma unroll
+        for (int s = 0; s < NST; ++s)
+            if (s < p.Cin2_p / KB) issue2(s, s);
+        prefetched = true;
+    } else if (flat) {
+#pragma unroll
+        for (int s = 0; s < NST; ++s)
+            if (s < nk) issue(s, s);
+        prefetched = true;
+    }
+
+    if (!flat)
+        for (int i = tid; i < nk * CPR; i += NT) {
+            const uint32_t g = p.ktab[i];
+            const int chan = p.ktoff[i] - (int)((g & 0xFF) * p.W + ((g >> 8) & 0xFF)) * p.Cin_p;
+            ktg_s[i] = g == 0xFFFFFFFFu ? g : (g | ((uint32_t)chan << 16));
+        }
+    for (int i = tid; i < BM; i += NT) {
+        const bool in = m0 + i < p.Mp;
+        prm_s[0][i] = in ? p.bias[m0 + i] : 0;
+        prm_s[1][i] = in ? p.m0s[m0 + i] : 0;
+        prm_s[2][i] = in ? p.chi[m0 + i] : 0;
+        prm_s[3][i] = in ? p.shm1[m0 + i] : 1;
+        if constexpr (FUSE == 2) {
+            prm2_s[0][i] = in ? p.bias2[m0 + i] : 0;
+            prm2_s[1][i] = in ? p.m0s2[m0 + i] : 0;
+            prm2_s[2][i] = in ? p.chi2[m0 + i] : 0;
+            prm2_s[3][i] = in ? p.shm12[m0 + i] : 1;
+        }
+    }
+
     __syncthreads();   // ktg_s, prm_s visible
     // per-lane fragment offsets inside a step's buffer
     int aoff[KS][FM], boff[KS][FN];
@@ -504,7 +520,7 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
     }
 
     // One GEMM over `steps` K steps fetched by `fetch(step, buffer)`; accumulators start at `bias_s`.
-    auto gemm = [&](int steps, const int *bias_s, auto fetch, bool with_residual_tile) {
+    auto gemm = [&](int steps, const int *bias_s, auto fetch, bool with_residual_tile, bool fetched) {
 #pragma unroll
         for (int fm = 0; fm < FM; ++fm) {
             acc_t init;
@@ -514,9 +530,11 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
             for (int fn = 0; fn < FN; ++fn) acc[fm][fn] = init;
         }
         // every buffer is free at the start: the first NST steps are all fetched at once
+        if (!fetched) {
 #pragma unroll
-        for (int s = 0; s < NST; ++s)
-            if (s < steps) fetch(s, s);
+            for (int s = 0; s < NST; ++s)
+                if (s < steps) fetch(s, s);
+        }
         int cur = 0, fill = 0;   // buffer computed on now / buffer refilled next (the one of step ks - 1)
         for (int ks = 0; ks < steps; ++ks) {
             // This wave's loads of step ks have landed once at most the loads of the steps after it
@@ -555,7 +573,7 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
     // residual convolution first: its int8 result stays packed in registers (16 channels per dword group)
     v4i rq[FUSE == 2 ? FM : 1][FUSE == 2 ? FN : 1];
     if constexpr (FUSE == 2) {
-        gemm(p.Cin2_p / KB, prm2_s[0], issue2, false);
+        gemm(p.Cin2_p / KB, prm2_s[0], issue2, false, prefetched);
 #pragma unroll
         for (int fm = 0; fm < FM; ++fm)
 #pragma unroll
@@ -571,7 +589,7 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
             }
         __syncthreads();   // every wave is done with the operand buffers before the main GEMM refills them
     }
-    gemm(nk, prm_s[0], issue, true);
+    gemm(nk, prm_s[0], issue, true, FUSE != 2 && prefetched);
 
     // epilogue: requantise, clamp, optional residual add, pack, store (NHWC)
     const int8_t *resbuf = nullptr;
