@@ -22,8 +22,6 @@
 //    256 threads, operands staged through registers into LDS.  KB = 64: two LDS
 //    buffers, one barrier per step.  KB = 128: one buffer, two barriers per step.
 //    MT = 32 uses v_mfma_i32_32x32x32_i8, MT = 16 uses v_mfma_i32_16x16x64_i8.
-#include <cstdlib>
-
 #include "conv_device.h"
 
 namespace isr {
@@ -343,12 +341,12 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
     __shared__ __attribute__((aligned(16))) int8_t Ls[NST][STAGE];   // per step: A rows, then B rows
     __shared__ uint32_t ktg_s[512];   // per 16-byte K chunk: ky | kx << 8 | channel byte offset << 16; ~0 = padding
     __shared__ __attribute__((aligned(16))) int prm_s[4][BM];   // bias, M0, chi, shift-1 of this M tile
-    // A fused residual add (two-buffer variant only) fetches the residual tile as whole pixel
+    // A fused residual add fetches the residual tile as whole pixel
     // rows, [pixel][BM channels] with the 16-byte chunks XOR-swizzled per pixel, into the
     // operand buffer that is idle during the last K step.
     constexpr int RCH = BM / 16;                    // chunks per pixel row
     constexpr int RPB = BM >= 256 ? 1 : 256 / BM;   // pixel rows per 256 bytes (one pass over the 64 banks)
-    static_assert(FUSE != 1 || (NST == 2 && STAGE >= BM * BN && BM * BN / 16 % NT == 0), "residual tile fits a buffer");
+    static_assert(FUSE != 1 || (STAGE >= BM * BN && BM * BN / 16 % NT == 0), "residual tile fits a buffer");
     __shared__ __attribute__((aligned(16))) int prm2_s[4][FUSE == 2 ? BM : 1];   // the same for the residual convolution
     auto rswz = [](int pixel) { return (pixel / RPB) & (RCH - 1); };
 
@@ -451,6 +449,7 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
     acc_t acc[FM][FN];
     auto lane_oc = [&](int fm) { return wm * 64 + fm * MT + 16 * (lane >> 5); };
 
+    int res_buf = -1;   // buffer that receives the residual tile
     auto issue_residual = [&](int buf) {
 #pragma unroll
         for (int j = 0; j < BM * BN / 16 / NT; ++j) {
@@ -463,7 +462,7 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
         }
     };
     if constexpr (FUSE == 1)
-        if (nk == 1) issue_residual(1);   // the second buffer is never used by a K step
+        if (nk < NST) { res_buf = NST - 1; issue_residual(res_buf); }   // the last buffer is never used by a K step
 
     // The first GEMM's first steps are fetched before the per-channel constants are staged, when
     // their addresses need nothing from LDS (plain 1x1 GEMM; the residual convolution always is one):
@@ -549,7 +548,7 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
             __builtin_amdgcn_s_barrier();   // every wave's loads of step ks landed; every wave is done with step ks - 1
             if (ks >= 1) {
                 if (ks + NST - 1 < steps) fetch(ks + NST - 1, fill);
-                else if (FUSE == 1 && with_residual_tile && ks + 1 == steps) issue_residual(fill);
+                else if (FUSE == 1 && with_residual_tile && ks + 1 == steps && res_buf < 0) { res_buf = fill; issue_residual(fill); }
                 fill = fill + 1 == NST ? 0 : fill + 1;
             }
             const int8_t *base = Ls[cur];
@@ -596,7 +595,7 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, MINB) void conv_dma_ker
     if constexpr (FUSE == 1) {
         wait_vmcnt<0>();
         __syncthreads();   // the residual tile is in LDS
-        resbuf = Ls[nk == 1 ? 1 : (nk & 1)];   // the buffer that held step nk - 2
+        resbuf = Ls[res_buf];
     }
     const int lo = p.relu ? p.zp_out : -128;
 #pragma unroll
@@ -680,6 +679,15 @@ static hipError_t launch_dma_fused(const ConvParams &p, hipStream_t st) {
             hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 2, 2, MINB2, true>), grid, dim3(NT), 0, st, p);
         else
             hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 2, 2, MINB2, false>), grid, dim3(NT), 0, st, p);
+    } else if (BM == 128 && p.Kp == 128) {
+        // two K steps: with a third buffer the residual tile is fetched at the start instead of
+        // during the last step, which measured faster than the fourth workgroup per CU
+        if constexpr (BM == 128) {
+            if (p.tie_free && p.add_tie_free)
+                hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 3, 1, 3, true>), grid, dim3(NT), 0, st, p);
+            else
+                hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 3, 1, 3, false>), grid, dim3(NT), 0, st, p);
+        }
     } else if (p.tie_free && p.add_tie_free)
         hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 2, 1, MINB, true>), grid, dim3(NT), 0, st, p);
     else
