@@ -209,3 +209,112 @@ def test_mc_is_additive_over_ranges_and_thread_invariant():
     lg, _ = m.forward(a0)
     assert np.array_equal(lg, la[7])
     assert aa[7] == int(np.flatnonzero(lg == lg.max())[0])
+
+
+# ---- the drivers that assemble Alg. 1 and Alg. 2 from the loop above ----
+
+def _golden_ratio(golden_dir, n, k):
+    """R / sigma of the golden file (50-digit values, independent of scipy and of the oracle)."""
+    import os
+    for line in open(os.path.join(golden_dir, "cp_radius_values.txt")):
+        f = line.split()
+        if len(f) == 4 and f[0] == str(n) and f[1] == str(k):
+            return float(f[3])
+    raise KeyError((n, k))
+
+
+def _vote_splitting_net():
+    """Five classes on a 3x2x2 input with no pooling of the noise away: the votes of noisy copies of a
+    grey image spread over all classes, so tallies tell streams, ranges and seeds apart."""
+    b = NetBuilder(rng=np.random.default_rng(8), in_shape=(3, 2, 2), num_classes=5)
+    tin = b.tensor(3, 2, 2, 0, 74.0)
+    t = b.conv(tin, 8, 1, 1, 0, False, bias=np.zeros(8), sh=5)
+    b.fc(b.gap(t), 5, bias=np.zeros(5))
+    return oracle.Model(b.blob()), np.full((3, 2, 2), 128, dtype=np.uint8)
+
+
+def test_certify_runs_selection_on_phase_0_and_estimation_on_phase_1():
+    """Alg. 1: n0 selection samples and n estimation samples on two disjoint streams; the class
+    comes from the first tally, the count that enters the bound from the second."""
+    m, x = _vote_splitting_net()
+    n0, n, sigma, seed, image = 60, 240, 64, 11, 5
+    cls, rad, p_l, k, c0, c1 = oracle.certify(m, x, sigma, n0, n, 0.001, seed=seed, image=image, threads=2)
+    _, _, want0 = m.mc(x, sigma, seed, image, 0, 0, n0, threads=1)
+    _, _, want1 = m.mc(x, sigma, seed, image, 1, 0, n, threads=1)
+    assert np.array_equal(c0, want0) and np.array_equal(c1, want1)
+    assert int(c0.sum()) == n0 and int(c1.sum()) == n and np.count_nonzero(c0) == 5
+    # the tallies a driver would get from one stream for both loops, from swapped streams or from
+    # swapped sample counts are all different from these
+    _, _, p1_n0 = m.mc(x, sigma, seed, image, 1, 0, n0, threads=1)
+    _, _, p0_n = m.mc(x, sigma, seed, image, 0, 0, n, threads=1)
+    assert not np.array_equal(c0, p1_n0) and not np.array_equal(c1, p0_n)
+    assert not np.array_equal(oracle.noisy(x, sigma, seed, image, 0, 0), oracle.noisy(x, sigma, seed, image, 1, 0))
+    # class from the selection tally (here it differs from the top class of the same number of
+    # estimation samples), count of that class read from the estimation tally
+    c_a = int(np.flatnonzero(c0 == c0.max())[0])
+    assert c_a != int(np.argmax(p1_n0))
+    assert k == int(c1[c_a])
+    assert (cls, rad, p_l, k) == oracle.stats.certify_decision(c0, c1, float(sigma), n, 0.001)
+    assert cls == oracle.stats.ABSTAIN and rad == 0.0    # 94 of 240 votes: the bound is far below 1/2
+    # seed and image id reach both streams
+    for kw in (dict(seed=seed + 1, image=image), dict(seed=seed, image=image + 1)):
+        _, _, _, _, d0, d1 = oracle.certify(m, x, sigma, n0, n, 0.001, threads=2, **kw)
+        _, _, e0 = m.mc(x, sigma, kw["seed"], kw["image"], 0, 0, n0, threads=1)
+        _, _, e1 = m.mc(x, sigma, kw["seed"], kw["image"], 1, 0, n, threads=1)
+        assert np.array_equal(d0, e0) and np.array_equal(d1, e1) and not np.array_equal(d1, c1)
+
+
+def test_certify_on_the_small_workload_matches_its_two_loops():
+    import synth
+    m = oracle.Model(synth.build_model(0))
+    x = synth.make_image(0, 1)
+    cls, rad, p_l, k, c0, c1 = oracle.certify(m, x, 32, 100, 300, 0.001, seed=0, image=0, threads=4)
+    assert np.array_equal(c0, m.mc(x, 32, 0, 0, 0, 0, 100, threads=2)[2])
+    assert np.array_equal(c1, m.mc(x, 32, 0, 0, 1, 0, 300, threads=2)[2])
+    assert (cls, rad, p_l, k) == oracle.stats.certify_decision(c0, c1, 32.0, 300, 0.001)
+
+
+def _constant_net():
+    """FC ignores its input: logits = bias, maxima at classes 1, 3, 4 (lowest index wins)."""
+    b = NetBuilder(rng=np.random.default_rng(5), in_shape=(3, 8, 8), num_classes=6)
+    tin = b.tensor(3, 8, 8, 0, 50.0)
+    t = b.conv(tin, 4, 3, 1, 1, True)
+    b.fc(b.gap(t), 6, w=np.zeros((6, 4)), bias=np.array([5, 9, -3, 9, 9, 0]))
+    return oracle.Model(b.blob())
+
+
+def test_certify_constant_classifier_reaches_the_largest_radius(golden_dir):
+    """All n estimation votes on one class: p_A = alpha^(1/n), the largest radius the procedure
+    can return (section on certified accuracy: every sample classified as the same class)."""
+    m = _constant_net()
+    x = np.random.default_rng(1).integers(0, 256, size=(3, 8, 8)).astype(np.uint8)
+    for n0, n in ((7, 1000), (100, 100)):
+        for sigma in (32, 64):
+            cls, rad, p_l, k, c0, c1 = oracle.certify(m, x, sigma, n0, n, 0.001, seed=3, image=2, threads=2)
+            assert cls == 1 and k == n
+            assert c0.tolist() == [0, n0, 0, 0, 0, 0] and c1.tolist() == [0, n, 0, 0, 0, 0]
+            want = sigma * _golden_ratio(golden_dir, n, n)
+            assert abs(rad - want) <= 1e-12 * want
+            assert abs(p_l - 0.001 ** (1.0 / n)) <= 1e-15
+
+
+def test_predict_constant_classifier_needs_eleven_samples():
+    """Alg. 2 with all n votes on one class: two-sided p-value 2 * 2^-n; at alpha = 0.001 ten
+    samples abstain (1.95e-3) and eleven return the class (9.77e-4)."""
+    m = _constant_net()
+    x = np.random.default_rng(1).integers(0, 256, size=(3, 8, 8)).astype(np.uint8)
+    cls, pv, n_a, n_b, counts = oracle.predict(m, x, 32, 10, 0.001, seed=0, image=0, threads=1)
+    assert cls == oracle.stats.ABSTAIN and (n_a, n_b) == (10, 0) and pv == 2.0 ** -9 and counts.tolist() == [0, 10, 0, 0, 0, 0]
+    cls, pv, n_a, n_b, counts = oracle.predict(m, x, 32, 11, 0.001, seed=0, image=0, threads=1)
+    assert cls == 1 and (n_a, n_b) == (11, 0) and pv == 2.0 ** -10 and counts.tolist() == [0, 11, 0, 0, 0, 0]
+
+
+def test_predict_runs_one_loop_on_phase_0():
+    m, x = _vote_splitting_net()
+    cls, pv, n_a, n_b, counts = oracle.predict(m, x, 64, 240, 0.001, seed=11, image=5, threads=2)
+    _, _, want = m.mc(x, 64, 11, 5, 0, 0, 240, threads=1)
+    assert np.array_equal(counts, want) and int(counts.sum()) == 240
+    assert not np.array_equal(counts, m.mc(x, 64, 11, 5, 1, 0, 240, threads=1)[2])
+    top = sorted(counts.tolist(), reverse=True)
+    assert (n_a, n_b) == (top[0], top[1]) and n_b > 0
+    assert (cls, pv, n_a, n_b) == oracle.stats.predict_decision(counts, 0.001)
