@@ -48,6 +48,16 @@ typedef struct isr_result {
     double p_lower;   /* certify: Clopper-Pearson lower bound of p_A; predict: binomial p-value */
     uint32_t n_top;   /* certify: estimation votes of the selected class; predict: n_A */
     uint32_t n_second;/* predict: n_B (runner-up votes); certify: 0 */
+    /* certify, integer-only tail (Thm 3.2, proof steps 2-3), for integer sigma in 1..1024 when a
+     * class is returned: the radius with the discrete law's own quantile in place of Phi^-1 --
+     * radius_int = the largest lattice point t (grid units) with floor(2^64 P[delta <= t]) <=
+     * floor(2^64 p_lower), delta ~ N_Z(0, sigma^2), by lookup in the sampler's cdf table (may be
+     * <= 0 when p_lower is barely above 1/2), and radius_sq_int = t * t for t > 0, else 0 (squared
+     * grid units).  t <= radius always (t lies in [radius - 3/2, radius - 1/2] up to the table's
+     * resolution).  Both 0 on abstain, for predict, and for a non-integer sigma.  The bound
+     * p_lower itself stays float64: the paper gives no integer form of the confidence bound. */
+    int32_t radius_int;
+    uint64_t radius_sq_int;
 } isr_result;
 
 /* ---- model ------------------------------------------------------------- */
@@ -165,6 +175,12 @@ int isr_debug_forward(isr_model *m, const uint8_t *x_device, uint32_t sigma, uin
 int isr_debug_tensor(isr_model *m, const uint8_t *x_device, uint32_t sigma, uint64_t seed,
                      uint32_t image_id, uint32_t phase, uint32_t sample, int32_t tensor_id,
                      int8_t *out_host);
+
+/* Which plan isr_debug_tensor serves a tensor from while fusion is enabled: *from_fused_out = 1 when the
+ * fused kernels store that tensor themselves (the bytes returned are the fused kernel's own output),
+ * 0 when no fused kernel stores it and the op-by-op kernels produce it for the hook.  Lets a parity
+ * test say which kernels a tensor comparison exercises.  ISR_ERR_ARG for an id outside the table. */
+int isr_debug_tensor_source(const isr_model *m, int32_t tensor_id, int *from_fused_out);
 
 /* ---- host-only pieces (no GPU needed) ------------------------------------ */
 

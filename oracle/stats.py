@@ -73,6 +73,19 @@ def certify_decision(counts0, counts1, sigma: float, n: int, alpha: float):
     return ABSTAIN, 0.0, p_l, k
 
 
+def certify_decision_integer(counts0, counts1, sigma: int, n: int, alpha: float):
+    """Alg. 1 with the integer-only tail of Thm 3.2 (proof steps 2 and 3): the class and the
+    bound as in certify_decision, then the radius read off the discrete Gaussian's own cdf
+    table instead of sigma * Phi^-1 -- returns (class, t, t * t or 0); (ABSTAIN, 0, 0) when
+    the bound is not above 1/2.  t may be <= 0 for a bound barely above 1/2: the class is
+    returned with squared radius 0."""
+    c_a = lowest_argmax(counts0)
+    p_l = cp_lower(int(counts1[c_a]), n, alpha)
+    if not p_l > 0.5:
+        return ABSTAIN, 0, 0
+    return c_a, discrete_quantile(sigma, p_l), radius_squared_int(sigma, p_l)
+
+
 def binom_pvalue(n_a: int, n_b: int) -> float:
     """Two-sided p-value of the hypothesis that n_a successes out of
     n_a + n_b trials come from a fair coin (Alg. 2, the binomial test):

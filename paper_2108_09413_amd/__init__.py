@@ -21,7 +21,7 @@ ABSTAIN = -1
 EXPORTS = [
     "isr_load_model", "isr_free_model", "isr_validate_model", "isr_model_info", "isr_workspace_bytes",
     "isr_set_workspace", "isr_certify", "isr_predict", "isr_debug_noisy", "isr_debug_forward",
-    "isr_debug_tensor", "isr_noise_table", "isr_cp_lower", "isr_normal_quantile", "isr_binom_pvalue",
+    "isr_debug_tensor", "isr_debug_tensor_source", "isr_noise_table", "isr_cp_lower", "isr_normal_quantile", "isr_binom_pvalue",
     "isr_decide_certify", "isr_decide_predict", "isr_discrete_quantile", "isr_set_fusion", "isr_set_conv_tile", "isr_profile", "isr_profile_read", "isr_strerror",
     "isr_last_device_error", "isr_certify_batch", "isr_predict_batch", "isr_certified_metrics", "isr_noise_bank",
 ]
@@ -38,11 +38,13 @@ class IsrError(RuntimeError):
 
 class Result(C.Structure):
     _fields_ = [("cls", C.c_int32), ("radius", C.c_double), ("p_lower", C.c_double),
-                ("n_top", C.c_uint32), ("n_second", C.c_uint32)]
+                ("n_top", C.c_uint32), ("n_second", C.c_uint32),
+                ("radius_int", C.c_int32), ("radius_sq_int", C.c_uint64)]
 
     def __repr__(self):
         return (f"Result(cls={self.cls}, radius={self.radius!r}, p_lower={self.p_lower!r}, "
-                f"n_top={self.n_top}, n_second={self.n_second})")
+                f"n_top={self.n_top}, n_second={self.n_second}, radius_int={self.radius_int}, "
+                f"radius_sq_int={self.radius_sq_int})")
 
 
 class Item(C.Structure):
@@ -78,6 +80,7 @@ def lib():
         L.isr_debug_noisy.argtypes = [vp, vp, u32, u64, u32, u32, u32, u32, vp]
         L.isr_debug_forward.argtypes = [vp, vp, u32, u64, u32, u32, u32, u32, vp, vp, vp]
         L.isr_debug_tensor.argtypes = [vp, vp, u32, u64, u32, u32, u32, i32, vp]
+        L.isr_debug_tensor_source.argtypes = [vp, i32, C.POINTER(C.c_int)]
         L.isr_noise_table.argtypes = [u32, vp, sz, C.POINTER(u32)]
         L.isr_cp_lower.argtypes = [u32, u32, dbl, C.POINTER(dbl)]
         L.isr_normal_quantile.argtypes = [dbl, C.POINTER(dbl)]
@@ -236,18 +239,23 @@ def isr_set_workspace(model: Model, chunk_samples: int, stream=None):
     model.workspace, model.chunk, model.stream = ws, chunk_samples, st
 
 
-def _dev_image(x):
-    """uint8 [C][H][W] image on the device (torch tensor); numpy input is uploaded."""
+def _dev_image(model, x):
+    """uint8 [C][H][W] image on the device (torch tensor); numpy input is uploaded with a blocking
+    copy, so it is resident whatever stream the library works on.  A tensor the caller produced on
+    another stream than the model's must be ordered before the call by the caller."""
     import torch
     if isinstance(x, np.ndarray):
         x = torch.from_numpy(np.ascontiguousarray(x, dtype=np.uint8)).cuda()
     assert x.dtype == torch.uint8 and x.is_cuda and x.is_contiguous()
+    # the kernels read exactly C*H*W bytes from this pointer
+    if x.numel() != model.C * model.H * model.W:
+        raise IsrError(ISR_ERR_ARG, f"image of {x.numel()} bytes for a {model.C}x{model.H}x{model.W} model")
     return x
 
 
 def isr_certify(model: Model, x, sigma: int, n0: int, n: int, alpha: float, seed: int = 0, image_id: int = 0,
                 want_counts: bool = True):
-    x = _dev_image(x)
+    x = _dev_image(model, x)
     res = Result()
     c0 = np.zeros(model.classes, dtype=np.uint32) if want_counts else None
     c1 = np.zeros(model.classes, dtype=np.uint32) if want_counts else None
@@ -257,7 +265,7 @@ def isr_certify(model: Model, x, sigma: int, n0: int, n: int, alpha: float, seed
 
 
 def isr_predict(model: Model, x, sigma: int, n: int, alpha: float, seed: int = 0, image_id: int = 0):
-    x = _dev_image(x)
+    x = _dev_image(model, x)
     res = Result()
     c = np.zeros(model.classes, dtype=np.uint32)
     _check(lib().isr_predict(model.handle, C.c_void_p(x.data_ptr()), sigma, n, alpha, C.c_uint64(seed), image_id,
@@ -277,12 +285,14 @@ def isr_noise_bank(sigma: int, seed: int, bank_id: int, first: int, count: int, 
     return out
 
 
-def _dev_images(xs):
+def _dev_images(model, xs):
     """uint8 [n][C][H][W] image array on the device."""
     import torch
     if isinstance(xs, np.ndarray):
         xs = torch.from_numpy(np.ascontiguousarray(xs, dtype=np.uint8)).cuda()
     assert xs.dtype == torch.uint8 and xs.is_cuda and xs.is_contiguous() and xs.dim() == 4
+    if tuple(xs.shape[1:]) != (model.C, model.H, model.W):
+        raise IsrError(ISR_ERR_ARG, f"images of shape {tuple(xs.shape[1:])} for a {model.C}x{model.H}x{model.W} model")
     return xs
 
 
@@ -292,7 +302,7 @@ def _items(items):
 
 def isr_certify_batch(model: Model, xs, items, n0: int, n: int, alpha: float, seed: int = 0):
     """items: list of (image index, sigma, image_id).  Returns (results, counts0, counts1)."""
-    xs = _dev_images(xs)
+    xs = _dev_images(model, xs)
     res = (Result * len(items))()
     c0 = np.zeros((len(items), model.classes), dtype=np.uint32)
     c1 = np.zeros((len(items), model.classes), dtype=np.uint32)
@@ -302,7 +312,7 @@ def isr_certify_batch(model: Model, xs, items, n0: int, n: int, alpha: float, se
 
 
 def isr_predict_batch(model: Model, xs, items, n: int, alpha: float, seed: int = 0):
-    xs = _dev_images(xs)
+    xs = _dev_images(model, xs)
     res = (Result * len(items))()
     c = np.zeros((len(items), model.classes), dtype=np.uint32)
     _check(lib().isr_predict_batch(model.handle, C.c_void_p(xs.data_ptr()), xs.shape[0], _items(items), len(items), n,
@@ -311,7 +321,7 @@ def isr_predict_batch(model: Model, xs, items, n: int, alpha: float, seed: int =
 
 
 def isr_debug_noisy(model: Model, x, sigma: int, seed: int, image_id: int, phase: int, sample_begin: int, count: int):
-    x = _dev_image(x)
+    x = _dev_image(model, x)
     out = np.zeros((count, model.C, model.H, model.W), dtype=np.int8)
     _check(lib().isr_debug_noisy(model.handle, C.c_void_p(x.data_ptr()), sigma, C.c_uint64(seed), image_id, phase,
                                  sample_begin, count, _np_ptr(out)), "isr_debug_noisy")
@@ -320,7 +330,7 @@ def isr_debug_noisy(model: Model, x, sigma: int, seed: int, image_id: int, phase
 
 def isr_debug_forward(model: Model, x, sigma: int, seed: int, image_id: int, phase: int, sample_begin: int,
                       count: int, want_logits: bool = True):
-    x = _dev_image(x)
+    x = _dev_image(model, x)
     logits = np.zeros((count, model.classes), dtype=np.int32) if want_logits else None
     argmax = np.zeros(count, dtype=np.int32)
     counts = np.zeros(model.classes, dtype=np.uint32)
@@ -332,11 +342,18 @@ def isr_debug_forward(model: Model, x, sigma: int, seed: int, image_id: int, pha
 
 def isr_debug_tensor(model: Model, x, sigma: int, seed: int, image_id: int, phase: int, sample: int,
                      tensor_id: int, shape):
-    x = _dev_image(x)
+    x = _dev_image(model, x)
     out = np.zeros(shape, dtype=np.int8)
     _check(lib().isr_debug_tensor(model.handle, C.c_void_p(x.data_ptr()), sigma, C.c_uint64(seed), image_id, phase,
                                   sample, tensor_id, _np_ptr(out)), "isr_debug_tensor")
     return out
+
+
+def isr_debug_tensor_source(model: Model, tensor_id: int) -> bool:
+    """True when isr_debug_tensor returns the fused kernels' own output for this tensor."""
+    out = C.c_int(0)
+    _check(lib().isr_debug_tensor_source(model.handle, tensor_id, C.byref(out)), "isr_debug_tensor_source")
+    return bool(out.value)
 
 
 def isr_set_fusion(model: Model, enable: bool):

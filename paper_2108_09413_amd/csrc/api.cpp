@@ -422,14 +422,13 @@ int isr_set_fusion(isr_model *m, int enable) {
 
 int isr_discrete_quantile(uint32_t sigma, double p_lower, int32_t *t_out, uint64_t *radius_sq_out) {
     if (sigma < 1 || sigma > 1024 || !(p_lower >= 0.0 && p_lower <= 1.0)) return ISR_ERR_ARG;
-    std::vector<uint64_t> T;
-    uint32_t R = 0;
-    if (!build_noise_table(sigma, T, R)) return ISR_ERR_ARG;
+    const auto tab = cached_noise_table(sigma);
+    if (!tab) return ISR_ERR_ARG;
     // floor(2^64 p): exact for a double below 1 (53 significant bits, scaled by a power of two)
     const uint64_t u = p_lower >= 1.0 ? ~0ull : (uint64_t)std::ldexp(p_lower, 64);
     // thresholds ascend: the number of entries <= u by binary search
-    const int64_t below = std::upper_bound(T.begin(), T.end(), u) - T.begin();
-    const int64_t t = -(int64_t)R - 1 + below;
+    const int64_t below = std::upper_bound(tab->T.begin(), tab->T.end(), u) - tab->T.begin();
+    const int64_t t = -(int64_t)tab->R - 1 + below;
     if (t_out) *t_out = (int32_t)t;
     if (radius_sq_out) *radius_sq_out = t > 0 ? (uint64_t)(t * t) : 0;
     return ISR_OK;
@@ -440,9 +439,10 @@ int isr_noise_bank(uint32_t sigma, uint64_t seed, uint32_t bank_id, uint32_t fir
     if (sigma < 1 || sigma > 1024 || !out_device || d == 0 || (d & 3) != 0) return ISR_ERR_ARG;
     if ((uint64_t)first + count > (1ull << 32)) return ISR_ERR_ARG;
     if (count == 0) return ISR_OK;
-    std::vector<uint64_t> T;
-    uint32_t R = 0;
-    if (!build_noise_table(sigma, T, R)) return ISR_ERR_ARG;
+    const auto tab = cached_noise_table(sigma);
+    if (!tab) return ISR_ERR_ARG;
+    const std::vector<uint64_t> &T = tab->T;
+    const uint32_t R = tab->R;
     const size_t n = T.size();
     // device form: high words, low words, guide table (as 32-bit words so that one upload carries all)
     const size_t guide_words = (NOISE_GUIDE_SIZE + 2) / 2;
@@ -692,6 +692,13 @@ int isr_debug_tensor(isr_model *m, const uint8_t *x_device, uint32_t sigma, uint
     HIP_TRY(hipStreamSynchronize(m->stream));
     for (int c = 0; c < t.C; ++c)
         for (size_t i = 0; i < hw; ++i) out_host[(size_t)c * hw + i] = tmp[i * t.Cp + c];
+    return ISR_OK;
+}
+
+int isr_debug_tensor_source(const isr_model *m, int32_t tensor_id, int *from_fused_out) {
+    if (!m || !from_fused_out || tensor_id < 0 || tensor_id >= (int)m->pm.tensors.size()) return ISR_ERR_ARG;
+    if (m->plan[1].has.empty()) return ISR_ERR_WORKSPACE;   // plans are placed by isr_set_workspace
+    *from_fused_out = (m->use_fused && m->plan[1].has[tensor_id]) ? 1 : 0;
     return ISR_OK;
 }
 

@@ -133,12 +133,19 @@ extern "C" int isr_decide_certify(const uint32_t *counts0, const uint32_t *count
     out->n_top = k;
     out->n_second = 0;
     out->p_lower = pl;
+    out->radius_int = 0;
+    out->radius_sq_int = 0;
     if (pl > 0.5) {
         double z = 0.0;
         rc = isr_normal_quantile(pl, &z);
         if (rc != ISR_OK) return rc;
         out->cls = (int32_t)ca;
         out->radius = sigma * z;
+        // integer-only tail (Thm 3.2, proof steps 2-3): quantile of the discrete law by table lookup
+        if (sigma >= 1.0 && sigma <= 1024.0 && sigma == std::floor(sigma)) {
+            rc = isr_discrete_quantile((uint32_t)sigma, pl, &out->radius_int, &out->radius_sq_int);
+            if (rc != ISR_OK) return rc;
+        }
     } else {
         out->cls = ISR_ABSTAIN;
         out->radius = 0.0;
@@ -154,6 +161,8 @@ extern "C" int isr_decide_predict(const uint32_t *counts, uint32_t classes, doub
     double pv = 1.0;
     int rc = isr_binom_pvalue(counts[ca], nb, &pv);
     if (rc != ISR_OK) return rc;
+    out->radius_int = 0;
+    out->radius_sq_int = 0;
     out->n_top = counts[ca];
     out->n_second = nb;
     out->p_lower = pv;

@@ -6,6 +6,7 @@
 
 #include <cstddef>
 #include <cstdint>
+#include <memory>
 #include <string>
 #include <vector>
 
@@ -27,6 +28,12 @@ struct DeviceNoiseTable {
 };
 
 bool build_noise_table(uint32_t sigma, std::vector<uint64_t> &T, uint32_t &R);
+struct NoiseTable {
+    std::vector<uint64_t> T;   // 2R ascending thresholds
+    uint32_t R = 0;
+};
+// Shared, immutable table of a sigma (built on first use); null for sigma outside 1..1024.
+std::shared_ptr<const NoiseTable> cached_noise_table(uint32_t sigma);
 bool build_device_table(uint32_t sigma, DeviceNoiseTable &out);
 
 // ---- parsed model (host) ---------------------------------------------------

@@ -2,6 +2,9 @@
 // (Def. 3.3 with location 0), integer arithmetic only, and the compact form
 // of it the device sampler reads.
 #include <cstdint>
+#include <map>
+#include <memory>
+#include <mutex>
 #include <vector>
 
 #include "isr.h"
@@ -47,14 +50,30 @@ bool build_noise_table(uint32_t sigma, std::vector<uint64_t> &T, uint32_t &R) {
     return true;
 }
 
+// The table of a sigma is a pure function of sigma: built once per process and shared
+// (the certification decision looks its quantile up in it on every call).
+std::shared_ptr<const NoiseTable> cached_noise_table(uint32_t sigma) {
+    static std::mutex mu;
+    static std::map<uint32_t, std::shared_ptr<const NoiseTable>> cache;
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = cache.find(sigma);
+    if (it != cache.end()) return it->second;
+    auto t = std::make_shared<NoiseTable>();
+    if (!build_noise_table(sigma, t->T, t->R)) return nullptr;
+    if (cache.size() >= 64) cache.clear();   // bounds the memory held (at most 147 KB per sigma)
+    cache[sigma] = t;
+    return t;
+}
+
 // Device form.  Pixels lie in [0, 255], so after saturation only
 // clamp(delta, -255, 255) matters: keep the (at most 510) thresholds between
 // -255 and 255, split into high/low words, plus a guide table on the top
 // GUIDE_BITS bits of the high word: guide[b] = #{j : hi[j] < (b << (32-GUIDE_BITS))}.
 bool build_device_table(uint32_t sigma, DeviceNoiseTable &out) {
-    std::vector<uint64_t> T;
-    uint32_t R = 0;
-    if (!build_noise_table(sigma, T, R)) return false;
+    const auto tab = cached_noise_table(sigma);
+    if (!tab) return false;
+    const std::vector<uint64_t> &T = tab->T;
+    const uint32_t R = tab->R;
     uint32_t reach = R < 255 ? R : 255;
     uint32_t first = R - reach;
     uint32_t n = 2 * reach;
@@ -78,10 +97,9 @@ bool build_device_table(uint32_t sigma, DeviceNoiseTable &out) {
 
 extern "C" int isr_noise_table(uint32_t sigma, uint64_t *T_host, size_t cap, uint32_t *R_out) {
     if (!R_out || (cap && !T_host)) return ISR_ERR_ARG;
-    std::vector<uint64_t> T;
-    uint32_t R = 0;
-    if (!isr::build_noise_table(sigma, T, R)) return ISR_ERR_ARG;
-    *R_out = R;
-    for (size_t i = 0; i < cap && i < T.size(); ++i) T_host[i] = T[i];
+    const auto tab = isr::cached_noise_table(sigma);
+    if (!tab) return ISR_ERR_ARG;
+    *R_out = tab->R;
+    for (size_t i = 0; i < cap && i < tab->T.size(); ++i) T_host[i] = tab->T[i];
     return ISR_OK;
 }

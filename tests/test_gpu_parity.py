@@ -32,6 +32,19 @@ def _say(msg):
     print(msg, flush=True)
 
 
+def _oracle_at(om, x, sigma, seed, image, phase, indices):
+    """Oracle logits and argmax of scattered sample indices, one host thread per index."""
+    from concurrent.futures import ThreadPoolExecutor
+    import os
+
+    def one(i):
+        lg, am, _ = om.mc(x, sigma, seed, image, phase, int(i), 1, threads=1)
+        return lg[0], int(am[0])
+    with ThreadPoolExecutor(max_workers=min(os.cpu_count() or 1, 16)) as ex:
+        out = list(ex.map(one, indices))
+    return np.stack([o[0] for o in out]), np.array([o[1] for o in out])
+
+
 # ---- S2: noise -------------------------------------------------------------
 
 @pytest.mark.parametrize("sigma", [1, 32, 64, 128, 256, 1024])
@@ -115,16 +128,28 @@ def test_device_sampler_law_at_scale(isr, sigma):
 
 # ---- S3-S6: layer tensors ----------------------------------------------------
 
-def _check_all_tensors(isr, blob, x, sigma, seed=3, image=1, phase=1, sample=17, chunk=4):
+def _check_all_tensors(isr, blob, x, sigma, seed=3, image=1, phase=1, sample=17, chunk=4, min_fused=0):
+    """Every tensor of one noisy copy against the oracle.  With fusion on (the default) a tensor that
+    a fused kernel stores is that kernel's own output; a tensor that no fused kernel stores (the
+    output of a convolution folded into a residual add, the 112x112 first-layer output under the
+    pooling fusion, the middle tensors of a block kernel) is served by the op-by-op kernels, so that
+    comparison checks those kernels and not the fused ones -- isr_debug_tensor_source says which.
+    The fused kernels are covered by the tensors they do store (block outputs), by the logits of
+    this copy below, and by the multi-copy logits check that follows every fused-kernel test.
+    min_fused: at least that many tensors must come from fused kernels (guards the test's premise)."""
     m = _load(isr, blob, chunk)
     om = oracle.Model(blob)
     a0 = oracle.noisy(x, sigma, seed, image, phase, sample)
     logits, tensors = om.forward(a0)
+    n_fused = 0
     for tid in sorted(tensors):
         c, h, w, _ = om.tensor_shape(tid)
         got = isr.isr_debug_tensor(m, x, sigma, seed, image, phase, sample, tid, (c, h, w))
         bad = np.argwhere(got != tensors[tid])
-        assert bad.size == 0, f"tensor {tid} shape {(c, h, w)}: {len(bad)} mismatches, first at {bad[0]}"
+        src = "fused" if isr.isr_debug_tensor_source(m, tid) else "op-by-op"
+        n_fused += src == "fused"
+        assert bad.size == 0, f"tensor {tid} ({src} plan) shape {(c, h, w)}: {len(bad)} mismatches, first at {bad[0]}"
+    assert n_fused >= min_fused, (n_fused, min_fused)
     gl, ga, gc = isr.isr_debug_forward(m, x, sigma, seed, image, phase, sample, 1)
     assert np.array_equal(gl[0], logits)
     m.close()
@@ -402,6 +427,9 @@ def test_config0_full_certify_and_predict(isr):
     assert res.cls == cls and res.n_top == k
     assert res.p_lower == pytest.approx(p_l, rel=1e-12)
     assert res.radius == pytest.approx(rad, rel=1e-9)
+    # integer-only tail (Thm 3.2, proof steps 2-3) from the device tallies, in the same call
+    assert (res.cls, res.radius_int, res.radius_sq_int) == oracle.stats.certify_decision_integer(oc0, oc1, 32, 1000, ALPHA)
+    assert res.radius_int > 0 and res.radius_sq_int == res.radius_int ** 2 and res.radius_int <= res.radius
     lg, am, cnt = isr.isr_debug_forward(m, x, 32, 0, 0, 1, 0, 1000)
     olg, oam, ocnt = om.mc(x, 32, 0, 0, 1, 0, 1000)
     assert np.array_equal(lg, olg) and np.array_equal(am, oam) and np.array_equal(cnt, ocnt)
@@ -452,20 +480,20 @@ def test_fused_and_unfused_kernels_agree(isr):
         m.close()
 
 
-def test_resnet20_logits_and_votes(isr):
-    _say("resnet20 logits parity")
+@pytest.mark.parametrize("item,sigma", [(1, 32), (1, 64), (1, 128), (2, 32), (2, 64), (2, 128)])
+def test_resnet20_logits_and_votes(isr, item, sigma):
+    """Two images at the three noise levels of the CIFAR-shaped workload: every selection sample
+    (n0 = 100), the first 5000 and the last 300 estimation samples of an n = 100000 run --
+    per-sample logits, argmax and tallies against the oracle."""
+    _say(f"resnet20 logits parity image {item} sigma {sigma}")
     blob = synth.build_model(1)
     om = oracle.Model(blob)
-    m = _load(isr, blob, 512)
-    for item, sigma in ((1, 32), (2, 64), (1, 128)):
-        x = synth.make_image(1, item)
-        lg, am, cnt = isr.isr_debug_forward(m, x, sigma, 0, item, 0, 0, 100)
-        olg, oam, ocnt = om.mc(x, sigma, 0, item, 0, 0, 100)
+    m = _load(isr, blob, 2048)
+    x = synth.make_image(1, item)
+    for phase, begin, count in ((0, 0, 100), (1, 0, 5000), (1, 99700, 300)):
+        lg, am, cnt = isr.isr_debug_forward(m, x, sigma, 0, item, phase, begin, count)
+        olg, oam, ocnt = om.mc(x, sigma, 0, item, phase, begin, count)
         assert np.array_equal(lg, olg) and np.array_equal(am, oam) and np.array_equal(cnt, ocnt)
-        for begin, count in ((0, 1000), (99700, 300)):     # first and last estimation samples of n = 100000
-            lg, am, cnt = isr.isr_debug_forward(m, x, sigma, 0, item, 1, begin, count)
-            olg, oam, ocnt = om.mc(x, sigma, 0, item, 1, begin, count)
-            assert np.array_equal(lg, olg) and np.array_equal(am, oam) and np.array_equal(cnt, ocnt)
     m.close()
 
 
@@ -483,6 +511,7 @@ def test_resnet20_certify_and_predict_end_to_end(isr):
     assert res.cls == cls and res.n_top == k
     assert res.p_lower == pytest.approx(p_l, rel=1e-12)
     assert res.radius == pytest.approx(rad, rel=1e-9)
+    assert (res.cls, res.radius_int, res.radius_sq_int) == oracle.stats.certify_decision_integer(oc0, oc1, 64, 1500, ALPHA)
     pres, pc = isr.isr_predict(m, x, 128, 333, ALPHA, seed=12, image_id=4)
     pcls, pv, n_a, n_b, opc = oracle.predict(om, x, 128, 333, ALPHA, seed=12, image=4)
     assert np.array_equal(pc, opc) and (pres.cls, pres.n_top, pres.n_second) == (pcls, n_a, n_b)
@@ -491,30 +520,59 @@ def test_resnet20_certify_and_predict_end_to_end(isr):
 
 
 def test_resnet110_logits(isr):
+    """1000 noisy copies of the deep narrow net inside bench.py's chunk of 4096 (the block-chain
+    kernels with every workgroup full and a ragged last one): logits, argmax, tallies."""
     _say("resnet110 logits parity")
     blob = synth.build_model(2)
     om = oracle.Model(blob)
-    m = _load(isr, blob, 64)
+    m = _load(isr, blob, 4096)
     x = synth.make_image(2, 1)
-    lg, am, cnt = isr.isr_debug_forward(m, x, 64, 0, 1, 1, 500, 256)
-    olg, oam, ocnt = om.mc(x, 64, 0, 1, 1, 500, 256)
+    lg, am, cnt = isr.isr_debug_forward(m, x, 64, 0, 1, 1, 500, 1000)
+    olg, oam, ocnt = om.mc(x, 64, 0, 1, 1, 500, 1000)
     assert np.array_equal(lg, olg) and np.array_equal(am, oam) and np.array_equal(cnt, ocnt)
     m.close()
 
 
-def test_resnet50_full_size_logits(isr):
-    """ResNet-50 at 224x224, 101 classes: a few sample indices from disjoint
-    ranges (including the last indices of a 100000-sample run)."""
-    _say("resnet50 224 logits parity")
-    blob = synth.build_model(3)
+@pytest.mark.parametrize("sigma", [32, 64, 128, 256])
+def test_resnet50_full_size_logits(isr, sigma):
+    """ResNet-50 at 224x224, 101 classes: 64 sample indices per noise level in four disjoint
+    ranges -- the selection loop, the start, the middle and the last indices of a
+    100000-sample estimation loop -- on two images."""
+    _say(f"resnet50 224 logits parity sigma {sigma}")
+    blob = synth.build_model(4)
     om = oracle.Model(blob)
-    m = _load(isr, blob, 8)
-    x = synth.make_image(3, 1)
-    for sigma, phase, begin, count in ((64, 0, 0, 12), (128, 1, 99988, 12), (32, 1, 50000, 8), (256, 0, 92, 8)):
-        _say(f"  sigma={sigma} phase={phase} begin={begin}")
-        lg, am, cnt = isr.isr_debug_forward(m, x, sigma, 0, 1, phase, begin, count)
-        olg, oam, ocnt = om.mc(x, sigma, 0, 1, phase, begin, count)
+    m = _load(isr, blob, 16)
+    for item, phase, begin, count in ((1, 0, 0, 16), (1, 1, 0, 16), (2, 1, 50000, 16), (2, 1, 99984, 16)):
+        x = synth.make_image(4, item)
+        lg, am, cnt = isr.isr_debug_forward(m, x, sigma, 0, item, phase, begin, count)
+        olg, oam, ocnt = om.mc(x, sigma, 0, item, phase, begin, count)
         assert np.array_equal(lg, olg) and np.array_equal(am, oam) and np.array_equal(cnt, ocnt)
+    m.close()
+
+
+# copies of a 668-copy chunk that sit on the boundaries of the kernels' pixel tiles: first and last
+# copy, both sides of the 64-, 128- and 256-copy marks (whole tiles at 7x7 ... 56x56 pixels per
+# copy), the middle of the chunk (second round of workgroups), and the ragged end
+CHUNK668_COPIES = (0, 1, 2, 31, 32, 63, 64, 65, 127, 128, 191, 192, 255, 256, 257, 300, 333, 334, 335, 400,
+                   447, 448, 511, 512, 513, 575, 576, 639, 640, 665, 666, 667)
+
+
+@pytest.mark.parametrize("sigma,item", [(32, 1), (256, 3)])
+def test_resnet50_chunk_668_sampled_copies(isr, sigma, item):
+    """bench.py's launch configuration (chunks of 668 copies, library-chosen tiles) at the
+    smallest and the largest noise level of the headline sweep: 32 copies spread over the
+    chunk, chosen on tile and workgroup-round boundaries, against the oracle one by one."""
+    _say(f"resnet50 224 parity at chunk 668, sigma {sigma}")
+    blob = synth.build_model(4)
+    om = oracle.Model(blob)
+    m = _load(isr, blob, 668)
+    x = synth.make_image(4, item)
+    begin = 99332                                # the last full chunk of an n = 100000 run
+    lg, am, cnt = isr.isr_debug_forward(m, x, sigma, 0, item, 1, begin, 668)
+    assert int(cnt.sum()) == 668 and np.array_equal(np.bincount(am, minlength=len(cnt)), cnt)
+    olg, oam = _oracle_at(om, x, sigma, 0, item, 1, [begin + i for i in CHUNK668_COPIES])
+    for j, i in enumerate(CHUNK668_COPIES):
+        assert np.array_equal(lg[i], olg[j]) and am[i] == oam[j], i
     m.close()
 
 
@@ -531,10 +589,10 @@ def test_resnet50_in_the_benchmarked_launch_configuration(isr):
     lg, am, cnt = isr.isr_debug_forward(m, x, 128, 0, 2, 1, 20000, 668)
     assert int(cnt.sum()) == 668 and np.array_equal(np.bincount(am, minlength=len(cnt)), cnt)
     assert np.array_equal(am, np.argmax(lg, axis=1))
-    for i in (0, 255, 667):
-        _say(f"  oracle sample {20000 + i}")
-        olg, oam, _ = om.mc(x, 128, 0, 2, 1, 20000 + i, 1)
-        assert np.array_equal(lg[i], olg[0]) and am[i] == oam[0]
+    picks = (0, 100, 255, 256, 333, 334, 512, 667)
+    olg, oam = _oracle_at(om, x, 128, 0, 2, 1, [20000 + i for i in picks])
+    for j, i in enumerate(picks):
+        assert np.array_equal(lg[i], olg[j]) and am[i] == oam[j], i
     for tile in (1, 2, 3, 4):
         _say(f"  forced tile {tile}")
         isr.isr_set_conv_tile(m, tile)
@@ -609,6 +667,8 @@ def _check_batch_against_oracle(isr, m, om, xs, items, n0, n, seed):
         assert res[i].cls == cls and res[i].n_top == k
         assert res[i].p_lower == pytest.approx(p_l, rel=1e-12)
         assert res[i].radius == pytest.approx(rad, rel=1e-9)
+        assert (res[i].cls, res[i].radius_int, res[i].radius_sq_int) == \
+            oracle.stats.certify_decision_integer(oc0, oc1, items[i][1], n, ALPHA), (i, items[i])
     pres, pc = isr.isr_predict_batch(m, xs, items, n, ALPHA, seed=seed + 1)
     pwant = oracle.predict_batch(om, xs, items, n, ALPHA, seed=seed + 1)
     for i, (cls, pv, n_a, n_b, opc) in enumerate(pwant):

@@ -77,6 +77,17 @@ def test_statistics_agree_with_oracle_on_random_counts():
         assert res.p_lower == pytest.approx(pl, rel=1e-12, abs=1e-15)
         if cls != ostats.ABSTAIN:
             assert res.radius == pytest.approx(rad, rel=max(1e-9, 1e-15 / abs(pl - 0.5)))
+        # integer-only tail on the same tallies (Thm 3.2): computed from the library's own bound,
+        # which may differ from the oracle's in the last bits -- compare on the library's bound
+        icls, t, t2 = ostats.certify_decision_integer(c0, c1, int(sigma), n, alpha)
+        assert icls == res.cls
+        if cls != ostats.ABSTAIN:
+            assert res.radius_int == ostats.discrete_quantile(int(sigma), res.p_lower)
+            assert res.radius_sq_int == ostats.radius_squared_int(int(sigma), res.p_lower)
+            assert abs(res.radius_int - t) <= (1 if abs(res.p_lower - pl) > 0 else 0)
+            assert res.radius - 1.5 - 1e-6 <= res.radius_int <= res.radius - 0.5 + 1e-6 + 1e-3 * sigma
+        else:
+            assert (res.radius_int, res.radius_sq_int) == (0, 0) and (t, t2) == (0, 0)
         cp = rng.multinomial(int(rng.choice([10, 100, 1000, 100000])), rng.dirichlet(np.ones(C) * 0.5)).astype(np.uint32)
         rp = isr.isr_decide_predict(cp, alpha)
         pc, pv, na, nb = ostats.predict_decision(cp, alpha)

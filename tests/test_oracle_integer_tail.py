@@ -76,3 +76,32 @@ def test_symmetry_and_monotonicity_and_edges():
     assert stats.discrete_quantile(32, 1.0) == 270 and stats.discrete_quantile(32, 0.0) == -272
     with pytest.raises(ValueError):
         stats.discrete_quantile(32, 1.5)
+
+
+def test_integer_certification_on_hand_tallies():
+    """Alg. 1 with the integer tail (Thm 3.2, proof steps 2-3) on tallies whose outcome is fixed by
+    the definitions: every estimation vote on one class gives p_A = alpha^(1/n), whose quantile
+    under the lattice law is read here off the cdf summed from Def. 3.3 in 60 digits; a bound
+    below one half abstains; the class comes from the selection tally, not the estimation tally."""
+    sigma, n, alpha = 64, 1000, 0.001
+    c0 = np.array([3, 90, 7], dtype=np.uint32)
+    c1 = np.array([0, n, 0], dtype=np.uint32)
+    cls, t, t2 = stats.certify_decision_integer(c0, c1, sigma, n, alpha)
+    p = mp.mpf(alpha) ** (mp.mpf(1) / n)
+    cdf = _exact_cdf(sigma, 100, 200)
+    want = max(k for k in cdf if cdf[k] <= p)
+    assert (cls, t, t2) == (1, want, want * want) and 100 < want < 200
+    assert stats.radius(sigma, float(p)) - 1.5 <= t <= stats.radius(sigma, float(p)) - 0.5
+    # the estimation tally's own top class is ignored: class 1 was selected, its 400 of 1000 votes abstain
+    c1b = np.array([600, 400, 0], dtype=np.uint32)
+    assert stats.certify_decision_integer(c0, c1b, sigma, n, alpha) == (stats.ABSTAIN, 0, 0)
+    # selected class with 600 of 1000: p_A = 0.5510754739370525 (golden file), a small positive radius
+    c1c = np.array([400, 600, 0], dtype=np.uint32)
+    cls, t, t2 = stats.certify_decision_integer(c0, c1c, sigma, n, alpha)
+    cdf = _exact_cdf(sigma, 0, 20)
+    want = max(k for k in cdf if cdf[k] <= mp.mpf("0.55107547393705244475"))
+    assert (cls, t, t2) == (1, want, want * want) and want == 7   # 64 * 0.12838 - 1/2 = 7.7
+    # a bound just above one half: class returned, quantile -1 or 0, squared radius 0
+    c1d = np.array([450, 550, 0], dtype=np.uint32)    # p_A = 0.50067596 (smallest certifying count)
+    cls, t, t2 = stats.certify_decision_integer(c0, c1d, sigma, n, alpha)
+    assert cls == 1 and t in (-1, 0) and t2 == 0
