@@ -29,6 +29,8 @@ constexpr int TABLE_SLOTS = 8;
 
 }  // namespace
 
+void isr::set_last_device_error(int hip_error) { g_last_hip_error = hip_error; }
+
 struct isr_model {
     ParsedModel pm;
     std::vector<DevOp> ops;             // one descriptor per op of the blob
@@ -95,6 +97,11 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
     const ParsedModel &pm = m->pm;
     uint8_t *ws = m->ws;
     if (bc) count = (uint64_t)bc->n_items * bc->n_per_item;
+    // bytes of one copy of a tensor: copies are contiguous, so a range of copies of a chunk is a sub-chunk
+    auto tptr = [&](int t, uint32_t first_copy) -> uint8_t * {
+        const TensorDesc &d = pm.tensors[t];
+        return ws + pl.toff[t] + (size_t)first_copy * d.H * d.W * d.Cp;
+    };
     for (uint64_t done = 0; done < count;) {
         uint32_t cnt = (uint32_t)std::min<uint64_t>(m->chunk, count - done);
         if (bc) cnt = (uint32_t)std::min<uint64_t>(cnt, (uint64_t)bc->n_per_item * 65534);   // one grid row per item
@@ -114,147 +121,181 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
         };
         std::vector<std::pair<double, double>> ev_work;   // (ops, bytes) per timed launch
         int prc;
-        NoiseParams np;
-        np.x = x; np.table = table; np.out = (int8_t *)(ws + pl.toff[0]);
-        np.C = pm.C; np.H = pm.H; np.W = pm.W;
-        np.key0 = (uint32_t)seed; np.key1 = (uint32_t)(seed >> 32);
-        np.image = image; np.phase = phase; np.sample_begin = begin + (uint32_t)done; np.count = cnt;
-        np.items = nullptr; np.n_per_item = 0; np.item_first = 0; np.item_count = 0; np.slot_begin = 0;
-        if (bc) {
-            np.items = bc->items; np.n_per_item = bc->n_per_item; np.slot_begin = done;
-            np.item_first = (uint32_t)(done / bc->n_per_item);
-            np.item_count = (uint32_t)((done + cnt - 1) / bc->n_per_item) - np.item_first + 1;
-        }
-        if ((prc = mark(KC_NOISE)) != ISR_OK) return prc;
-        ev_work.push_back({0.0, (double)cnt * pm.H * pm.W * 4});
-        HIP_TRY(launch_noise(np, m->stream));
-        if (stop_tensor != 0) {
-            for (const DevOp &d : pl.ops) {
-                if ((prc = mark(d.kclass)) != ISR_OK) return prc;
-                ev_work.push_back({d.ops_per_sample * cnt, d.bytes_per_sample * cnt});
-                switch (d.type) {
-                case OP_CONV: {
-                    if (d.stem_pool) {
-                        const TensorDesc &to = pm.tensors[d.out];
-                        StemPoolParams sp;
-                        sp.in = (const int8_t *)(ws + pl.toff[d.a]);
-                        sp.out = (int8_t *)(ws + pl.toff[d.out]);
-                        sp.w = d.conv.w; sp.bias = d.conv.bias; sp.m0s = d.conv.m0s; sp.chi = d.conv.chi; sp.shm1 = d.conv.shm1;
-                        sp.H = d.conv.H; sp.W = d.conv.W; sp.Ho = d.conv.Ho; sp.Wo = d.conv.Wo; sp.Hp = to.H; sp.Wp = to.W;
-                        sp.zp_in = d.conv.zp_in; sp.zp_out = d.conv.zp_out; sp.relu = d.conv.relu; sp.tie_free = d.conv.tie_free; sp.B = (int32_t)cnt;
-                        HIP_TRY(launch_stem_pool(sp, m->stream));
-                        break;
-                    }
-                    if (d.stem16) {
-                        const ConvParams &c = d.conv;
-                        Stem16Params sp;
-                        sp.in = (const int8_t *)(ws + pl.toff[d.a]);
-                        sp.out = (int8_t *)(ws + pl.toff[d.out]);
-                        sp.w = c.w; sp.bias = c.bias; sp.m0s = c.m0s; sp.chi = c.chi; sp.shm1 = c.shm1;
-                        sp.H = c.H; sp.W = c.W; sp.B = (int32_t)cnt; sp.zp_in = c.zp_in;
-                        sp.lo = c.relu ? c.zp_out : -128; sp.tie_free = c.tie_free;
-                        HIP_TRY(launch_stem16(sp, m->stream));
-                        break;
-                    }
-                    if (d.block) {
-                        BlockParams bp{};
-                        bp.in = (const int8_t *)(ws + pl.toff[d.a]);
-                        bp.out = (int8_t *)(ws + pl.toff[d.out]);
-                        bp.blocks = m->dblocks + d.chain_off;
-                        bp.nblocks = (int32_t)d.chain.size();
-                        bp.C = d.conv.Cout_p; bp.S = d.conv.H; bp.B = (int32_t)cnt;
-                        bp.tie_free = d.conv.tie_free && d.conv2.tie_free && d.conv2.add_tie_free;
-                        HIP_TRY(launch_basic_block(bp, m->stream));
-                        break;
-                    }
-                    if (d.trans) {
-                        const ConvParams &c1 = d.conv, &c2 = d.conv2, &cp = d.conv3;
-                        TransParams tp{};
-                        tp.in = (const int8_t *)(ws + pl.toff[d.a]);
-                        tp.out = (int8_t *)(ws + pl.toff[d.out]);
-                        tp.w1 = c1.w; tp.bias1 = c1.bias; tp.m0s1 = c1.m0s; tp.chi1 = c1.chi; tp.shm11 = c1.shm1;
-                        tp.w2 = c2.w; tp.bias2 = c2.bias; tp.m0s2 = c2.m0s; tp.chi2 = c2.chi; tp.shm12 = c2.shm1;
-                        tp.wp = cp.w; tp.biasp = cp.bias; tp.m0sp = cp.m0s; tp.chip = cp.chi; tp.shm1p = cp.shm1;
-                        tp.C = c1.Cout_p; tp.S = c1.Ho; tp.B = (int32_t)cnt;
-                        tp.zp_x = c1.zp_in; tp.zp_t = c1.zp_out;
-                        tp.lo1 = c1.relu ? c1.zp_out : -128;
-                        tp.lo2 = c2.relu ? c2.zp_out : -128;
-                        tp.lop = cp.relu ? cp.zp_out : -128;
-                        tp.add_mul_self = cp.add_mul_self; tp.add_mul_res = cp.add_mul_res; tp.add_c0 = cp.add_c0;
-                        tp.add_k = cp.add_k; tp.add_sh = cp.add_sh; tp.add_lo = cp.add_lo;
-                        tp.tie_free = c1.tie_free && c2.tie_free && cp.tie_free && cp.add_tie_free;
-                        HIP_TRY(launch_trans_block(tp, m->stream));
-                        break;
-                    }
-                    if (d.bneck) {
-                        const ConvParams &c1 = d.conv, &c2 = d.conv2, &c3 = d.conv3;
-                        BneckParams bp{};
-                        bp.in = (const int8_t *)(ws + pl.toff[d.a]);
-                        bp.out = (int8_t *)(ws + pl.toff[d.out]);
-                        bp.w1 = c1.w; bp.bias1 = c1.bias; bp.m0s1 = c1.m0s; bp.chi1 = c1.chi; bp.shm11 = c1.shm1;
-                        bp.w2 = c2.w; bp.bias2 = c2.bias; bp.m0s2 = c2.m0s; bp.chi2 = c2.chi; bp.shm12 = c2.shm1;
-                        bp.zpad = c1.zpad;
-                        bp.Cin_p = c1.Cin_p; bp.H = c1.H; bp.W = c1.W; bp.B = (int32_t)cnt; bp.tail = d.bneck == 2;
-                        bp.zp_t1 = c1.zp_out;
-                        bp.lo1 = c1.relu ? c1.zp_out : -128;
-                        bp.lo2 = c2.relu ? c2.zp_out : -128;
-                        bp.tie_free = c1.tie_free && c2.tie_free;
-                        if (bp.tail) {
-                            bp.w3 = c3.w; bp.bias3 = c3.bias; bp.m0s3 = c3.m0s; bp.chi3 = c3.chi; bp.shm13 = c3.shm1;
-                            bp.Cout_p = c3.Cout_p;
-                            bp.lo3 = c3.relu ? c3.zp_out : -128;
-                            bp.add_mul_self = c3.add_mul_self; bp.add_mul_res = c3.add_mul_res; bp.add_c0 = c3.add_c0;
-                            bp.add_k = c3.add_k; bp.add_sh = c3.add_sh; bp.add_lo = c3.add_lo;
-                            bp.tie_free = bp.tie_free && c3.tie_free && c3.add_tie_free;
-                        }
-                        HIP_TRY(launch_bottleneck(bp, m->stream));
-                        break;
-                    }
-                    ConvParams c = d.conv;
-                    c.in = (const int8_t *)(ws + pl.toff[d.a]);
-                    c.out = (int8_t *)(ws + pl.toff[d.out]);
-                    c.res = c.fuse_add == 1 ? (const int8_t *)(ws + pl.toff[d.b]) : nullptr;
-                    c.in2 = c.fuse_add == 2 ? (const int8_t *)(ws + pl.toff[d.b]) : nullptr;
-                    c.npix = (int32_t)(cnt * c.Ho * c.Wo);
-                    c.force_tile = m->conv_tile;
-                    HIP_TRY(launch_conv(c, m->stream));
-                    break; }
-                case OP_ADD: {
-                    AddParams a = d.add;
-                    const TensorDesc &t = pm.tensors[d.out];
-                    a.a = (const int8_t *)(ws + pl.toff[d.a]);
-                    a.b = (const int8_t *)(ws + pl.toff[d.b]);
-                    a.out = (int8_t *)(ws + pl.toff[d.out]);
-                    a.n16 = (int64_t)cnt * t.H * t.W * t.Cp / 16;
-                    HIP_TRY(launch_add(a, m->stream));
-                    break; }
-                case OP_MAXPOOL: {
-                    PoolParams p = d.pool;
-                    p.in = (const int8_t *)(ws + pl.toff[d.a]);
-                    p.out = (int8_t *)(ws + pl.toff[d.out]);
-                    p.B = (int32_t)cnt;
-                    HIP_TRY(launch_maxpool(p, m->stream));
-                    break; }
-                case OP_GAP: {
-                    GapParams g = d.gap;
-                    g.in = (const int8_t *)(ws + pl.toff[d.a]);
-                    g.out = (int8_t *)(ws + pl.toff[d.out]);
-                    g.B = (int32_t)cnt;
-                    HIP_TRY(launch_gap(g, m->stream));
-                    break; }
-                case OP_FC: {
-                    FcParams f = d.fc;
-                    f.in = (const int8_t *)(ws + pl.toff[d.a]);
-                    f.B = (int32_t)cnt;
-                    f.logits = logits_host ? (int32_t *)(ws + pl.logits_off) : nullptr;
-                    f.argmax = argmax_host ? (int32_t *)(ws + pl.argmax_off) : nullptr;
-                    f.counts = dcounts;
-                    if (bc) { f.n_per_item = bc->n_per_item; f.slot_begin = done; }
-                    HIP_TRY(launch_fc(f, m->stream));
-                    break; }
-                }
-                if (stop_tensor > 0 && d.out == stop_tensor) break;
+
+        // copies [j0, j0 + bn) of the chunk through the noise stage
+        auto run_noise = [&](uint32_t j0, uint32_t bn) -> int {
+            NoiseParams np;
+            np.x = x; np.table = table; np.out = (int8_t *)tptr(0, j0);
+            np.C = pm.C; np.H = pm.H; np.W = pm.W;
+            np.key0 = (uint32_t)seed; np.key1 = (uint32_t)(seed >> 32);
+            np.image = image; np.phase = phase; np.sample_begin = begin + (uint32_t)done + j0; np.count = bn;
+            np.items = nullptr; np.n_per_item = 0; np.item_first = 0; np.item_count = 0; np.slot_begin = 0;
+            if (bc) {
+                const uint64_t s0 = done + j0;
+                np.items = bc->items; np.n_per_item = bc->n_per_item; np.slot_begin = s0;
+                np.item_first = (uint32_t)(s0 / bc->n_per_item);
+                np.item_count = (uint32_t)((s0 + bn - 1) / bc->n_per_item) - np.item_first + 1;
             }
+            if ((prc = mark(KC_NOISE)) != ISR_OK) return prc;
+            ev_work.push_back({0.0, (double)bn * pm.H * pm.W * 4});
+            HIP_TRY(launch_noise(np, m->stream));
+            return ISR_OK;
+        };
+        // copies [j0, j0 + bn) of the chunk through one op of the plan
+        auto run_op = [&](const DevOp &d, uint32_t j0, uint32_t bn) -> int {
+            if ((prc = mark(d.kclass)) != ISR_OK) return prc;
+            ev_work.push_back({d.ops_per_sample * bn, d.bytes_per_sample * bn});
+            switch (d.type) {
+            case OP_CONV: {
+                if (d.stem_pool) {
+                    const TensorDesc &to = pm.tensors[d.out];
+                    StemPoolParams sp;
+                    sp.in = (const int8_t *)tptr(d.a, j0);
+                    sp.out = (int8_t *)tptr(d.out, j0);
+                    sp.w = d.conv.w; sp.bias = d.conv.bias; sp.m0s = d.conv.m0s; sp.chi = d.conv.chi; sp.shm1 = d.conv.shm1;
+                    sp.H = d.conv.H; sp.W = d.conv.W; sp.Ho = d.conv.Ho; sp.Wo = d.conv.Wo; sp.Hp = to.H; sp.Wp = to.W;
+                    sp.zp_in = d.conv.zp_in; sp.zp_out = d.conv.zp_out; sp.relu = d.conv.relu; sp.tie_free = d.conv.tie_free; sp.B = (int32_t)bn;
+                    HIP_TRY(launch_stem_pool(sp, m->stream));
+                    break;
+                }
+                if (d.stem16) {
+                    const ConvParams &c = d.conv;
+                    Stem16Params sp;
+                    sp.in = (const int8_t *)tptr(d.a, j0);
+                    sp.out = (int8_t *)tptr(d.out, j0);
+                    sp.w = c.w; sp.bias = c.bias; sp.m0s = c.m0s; sp.chi = c.chi; sp.shm1 = c.shm1;
+                    sp.H = c.H; sp.W = c.W; sp.B = (int32_t)bn; sp.zp_in = c.zp_in;
+                    sp.lo = c.relu ? c.zp_out : -128; sp.tie_free = c.tie_free;
+                    HIP_TRY(launch_stem16(sp, m->stream));
+                    break;
+                }
+                if (d.block) {
+                    BlockParams bp{};
+                    bp.in = (const int8_t *)tptr(d.a, j0);
+                    bp.out = (int8_t *)tptr(d.out, j0);
+                    bp.blocks = m->dblocks + d.chain_off;
+                    bp.nblocks = (int32_t)d.chain.size();
+                    bp.C = d.conv.Cout_p; bp.S = d.conv.H; bp.B = (int32_t)bn;
+                    bp.tie_free = d.conv.tie_free && d.conv2.tie_free && d.conv2.add_tie_free;
+                    HIP_TRY(launch_basic_block(bp, m->stream));
+                    break;
+                }
+                if (d.trans) {
+                    const ConvParams &c1 = d.conv, &c2 = d.conv2, &cp = d.conv3;
+                    TransParams tp{};
+                    tp.in = (const int8_t *)tptr(d.a, j0);
+                    tp.out = (int8_t *)tptr(d.out, j0);
+                    tp.w1 = c1.w; tp.bias1 = c1.bias; tp.m0s1 = c1.m0s; tp.chi1 = c1.chi; tp.shm11 = c1.shm1;
+                    tp.w2 = c2.w; tp.bias2 = c2.bias; tp.m0s2 = c2.m0s; tp.chi2 = c2.chi; tp.shm12 = c2.shm1;
+                    tp.wp = cp.w; tp.biasp = cp.bias; tp.m0sp = cp.m0s; tp.chip = cp.chi; tp.shm1p = cp.shm1;
+                    tp.C = c1.Cout_p; tp.S = c1.Ho; tp.B = (int32_t)bn;
+                    tp.zp_x = c1.zp_in; tp.zp_t = c1.zp_out;
+                    tp.lo1 = c1.relu ? c1.zp_out : -128;
+                    tp.lo2 = c2.relu ? c2.zp_out : -128;
+                    tp.lop = cp.relu ? cp.zp_out : -128;
+                    tp.add_mul_self = cp.add_mul_self; tp.add_mul_res = cp.add_mul_res; tp.add_c0 = cp.add_c0;
+                    tp.add_k = cp.add_k; tp.add_sh = cp.add_sh; tp.add_lo = cp.add_lo;
+                    tp.tie_free = c1.tie_free && c2.tie_free && cp.tie_free && cp.add_tie_free;
+                    HIP_TRY(launch_trans_block(tp, m->stream));
+                    break;
+                }
+                if (d.bneck) {
+                    const ConvParams &c1 = d.conv, &c2 = d.conv2, &c3 = d.conv3;
+                    BneckParams bp{};
+                    bp.in = (const int8_t *)tptr(d.a, j0);
+                    bp.out = (int8_t *)tptr(d.out, j0);
+                    bp.w1 = c1.w; bp.bias1 = c1.bias; bp.m0s1 = c1.m0s; bp.chi1 = c1.chi; bp.shm11 = c1.shm1;
+                    bp.w2 = c2.w; bp.bias2 = c2.bias; bp.m0s2 = c2.m0s; bp.chi2 = c2.chi; bp.shm12 = c2.shm1;
+                    bp.zpad = c1.zpad;
+                    bp.Cin_p = c1.Cin_p; bp.H = c1.H; bp.W = c1.W; bp.B = (int32_t)bn; bp.tail = d.bneck == 2;
+                    bp.zp_t1 = c1.zp_out;
+                    bp.lo1 = c1.relu ? c1.zp_out : -128;
+                    bp.lo2 = c2.relu ? c2.zp_out : -128;
+                    bp.tie_free = c1.tie_free && c2.tie_free;
+                    if (bp.tail) {
+                        bp.w3 = c3.w; bp.bias3 = c3.bias; bp.m0s3 = c3.m0s; bp.chi3 = c3.chi; bp.shm13 = c3.shm1;
+                        bp.Cout_p = c3.Cout_p;
+                        bp.lo3 = c3.relu ? c3.zp_out : -128;
+                        bp.add_mul_self = c3.add_mul_self; bp.add_mul_res = c3.add_mul_res; bp.add_c0 = c3.add_c0;
+                        bp.add_k = c3.add_k; bp.add_sh = c3.add_sh; bp.add_lo = c3.add_lo;
+                        bp.tie_free = bp.tie_free && c3.tie_free && c3.add_tie_free;
+                    }
+                    HIP_TRY(launch_bottleneck(bp, m->stream));
+                    break;
+                }
+                ConvParams c = d.conv;
+                c.in = (const int8_t *)tptr(d.a, j0);
+                c.out = (int8_t *)tptr(d.out, j0);
+                c.res = c.fuse_add == 1 ? (const int8_t *)tptr(d.b, j0) : nullptr;
+                c.in2 = c.fuse_add == 2 ? (const int8_t *)tptr(d.b, j0) : nullptr;
+                c.npix = (int32_t)(bn * c.Ho * c.Wo);
+                c.force_tile = m->conv_tile;
+                HIP_TRY(launch_conv(c, m->stream));
+                break; }
+            case OP_ADD: {
+                AddParams a = d.add;
+                const TensorDesc &t = pm.tensors[d.out];
+                a.a = (const int8_t *)tptr(d.a, j0);
+                a.b = (const int8_t *)tptr(d.b, j0);
+                a.out = (int8_t *)tptr(d.out, j0);
+                a.n16 = (int64_t)bn * t.H * t.W * t.Cp / 16;
+                HIP_TRY(launch_add(a, m->stream));
+                break; }
+            case OP_MAXPOOL: {
+                PoolParams p = d.pool;
+                p.in = (const int8_t *)tptr(d.a, j0);
+                p.out = (int8_t *)tptr(d.out, j0);
+                p.B = (int32_t)bn;
+                HIP_TRY(launch_maxpool(p, m->stream));
+                break; }
+            case OP_GAP: {
+                GapParams g = d.gap;
+                g.in = (const int8_t *)tptr(d.a, j0);
+                g.out = (int8_t *)tptr(d.out, j0);
+                g.B = (int32_t)bn;
+                HIP_TRY(launch_gap(g, m->stream));
+                break; }
+            case OP_FC: {
+                FcParams f = d.fc;
+                f.in = (const int8_t *)tptr(d.a, j0);
+                f.B = (int32_t)bn;
+                f.logits = logits_host ? (int32_t *)(ws + pl.logits_off) + (size_t)j0 * pm.classes : nullptr;
+                f.argmax = argmax_host ? (int32_t *)(ws + pl.argmax_off) + j0 : nullptr;
+                f.counts = dcounts;
+                if (bc) { f.n_per_item = bc->n_per_item; f.slot_begin = done + j0; }
+                HIP_TRY(launch_fc(f, m->stream));
+                break; }
+            }
+            return ISR_OK;
+        };
+
+        // The plan is walked in segments (plan.h): the ops of a segment run back to back on one
+        // sub-chunk of copies after the other, so that what an op writes is still in the caches
+        // when the next op of the segment reads it.  Segment 0 starts with the noise stage.
+        size_t nops = pl.ops.size();
+        if (stop_tensor == 0) nops = 0;
+        else if (stop_tensor > 0)
+            for (size_t i = 0; i < pl.ops.size(); ++i)
+                if (pl.ops[i].out == stop_tensor) { nops = i + 1; break; }
+        size_t op0 = 0;
+        bool noise_done = false;
+        for (size_t sg = 0; sg <= pl.segments.size() && (op0 < nops || !noise_done); ++sg) {
+            // ops [op0, op1) in sub-chunks of `sub` copies; past the last segment: the rest, whole chunk
+            size_t op1 = nops;
+            uint32_t sub = cnt;
+            if (sg < pl.segments.size()) {
+                op1 = std::min(nops, pl.segments[sg].end);
+                sub = std::max<uint32_t>(1, std::min(cnt, pl.segments[sg].sub));
+            }
+            if (op1 < op0) op1 = op0;
+            for (uint32_t j0 = 0; j0 < cnt; j0 += sub) {
+                const uint32_t bn = std::min(sub, cnt - j0);
+                if (!noise_done && (prc = run_noise(j0, bn)) != ISR_OK) return prc;
+                for (size_t i = op0; i < op1; ++i)
+                    if ((prc = run_op(pl.ops[i], j0, bn)) != ISR_OK) return prc;
+            }
+            noise_done = true;
+            op0 = op1;
         }
         if (timed) {
             if ((prc = mark(-1)) != ISR_OK) return prc;
@@ -439,22 +480,9 @@ int isr_noise_bank(uint32_t sigma, uint64_t seed, uint32_t bank_id, uint32_t fir
     if (sigma < 1 || sigma > 1024 || !out_device || d == 0 || (d & 3) != 0) return ISR_ERR_ARG;
     if ((uint64_t)first + count > (1ull << 32)) return ISR_ERR_ARG;
     if (count == 0) return ISR_OK;
-    const auto tab = cached_noise_table(sigma);
-    if (!tab) return ISR_ERR_ARG;
-    const std::vector<uint64_t> &T = tab->T;
-    const uint32_t R = tab->R;
-    const size_t n = T.size();
-    // device form: high words, low words, guide table (as 32-bit words so that one upload carries all)
-    const size_t guide_words = (NOISE_GUIDE_SIZE + 2) / 2;
-    std::vector<uint32_t> host(2 * n + guide_words, 0);
-    for (size_t j = 0; j < n; ++j) { host[j] = (uint32_t)(T[j] >> 32); host[n + j] = (uint32_t)T[j]; }
-    uint16_t *guide = (uint16_t *)(host.data() + 2 * n);
-    size_t j = 0;
-    for (uint32_t b = 0; b <= NOISE_GUIDE_SIZE; ++b) {
-        const uint64_t start = (uint64_t)b << (32 - NOISE_GUIDE_BITS);
-        while (j < n && (uint64_t)host[j] < start) ++j;
-        guide[b] = (uint16_t)j;
-    }
+    std::vector<uint32_t> host;
+    uint32_t n = 0, R = 0;
+    if (!build_bank_table(sigma, host, n, R)) return ISR_ERR_ARG;
     hipStream_t st = (hipStream_t)hip_stream;
     uint32_t *dev = nullptr;
     HIP_TRY(hipMalloc((void **)&dev, host.size() * 4));
@@ -533,6 +561,7 @@ size_t isr_workspace_bytes(const isr_model *m, uint32_t chunk_samples) {
     for (int i = 0; i < 2; ++i) {
         Plan pl;
         pl.ops = m->plan[i].ops;
+        if (i == 1) plan_segments(m->pm, chunk_samples, pl);
         plan_workspace(m->pm, chunk_samples, pl);
         need = std::max(need, pl.bytes);
     }
@@ -546,6 +575,7 @@ int isr_set_workspace(isr_model *m, void *workspace_device, size_t bytes, uint32
     for (const TensorDesc &t : m->pm.tensors)
         if ((uint64_t)chunk_samples * t.H * t.W * std::max(t.Cp, 16) >= (1ull << 31)) return ISR_ERR_ARG;
     if (bytes < isr_workspace_bytes(m, chunk_samples)) return ISR_ERR_WORKSPACE;
+    plan_segments(m->pm, chunk_samples, m->plan[1]);
     for (int i = 0; i < 2; ++i) plan_workspace(m->pm, chunk_samples, m->plan[i]);
     m->ws = (uint8_t *)workspace_device;
     m->ws_bytes = bytes;

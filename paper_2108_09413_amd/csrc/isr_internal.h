@@ -34,6 +34,10 @@ struct NoiseTable {
 };
 // Shared, immutable table of a sigma (built on first use); null for sigma outside 1..1024.
 std::shared_ptr<const NoiseTable> cached_noise_table(uint32_t sigma);
+// Table of the stored-noise generator as one block of 32-bit words: n high words, n low words, guide table.
+bool build_bank_table(uint32_t sigma, std::vector<uint32_t> &words, uint32_t &n_out, uint32_t &R_out);
+// Records the hipError_t that isr_last_device_error() reports on this thread.
+void set_last_device_error(int hip_error);
 bool build_device_table(uint32_t sigma, DeviceNoiseTable &out);
 
 // ---- parsed model (host) ---------------------------------------------------

@@ -93,6 +93,29 @@ bool build_device_table(uint32_t sigma, DeviceNoiseTable &out) {
     return true;
 }
 
+// Form read by the stored-noise generator, as 32-bit words so that one upload carries all:
+// n high words, n low words, then the guide table (NOISE_GUIDE_SIZE + 2 entries of 16 bits) on
+// the top bits of the high word over all n = 2R thresholds.
+bool build_bank_table(uint32_t sigma, std::vector<uint32_t> &words, uint32_t &n_out, uint32_t &R_out) {
+    const auto tab = cached_noise_table(sigma);
+    if (!tab) return false;
+    const std::vector<uint64_t> &T = tab->T;
+    const size_t n = T.size();
+    const size_t guide_words = (NOISE_GUIDE_SIZE + 2) / 2;
+    words.assign(2 * n + guide_words, 0);
+    for (size_t j = 0; j < n; ++j) { words[j] = (uint32_t)(T[j] >> 32); words[n + j] = (uint32_t)T[j]; }
+    uint16_t *guide = (uint16_t *)(words.data() + 2 * n);
+    size_t j = 0;
+    for (uint32_t b = 0; b <= NOISE_GUIDE_SIZE; ++b) {
+        const uint64_t start = (uint64_t)b << (32 - NOISE_GUIDE_BITS);
+        while (j < n && (uint64_t)words[j] < start) ++j;
+        guide[b] = (uint16_t)j;
+    }
+    n_out = (uint32_t)n;
+    R_out = tab->R;
+    return true;
+}
+
 }  // namespace isr
 
 extern "C" int isr_noise_table(uint32_t sigma, uint64_t *T_host, size_t cap, uint32_t *R_out) {

@@ -25,6 +25,27 @@ int mfma32_row_of_channel(int oc_local) {
 
 }  // namespace
 
+// Sub-chunk schedule of a plan for chunks of B copies.  ISR_SEGMENTS="end:sub,end:sub,..." (op index
+// after the segment's last op : copies per sub-chunk) overrides the built-in choice; for tuning.
+void plan_segments(const ParsedModel &pm, uint32_t B, Plan &pl) {
+    pl.segments.clear();
+    (void)pm; (void)B;
+    if (const char *env = std::getenv("ISR_SEGMENTS")) {
+        const char *p = env;
+        while (*p) {
+            char *q = nullptr;
+            const long end = std::strtol(p, &q, 10);
+            if (q == p || *q != ':') break;
+            p = q + 1;
+            const long sub = std::strtol(p, &q, 10);
+            if (q == p) break;
+            p = *q == ',' ? q + 1 : q;
+            if (end > 0 && sub > 0 && (pl.segments.empty() || (size_t)end > pl.segments.back().end))
+                pl.segments.push_back({(size_t)end, (uint32_t)sub});
+        }
+    }
+}
+
 // Offsets of every tensor for a chunk of B samples; buffers are reused once the
 // last op reading a tensor has been issued (stream order makes that safe).
 void plan_workspace(const ParsedModel &pm, uint32_t B, Plan &pl) {
@@ -70,11 +91,23 @@ void plan_workspace(const ParsedModel &pm, uint32_t B, Plan &pl) {
     pl.has.assign(nt, 0);
     pl.toff[0] = alloc(tbytes(0));
     pl.has[0] = 1;
-    for (int i = 0; i < (int)pl.ops.size(); ++i) {
-        const DevOp &o = pl.ops[i];
-        if (o.type != OP_FC) { pl.toff[o.out] = alloc(tbytes(o.out)); pl.has[o.out] = 1; }
-        for (int t : {o.a, o.b})
-            if (t >= 0 && last_use[t] == i && !(t == o.b && o.a == o.b)) release(pl.toff[t], tbytes(t));
+    // A segment runs its ops sub-chunk by sub-chunk, so every tensor it touches is live for the
+    // whole segment: outputs are placed when the segment starts, inputs released when it ends.
+    // An op outside the segments is a segment of its own.
+    size_t seg = 0;
+    for (int i = 0; i < (int)pl.ops.size();) {
+        while (seg < pl.segments.size() && pl.segments[seg].end <= (size_t)i) ++seg;
+        const int end = seg < pl.segments.size() ? (int)std::min(pl.segments[seg].end, pl.ops.size()) : i + 1;
+        for (int j = i; j < end; ++j) {
+            const DevOp &o = pl.ops[j];
+            if (o.type != OP_FC) { pl.toff[o.out] = alloc(tbytes(o.out)); pl.has[o.out] = 1; }
+        }
+        for (int j = i; j < end; ++j) {
+            const DevOp &o = pl.ops[j];
+            for (int t : {o.a, o.b})
+                if (t >= 0 && last_use[t] == j && !(t == o.b && o.a == o.b)) release(pl.toff[t], tbytes(t));
+        }
+        i = end;
     }
     pl.logits_off = round_up(top, 256);
     pl.argmax_off = pl.logits_off + round_up((size_t)B * pm.classes * 4, 256);

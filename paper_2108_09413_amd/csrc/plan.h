@@ -34,9 +34,17 @@ struct DevOp {
     FcParams fc{};
 };
 
+// A run of consecutive ops that is executed sub-chunk by sub-chunk: ops [previous end, end) of the
+// plan on `sub` copies at a time.  Ops after the last segment run on the whole chunk.
+struct Segment {
+    size_t end;
+    uint32_t sub;
+};
+
 // An executable op list plus where each tensor lives in the workspace.
 struct Plan {
     std::vector<DevOp> ops;
+    std::vector<Segment> segments;      // empty: every op runs on the whole chunk
     std::vector<size_t> toff;           // per tensor offset inside the workspace
     std::vector<char> has;              // tensor is produced by this plan
     size_t logits_off = 0, argmax_off = 0, bytes = 0;
@@ -55,6 +63,8 @@ int build_device_ops(const ParsedModel &pm, std::vector<DevOp> &ops, ConstArena 
 void rebase_device_ops(std::vector<DevOp> &ops, const uint8_t *base);
 // The op list with every fusion the kernels cover applied (from the rebased op-by-op list).
 void build_fused_plan(const ParsedModel &pm, const std::vector<DevOp> &plain, std::vector<DevOp> &fused);
+// Chooses the sub-chunk segments of a plan for chunks of B samples (before plan_workspace).
+void plan_segments(const ParsedModel &pm, uint32_t B, Plan &pl);
 // Offsets of every tensor of a chunk of B samples in the workspace.
 void plan_workspace(const ParsedModel &pm, uint32_t B, Plan &pl);
 
