@@ -154,6 +154,19 @@ int isr_predict_batch(isr_model *m, const uint8_t *x_device, uint32_t n_images, 
 int isr_noise_bank(uint32_t sigma, uint64_t seed, uint32_t bank_id, uint32_t first, uint32_t count, uint32_t d,
                    int16_t *out_device, void *hip_stream);
 
+/* isr_noise_bank for callers that cannot allocate device memory: code under HIP graph capture
+ * set-up, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same draws, same
+ * error behaviour as isr_noise_bank, but the sampler's table goes into a fixed array in device
+ * memory that is part of the library's code object (isr_noise_bank_static_capacity() bytes, 64 KiB:
+ * room for every sigma up to about 420; each GPU the library runs on holds its own copy for the
+ * life of the process) and the call performs no hipMalloc / hipFree.  ISR_ERR_WORKSPACE when the
+ * table of this sigma does not fit the array.  All calls on one GPU share that array: calls that
+ * overlap in time on one GPU, from any thread or stream, race -- serialise them.  A call leaves
+ * its table in the array; the next call overwrites it before its kernel runs. */
+int isr_noise_bank_static(uint32_t sigma, uint64_t seed, uint32_t bank_id, uint32_t first, uint32_t count,
+                          uint32_t d, int16_t *out_device, void *hip_stream);
+size_t isr_noise_bank_static_capacity(void);
+
 /* ---- parity / resume hooks (sample-index ranges are reproducible) -------- */
 
 /* Noisy copies for sample indices [sample_begin, sample_begin+count) of one

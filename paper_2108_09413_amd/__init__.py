@@ -24,6 +24,7 @@ EXPORTS = [
     "isr_debug_tensor", "isr_debug_tensor_source", "isr_noise_table", "isr_cp_lower", "isr_normal_quantile", "isr_binom_pvalue",
     "isr_decide_certify", "isr_decide_predict", "isr_discrete_quantile", "isr_set_fusion", "isr_set_conv_tile", "isr_profile", "isr_profile_read", "isr_strerror",
     "isr_last_device_error", "isr_certify_batch", "isr_predict_batch", "isr_certified_metrics", "isr_noise_bank",
+    "isr_noise_bank_static", "isr_noise_bank_static_capacity",
 ]
 
 
@@ -92,6 +93,9 @@ def lib():
         L.isr_predict_batch.argtypes = [vp, vp, u32, C.POINTER(Item), u32, u32, dbl, u64, C.POINTER(Result), vp]
         L.isr_certified_metrics.argtypes = [C.POINTER(Result), vp, u32, vp, u32, C.POINTER(dbl), vp]
         L.isr_noise_bank.argtypes = [u32, u64, u32, u32, u32, u32, vp, vp]
+        L.isr_noise_bank_static.argtypes = [u32, u64, u32, u32, u32, u32, vp, vp]
+        L.isr_noise_bank_static_capacity.argtypes = []
+        L.isr_noise_bank_static_capacity.restype = sz
         L.isr_set_fusion.argtypes = [vp, C.c_int]
         L.isr_set_conv_tile.argtypes = [vp, C.c_int]
         L.isr_profile.argtypes = [vp, u32]
@@ -100,7 +104,7 @@ def lib():
         L.isr_strerror.restype = C.c_char_p
         L.isr_last_device_error.argtypes = []
         for name in EXPORTS:
-            if name not in ("isr_workspace_bytes", "isr_strerror"):
+            if name not in ("isr_workspace_bytes", "isr_strerror", "isr_noise_bank_static_capacity"):
                 getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -282,6 +286,17 @@ def isr_noise_bank(sigma: int, seed: int, bank_id: int, first: int, count: int, 
     st = torch.cuda.current_stream()
     _check(lib().isr_noise_bank(sigma, C.c_uint64(seed), bank_id, first, count, d, C.c_void_p(out.data_ptr()),
                                 C.c_void_p(st.cuda_stream)), "isr_noise_bank")
+    return out
+
+
+def isr_noise_bank_static(sigma: int, seed: int, bank_id: int, first: int, count: int, d: int, out):
+    """isr_noise_bank into a caller-provided int16 [count][d] device tensor with no device allocation
+    inside the library (the table goes into the library's fixed device array)."""
+    import torch
+    assert out.dtype == torch.int16 and out.is_cuda and out.is_contiguous() and out.numel() == count * d
+    st = torch.cuda.current_stream()
+    _check(lib().isr_noise_bank_static(sigma, C.c_uint64(seed), bank_id, first, count, d, C.c_void_p(out.data_ptr()),
+                                       C.c_void_p(st.cuda_stream)), "isr_noise_bank_static")
     return out
 
 
