@@ -249,14 +249,18 @@ int isr_set_fusion(isr_model *m, int enable);
  * direct-to-LDS convolution kernel for layers with more than 64 stored output
  * channels.  0 (the default) lets the library choose per launch; 1..4 force
  * 128x128, 128x256, 256x128, 256x256 (channels x pixels; the 256-channel tiles
- * only where a layer has more than 128 channels).  Results are identical for
- * every choice.  ISR_ERR_ARG for other values. */
+ * only where a layer has more than 128 channels); 5 forces 256x256 computed by
+ * four waves of 128x128 each instead of sixteen of 64x64.  Results are identical
+ * for every choice.  ISR_ERR_ARG for other values. */
 int isr_set_conv_tile(isr_model *m, int tile);
 
 /* ---- per-kernel timing (HIP events on the model's stream) ------------------ */
 
 typedef struct isr_kernel_stat {
-    char name[32];        /* "noise", "conv_m16/32/64/128", "add", "maxpool", "gap", "fc_vote" */
+    char name[80];        /* kernel instance as a profiler prints it, template arguments included:
+                             "conv_dma_kernel<BM, BN, KB, stages, fused add, min blocks, wave tile>",
+                             "bottleneck_kernel<tail, tie-free>", "stem_pool_kernel", "noise_kernel", ... */
+    int32_t is_conv;      /* 1: the kernel executes convolution ops of the model (S3/S4 of the path) */
     uint64_t launches;    /* launches timed so far */
     double total_ms;      /* sum of their durations */
     double alg_ops;       /* algorithmic integer ops of those launches (2 per multiply-accumulate,
@@ -265,7 +269,7 @@ typedef struct isr_kernel_stat {
 } isr_kernel_stat;
 
 /* every_chunks > 0: bracket every kernel launch of each every_chunks-th chunk
- * with HIP events and accumulate per kernel class (the chunk is followed by a
+ * with HIP events and accumulate per kernel instance (the chunk is followed by a
  * stream synchronisation); 0 switches timing off.  Either call resets the
  * accumulators. */
 int isr_profile(isr_model *m, uint32_t every_chunks);

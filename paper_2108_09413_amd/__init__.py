@@ -53,7 +53,7 @@ class Item(C.Structure):
 
 
 class KernelStat(C.Structure):
-    _fields_ = [("name", C.c_char * 32), ("launches", C.c_uint64), ("total_ms", C.c_double),
+    _fields_ = [("name", C.c_char * 80), ("is_conv", C.c_int32), ("launches", C.c_uint64), ("total_ms", C.c_double),
                 ("alg_ops", C.c_double), ("alg_bytes", C.c_double)]
 
 
@@ -384,9 +384,10 @@ def isr_profile(model: Model, every_chunks: int):
 
 
 def isr_profile_read(model: Model):
-    """List of dicts: name, launches, total_ms, alg_ops, alg_bytes per kernel class."""
-    arr = (KernelStat * 16)()
+    """List of dicts: name, is_conv, launches, total_ms, alg_ops, alg_bytes per kernel instance."""
+    arr = (KernelStat * 64)()
     n = C.c_uint32(0)
-    _check(lib().isr_profile_read(model.handle, arr, 16, C.byref(n)), "isr_profile_read")
-    return [dict(name=arr[i].name.decode(), launches=int(arr[i].launches), total_ms=arr[i].total_ms,
-                 alg_ops=arr[i].alg_ops, alg_bytes=arr[i].alg_bytes) for i in range(min(n.value, 16))]
+    _check(lib().isr_profile_read(model.handle, arr, 64, C.byref(n)), "isr_profile_read")
+    return [dict(name=arr[i].name.decode(), is_conv=bool(arr[i].is_conv), launches=int(arr[i].launches),
+                 total_ms=arr[i].total_ms, alg_ops=arr[i].alg_ops, alg_bytes=arr[i].alg_bytes)
+            for i in range(min(n.value, 64))]

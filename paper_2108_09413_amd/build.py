@@ -9,20 +9,25 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libisr.so")
-SOURCES = ["api.cpp", "plan.cpp", "model_parse.cpp", "noise_table.cpp", "host_stats.cpp", "kernels.hip", "conv_igemm.hip", "stem_pool.hip", "basic_block.hip", "bottleneck.hip", "stem16.hip", "trans_block.hip", "noise_bank_static.hip"]
+SOURCES = ["api.cpp", "plan.cpp", "model_parse.cpp", "noise_table.cpp", "host_stats.cpp", "kernels.hip", "conv_igemm.hip", "stem_pool.hip", "basic_block.hip", "bottleneck.hip", "stem16.hip", "trans_block.hip", "noise_bank_static.hip", "conv_deep.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 # kernels: gfx950 only; packed-FP32 instruction selection is switched off; MFMA results go to
 # ordinary VGPRs (no accumulator-register copies in front of the epilogue arithmetic)
 HIP_FLAGS = ["--offload-arch=gfx950", "-x", "hip", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-             "-mllvm", "-amdgpu-mfma-vgpr-form=1", "-Wno-unknown-attributes"]
+             "-Wno-unknown-attributes"]
+VGPR_FORM = ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]
+# kernels whose accumulators exceed the ordinary VGPRs keep the default (accumulation registers)
+ACC_REGISTER_SOURCES = {"conv_deep.hip"}
 # host-only sources: plain C++ against the HIP runtime headers
 HOST_FLAGS = ["-x", "c++", "-D__HIP_PLATFORM_AMD__", "-I", "/opt/rocm/include"]
 
 
 def _compile(src: str) -> str:
     obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
-    flags = HIP_FLAGS if src.endswith(".hip") else HOST_FLAGS
+    flags = HOST_FLAGS
+    if src.endswith(".hip"):
+        flags = HIP_FLAGS + ([] if src in ACC_REGISTER_SOURCES else VGPR_FORM)
     proc = subprocess.run([HIPCC, *COMMON, *flags, "-c", os.path.join(CSRC, src), "-o", obj],
                           stderr=subprocess.PIPE, text=True)
     noise = "is not a recognized feature for this target"

@@ -6,6 +6,7 @@
 #include <cstring>
 #include <map>
 #include <new>
+#include <string>
 
 #include "isr_internal.h"
 #include "plan.h"
@@ -30,6 +31,10 @@ constexpr int TABLE_SLOTS = 8;
 }  // namespace
 
 void isr::set_last_device_error(int hip_error) { g_last_hip_error = hip_error; }
+
+namespace { thread_local const char *g_kernel_name = ""; }
+void isr::set_kernel_name(const char *name) { g_kernel_name = name; }
+const char *isr::last_kernel_name() { return g_kernel_name; }
 
 struct isr_model {
     ParsedModel pm;
@@ -58,7 +63,7 @@ struct isr_model {
     uint32_t profile_every = 0;
     uint64_t chunk_counter = 0;
     std::vector<hipEvent_t> events;
-    isr_kernel_stat stats[KC_COUNT] = {};
+    std::map<std::string, isr_kernel_stat> stats;   // per kernel instance (name as a profiler prints it)
 };
 
 namespace {
@@ -107,8 +112,7 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
         if (bc) cnt = (uint32_t)std::min<uint64_t>(cnt, (uint64_t)bc->n_per_item * 65534);   // one grid row per item
         const bool timed = m->profile_every && (m->chunk_counter++ % m->profile_every) == 0;
         size_t ev = 0;
-        std::vector<int> ev_class;
-        auto mark = [&](int kclass) -> int {   // event before a launch (kclass >= 0) / after the last one
+        auto mark = [&]() -> int {   // event before a launch / after the last one
             if (!timed) return ISR_OK;
             if (ev == m->events.size()) {
                 hipEvent_t e;
@@ -116,10 +120,10 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
                 m->events.push_back(e);
             }
             HIP_TRY(hipEventRecord(m->events[ev++], m->stream));
-            if (kclass >= 0) ev_class.push_back(kclass);
             return ISR_OK;
         };
-        std::vector<std::pair<double, double>> ev_work;   // (ops, bytes) per timed launch
+        struct Work { const char *kernel; int conv; double ops, bytes; };
+        std::vector<Work> ev_work;   // per timed launch: the kernel instance and its algorithmic work
         int prc;
 
         // copies [j0, j0 + bn) of the chunk through the noise stage
@@ -136,15 +140,15 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
                 np.item_first = (uint32_t)(s0 / bc->n_per_item);
                 np.item_count = (uint32_t)((s0 + bn - 1) / bc->n_per_item) - np.item_first + 1;
             }
-            if ((prc = mark(KC_NOISE)) != ISR_OK) return prc;
-            ev_work.push_back({0.0, (double)bn * pm.H * pm.W * 4});
+            if ((prc = mark()) != ISR_OK) return prc;
             HIP_TRY(launch_noise(np, m->stream));
+            ev_work.push_back({last_kernel_name(), 0, 0.0, (double)bn * pm.H * pm.W * 4});
             return ISR_OK;
         };
         // copies [j0, j0 + bn) of the chunk through one op of the plan
         auto run_op = [&](const DevOp &d, uint32_t j0, uint32_t bn) -> int {
-            if ((prc = mark(d.kclass)) != ISR_OK) return prc;
-            ev_work.push_back({d.ops_per_sample * bn, d.bytes_per_sample * bn});
+            if ((prc = mark()) != ISR_OK) return prc;
+            set_kernel_name("");
             switch (d.type) {
             case OP_CONV: {
                 if (d.stem_pool) {
@@ -266,6 +270,7 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
                 HIP_TRY(launch_fc(f, m->stream));
                 break; }
             }
+            ev_work.push_back({last_kernel_name(), d.type == OP_CONV ? 1 : 0, d.ops_per_sample * bn, d.bytes_per_sample * bn});
             return ISR_OK;
         };
 
@@ -298,16 +303,20 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
             op0 = op1;
         }
         if (timed) {
-            if ((prc = mark(-1)) != ISR_OK) return prc;
+            if ((prc = mark()) != ISR_OK) return prc;
             HIP_TRY(hipStreamSynchronize(m->stream));
-            for (size_t i = 0; i + 1 < ev; ++i) {
+            for (size_t i = 0; i + 1 < ev && i < ev_work.size(); ++i) {
                 float ms = 0.f;
                 HIP_TRY(hipEventElapsedTime(&ms, m->events[i], m->events[i + 1]));
-                isr_kernel_stat &st = m->stats[ev_class[i]];
+                isr_kernel_stat &st = m->stats[ev_work[i].kernel];
+                if (st.launches == 0) {
+                    std::strncpy(st.name, ev_work[i].kernel, sizeof(st.name) - 1);
+                    st.is_conv = ev_work[i].conv;
+                }
                 st.launches += 1;
                 st.total_ms += ms;
-                st.alg_ops += ev_work[i].first;
-                st.alg_bytes += ev_work[i].second;
+                st.alg_ops += ev_work[i].ops;
+                st.alg_bytes += ev_work[i].bytes;
             }
         }
         if (logits_host) {
@@ -501,7 +510,7 @@ int isr_noise_bank(uint32_t sigma, uint64_t seed, uint32_t bank_id, uint32_t fir
 }
 
 int isr_set_conv_tile(isr_model *m, int tile) {
-    if (!m || tile < 0 || tile > 4) return ISR_ERR_ARG;
+    if (!m || tile < 0 || tile > 6) return ISR_ERR_ARG;
     m->conv_tile = tile;
     return ISR_OK;
 }
@@ -510,21 +519,17 @@ int isr_profile(isr_model *m, uint32_t every_chunks) {
     if (!m) return ISR_ERR_ARG;
     m->profile_every = every_chunks;
     m->chunk_counter = 0;
-    for (int i = 0; i < KC_COUNT; ++i) {
-        m->stats[i] = isr_kernel_stat{};
-        std::strncpy(m->stats[i].name, KC_NAMES[i], sizeof(m->stats[i].name) - 1);
-    }
+    m->stats.clear();
     return ISR_OK;
 }
 
 int isr_profile_read(const isr_model *m, isr_kernel_stat *out_host, uint32_t cap, uint32_t *n_out) {
     if (!m || !n_out || (cap && !out_host)) return ISR_ERR_ARG;
     uint32_t n = 0;
-    for (int i = 0; i < KC_COUNT; ++i)
-        if (m->stats[i].launches) {
-            if (n < cap) out_host[n] = m->stats[i];
-            ++n;
-        }
+    for (const auto &kv : m->stats) {
+        if (n < cap) out_host[n] = kv.second;
+        ++n;
+    }
     *n_out = n;
     return ISR_OK;
 }

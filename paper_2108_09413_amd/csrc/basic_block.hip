@@ -13,6 +13,8 @@
 // block overwrites x in LDS in place -- a lane reads the residual at its own pixel and writes
 // the sum there, the second convolution itself reads only t -- so a run of identity blocks
 // reads its input from HBM once and writes once.
+#include <string>
+
 #include "conv_device.h"
 
 namespace isr {
@@ -211,6 +213,8 @@ __global__ __launch_bounds__(256) void basic_block_kernel(const BlockParams p) {
 template <int C, int S, int NI>
 hipError_t launch_shape(const BlockParams &p, hipStream_t st) {
     const unsigned blocks = (unsigned)((p.B + NI - 1) / NI);
+    static const std::string name = "basic_block_kernel<" + std::to_string(C) + ", " + std::to_string(S) + ", " + std::to_string(NI) + ">";
+    set_kernel_name(name.c_str());
     if (p.tie_free) hipLaunchKernelGGL((basic_block_kernel<C, S, NI, true>), dim3(blocks), dim3(256), 0, st, p);
     else hipLaunchKernelGGL((basic_block_kernel<C, S, NI, false>), dim3(blocks), dim3(256), 0, st, p);
     return hipGetLastError();

@@ -323,6 +323,8 @@ hipError_t launch_bottleneck(const BneckParams &p, hipStream_t st) {
     const long tiles = (long)p.B * ((p.H + BT - 1) / BT) * ((p.W + BT - 1) / BT);
     if (tiles > 0x7fffffffL || (long)p.B * p.H * p.W * (p.Cin_p > 64 ? p.Cin_p : 64) >= (1L << 31)) return hipErrorInvalidValue;
     const dim3 grid((unsigned)tiles), block(256);
+    set_kernel_name(p.tail ? (p.tie_free ? "bottleneck_kernel<true, true>" : "bottleneck_kernel<true, false>")
+                           : (p.tie_free ? "bottleneck_kernel<false, true>" : "bottleneck_kernel<false, false>"));
     if (p.tail) {
         if (p.tie_free) hipLaunchKernelGGL((bottleneck_kernel<true, true>), grid, block, 0, st, p);
         else hipLaunchKernelGGL((bottleneck_kernel<true, false>), grid, block, 0, st, p);

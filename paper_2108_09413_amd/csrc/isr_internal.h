@@ -102,7 +102,7 @@ struct ConvParams {
     const int8_t *zpad;      // 16 bytes of z_in: source of out-of-image taps for loads that go straight to LDS
     int32_t H, W, Cin_p, Ho, Wo, Cout_p;
     int32_t k, stride, pad, Kp, Mp;   // k: kernel size (k x k taps)
-    int32_t force_tile;      // 0: the launcher picks the output tile; 1..4: 128x128, 128x256, 256x128, 256x256
+    int32_t force_tile;      // 0: the launcher picks the output tile; 1..5: 128x128, 128x256, 256x128, 256x256, 256x256 with 128x128 per wave
     int32_t kb;              // K bytes per step of the kernel (64 or 128); Kp is a multiple of it
     int32_t zp_in, zp_out, relu;
     int32_t npix;            // B * Ho * Wo
@@ -250,10 +250,16 @@ struct NoiseBankParams {
     uint32_t key0, key1, bank, first, count;
 };
 
+// Name of the kernel instance the last launcher call on this thread enqueued (template arguments
+// included, as a profiler prints them); the per-kernel timing report is keyed by it.
+void set_kernel_name(const char *name);
+const char *last_kernel_name();
+
 // Kernel launchers (kernels.hip / conv_igemm.hip).  All asynchronous on `st`.
 hipError_t launch_noise_bank(const NoiseBankParams &p, hipStream_t st);
 hipError_t launch_noise(const NoiseParams &p, hipStream_t st);
 hipError_t launch_conv(const ConvParams &p, hipStream_t st);
+hipError_t launch_conv_deep(const ConvParams &p, hipStream_t st);   // 256 x 256 tiles, 128 x 128 per wave (conv_deep.hip)
 hipError_t launch_stem_pool(const StemPoolParams &p, hipStream_t st);
 bool stem_pool_supported(int k, int stride, int pad, int cout_p, int H, int W, int fast_requant, int pool_k,
                          int pool_stride, int pool_pad);

@@ -141,6 +141,7 @@ hipError_t launch_noise(const NoiseParams &p, hipStream_t st) {
     long blocks = (total + 255) / 256;
     const long cap = rows >= 4 ? 256 : 256 * 4;   // the table is staged into LDS once per workgroup
     if (blocks > cap) blocks = cap;
+    set_kernel_name("noise_kernel");
     hipLaunchKernelGGL(noise_kernel, dim3((unsigned)blocks, rows), dim3(256), 0, st, p);
     return hipGetLastError();
 }
@@ -210,6 +211,7 @@ hipError_t launch_noise_bank(const NoiseBankParams &p, hipStream_t st) {
     const size_t lds = ((size_t)p.n + 2) * 4;   // at most 128 KiB plus the 8 KiB guide: within the 160 KiB of a CU (sigma 1024 needs 72 KiB)
     hipError_t e = hipFuncSetAttribute((const void *)noise_bank_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
+    set_kernel_name("noise_bank_kernel");
     hipLaunchKernelGGL(noise_bank_kernel, dim3((unsigned)blocks), dim3(256), lds, st, p);
     return hipGetLastError();
 }
@@ -250,6 +252,7 @@ hipError_t launch_add(const AddParams &p, hipStream_t st) {
     if (p.n16 <= 0) return hipSuccess;
     long blocks = (p.n16 + 255) / 256;
     if (blocks > 256 * 32) blocks = 256 * 32;
+    set_kernel_name("add_kernel");
     hipLaunchKernelGGL(add_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p);
     return hipGetLastError();
 }
@@ -298,6 +301,7 @@ hipError_t launch_maxpool(const PoolParams &p, hipStream_t st) {
     if (total <= 0) return hipSuccess;
     long blocks = (total + 255) / 256;
     if (blocks > 256 * 32) blocks = 256 * 32;
+    set_kernel_name("maxpool_kernel");
     hipLaunchKernelGGL(maxpool_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p);
     return hipGetLastError();
 }
@@ -336,6 +340,7 @@ hipError_t launch_gap(const GapParams &p, hipStream_t st) {
     if (total <= 0) return hipSuccess;
     long blocks = (total + 255) / 256;
     if (blocks > 256 * 32) blocks = 256 * 32;
+    set_kernel_name("gap_kernel");
     hipLaunchKernelGGL(gap_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p);
     return hipGetLastError();
 }
@@ -445,11 +450,13 @@ hipError_t launch_fc(const FcParams &p, hipStream_t st) {
     if (p.Kp % 1024 == 0) {
         long blocks = p.B;
         if (blocks > 256 * 16) blocks = 256 * 16;
+        set_kernel_name("fc_vote_ksplit_kernel");
         hipLaunchKernelGGL(fc_vote_ksplit_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p);
         return hipGetLastError();
     }
     long blocks = ((long)p.B + 3) / 4;
     if (blocks > 256 * 8) blocks = 256 * 8;
+    set_kernel_name("fc_vote_kernel");
     hipLaunchKernelGGL(fc_vote_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p);
     return hipGetLastError();
 }

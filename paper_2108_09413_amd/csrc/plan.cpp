@@ -8,9 +8,6 @@
 
 namespace isr {
 
-const char *const KC_NAMES[KC_COUNT] = {"noise", "conv_m16", "conv_m32", "conv_m64", "conv_m128",
-                                        "add", "maxpool", "gap", "fc_vote"};
-
 namespace {
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -447,8 +444,6 @@ int build_device_ops(const ParsedModel &pm, std::vector<DevOp> &ops, ConstArena 
             c.H = ti.H; c.W = ti.W; c.Cin_p = cin_p; c.Ho = to.H; c.Wo = to.W; c.Cout_p = cout_p;
             c.k = k; c.stride = o.stride; c.pad = o.pad; c.Kp = Kp; c.Mp = Mp; c.kb = kb;
             c.zp_in = ti.zp; c.zp_out = to.zp; c.relu = o.relu; c.c4 = c4 ? 1 : 0;
-            int tm = conv_tile_m(cout_p);
-            d.kclass = tm == 16 ? KC_CONV16 : tm == 32 ? KC_CONV32 : tm == 64 ? KC_CONV64 : KC_CONV128;
             d.ops_per_sample = 2.0 * to.C * to.H * to.W * ti.C * k * k;
             d.bytes_per_sample = (double)ti.C * ti.H * ti.W + (double)to.C * to.H * to.W;
             break; }
@@ -456,21 +451,18 @@ int build_device_ops(const ParsedModel &pm, std::vector<DevOp> &ops, ConstArena 
             AddParams &a = d.add;
             a.za = pm.tensors[o.a].zp; a.zb = pm.tensors[o.b].zp; a.zo = pm.tensors[o.out].zp;
             a.Ma = o.Ma; a.Mb = o.Mb; a.sh = o.sh; a.relu = o.relu;
-            d.kclass = KC_ADD;
             d.bytes_per_sample = 3.0 * pm.tensors[o.out].C * pm.tensors[o.out].H * pm.tensors[o.out].W;
             break; }
         case OP_MAXPOOL: {
             const TensorDesc &ti = pm.tensors[o.a], &to = pm.tensors[o.out];
             PoolParams &p = d.pool;
             p.H = ti.H; p.W = ti.W; p.Cp = ti.Cp; p.Ho = to.H; p.Wo = to.W; p.k = o.k; p.stride = o.stride; p.pad = o.pad;
-            d.kclass = KC_POOL;
             d.bytes_per_sample = (double)ti.C * ti.H * ti.W + (double)to.C * to.H * to.W;
             break; }
         case OP_GAP: {
             const TensorDesc &ti = pm.tensors[o.a], &to = pm.tensors[o.out];
             GapParams &g = d.gap;
             g.HW = ti.H * ti.W; g.Cp = ti.Cp; g.zp_in = ti.zp; g.zp_out = to.zp; g.M0 = o.Ma; g.sh = o.sh;
-            d.kclass = KC_GAP;
             d.bytes_per_sample = (double)ti.C * ti.H * ti.W + (double)to.C;
             break; }
         case OP_FC: {
@@ -495,7 +487,6 @@ int build_device_ops(const ParsedModel &pm, std::vector<DevOp> &ops, ConstArena 
             f.w = (const int8_t *)arena.put(w.data(), w.size());
             f.bias = (const int32_t *)arena.put(bias.data(), bias.size() * 4);
             f.Kp = Kp; f.classes = classes; f.classes_p = classes_p;
-            d.kclass = KC_FC;
             d.ops_per_sample = 2.0 * classes * ti.C * hw;
             d.bytes_per_sample = (double)ti.C * hw;
             break; }

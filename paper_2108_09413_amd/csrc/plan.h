@@ -10,13 +10,9 @@
 
 namespace isr {
 
-enum KernelClass { KC_NOISE, KC_CONV16, KC_CONV32, KC_CONV64, KC_CONV128, KC_ADD, KC_POOL, KC_GAP, KC_FC, KC_COUNT };
-extern const char *const KC_NAMES[KC_COUNT];
-
 struct DevOp {
     OpType type;
     int a = -1, b = -1, out = -1;
-    int kclass = 0;
     double ops_per_sample = 0.0, bytes_per_sample = 0.0;   // algorithmic, for the timing report
     ConvParams conv{};
     int stem_pool = 0;                  // conv fused with the max pooling after it (out = the pooled tensor)

@@ -80,6 +80,7 @@ bool stem16_supported(int k, int stride, int pad, int cout_p, int H, int W, int 
 hipError_t launch_stem16(const Stem16Params &p, hipStream_t st) {
     if (p.B <= 0) return hipSuccess;
     if (!p.in || !p.out || !p.w || !stem16_supported(3, 1, 1, 16, p.H, p.W, 1)) return hipErrorInvalidValue;
+    set_kernel_name("stem16_kernel");
     hipLaunchKernelGGL(stem16_kernel, dim3((unsigned)((p.B + 3) / 4)), dim3(256), 0, st, p);
     return hipGetLastError();
 }

@@ -165,6 +165,7 @@ hipError_t launch_stem_pool(const StemPoolParams &p, hipStream_t st) {
     if ((4 * P + 7) * (p.W + 8) * 4 > SP_IN_BYTES) return hipErrorInvalidValue;
     const long blocks = (long)p.B * ((p.Hp + P - 1) / P);
     if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+    set_kernel_name("stem_pool_kernel");
     hipLaunchKernelGGL(stem_pool_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p);
     return hipGetLastError();
 }

@@ -9,6 +9,8 @@
 // LDS read at a tap-shifted address; t, u and r never leave the CU.  Weight fragments come
 // from global memory (L2-resident) into registers once per convolution.
 // (C, S) = (32, 16) and (64, 8); v_mfma_i32_32x32x32_i8 throughout.
+#include <string>
+
 #include "conv_device.h"
 
 namespace isr {
@@ -155,6 +157,8 @@ __global__ __launch_bounds__(256, C == 32 ? 3 : 2) void trans_block_kernel(const
 template <int C, int S, int NI>
 hipError_t launch_shape(const TransParams &p, hipStream_t st) {
     const unsigned blocks = (unsigned)((p.B + NI - 1) / NI);
+    static const std::string name = "trans_block_kernel<" + std::to_string(C) + ", " + std::to_string(S) + ", " + std::to_string(NI) + ">";
+    set_kernel_name(name.c_str());
     if (p.tie_free) hipLaunchKernelGGL((trans_block_kernel<C, S, NI, true>), dim3(blocks), dim3(256), 0, st, p);
     else hipLaunchKernelGGL((trans_block_kernel<C, S, NI, false>), dim3(blocks), dim3(256), 0, st, p);
     return hipGetLastError();

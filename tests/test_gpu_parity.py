@@ -593,7 +593,7 @@ def test_resnet50_in_the_benchmarked_launch_configuration(isr):
     olg, oam = _oracle_at(om, x, 128, 0, 2, 1, [20000 + i for i in picks])
     for j, i in enumerate(picks):
         assert np.array_equal(lg[i], olg[j]) and am[i] == oam[j], i
-    for tile in (1, 2, 3, 4):
+    for tile in (1, 2, 3, 4, 5, 6):
         _say(f"  forced tile {tile}")
         isr.isr_set_conv_tile(m, tile)
         lg2, am2, cnt2 = isr.isr_debug_forward(m, x, 128, 0, 2, 1, 20000, 668)
@@ -625,7 +625,7 @@ def test_cifar_nets_in_the_benchmarked_launch_configuration(isr, cfg, chunk):
     m.close()
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5, 6])
 def test_every_conv_tile_against_the_oracle(isr, tile):
     """Layers deep enough for 128-byte K steps and for every output tile of the
     direct-to-LDS kernel, channel counts that leave a ragged last M tile, a ragged
