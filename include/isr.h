@@ -234,15 +234,16 @@ int isr_decide_predict(const uint32_t *counts, uint32_t classes, double alpha, i
 int isr_certified_metrics(const isr_result *results, const int32_t *labels, uint32_t count, const double *radii,
                           uint32_t n_radii, double *cp_out, double *ca_out);
 
-/* Kernel-variant switch for parity checks: enable != 0 (the default) lets the
- * library fuse ops of the blob into one kernel where it can (a residual add into
- * the convolution before it; the first convolution with the max pooling after
+/* Kernel-variant switch for parity checks: enable = 1 (the default) lets the
+ * library fuse ops of the blob into one kernel where that is faster (a residual add
+ * into the convolution before it; the first convolution with the max pooling after
  * it; a 1x1 convolution that only feeds a residual add into that add's kernel;
  * whole residual blocks of the narrow nets; the convolutions of a bottleneck block
- * with 64 middle channels);
- * 0 runs every op of the blob as its own kernel.  Results are identical either
- * way; tensors that a fused kernel never stores are served by the unfused plan
- * in isr_debug_tensor. */
+ * with 64 middle channels); 2 also folds identity bottleneck blocks with 128 middle
+ * channels into one kernel (correct, at present slower than their three kernels);
+ * 0 runs every op of the blob as its own kernel.  Results are identical in every
+ * mode; tensors that a fused kernel never stores are served by the unfused plan
+ * in isr_debug_tensor.  ISR_ERR_ARG for other values. */
 int isr_set_fusion(isr_model *m, int enable);
 
 /* Kernel-variant switch for parity checks and tuning: output tile of the

@@ -371,8 +371,9 @@ def isr_debug_tensor_source(model: Model, tensor_id: int) -> bool:
     return bool(out.value)
 
 
-def isr_set_fusion(model: Model, enable: bool):
-    _check(lib().isr_set_fusion(model.handle, 1 if enable else 0), "isr_set_fusion")
+def isr_set_fusion(model: Model, enable):
+    """False / 0: one kernel per op; True / 1: the default fusions; 2: every fusion the kernels cover."""
+    _check(lib().isr_set_fusion(model.handle, int(enable)), "isr_set_fusion")
 
 
 def isr_set_conv_tile(model: Model, tile: int):

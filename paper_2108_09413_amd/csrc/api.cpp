@@ -39,7 +39,7 @@ const char *isr::last_kernel_name() { return g_kernel_name; }
 struct isr_model {
     ParsedModel pm;
     std::vector<DevOp> ops;             // one descriptor per op of the blob
-    Plan plan[2];                       // [0] op by op, [1] with every fusion the kernels cover
+    Plan plan[3];                       // [0] op by op, [1] with the fusions that pay, [2] with every fusion the kernels cover
     int use_fused = 1;
     int conv_tile = 0;                  // forced conv output tile (0 = automatic)
     uint8_t *dconst = nullptr;          // weights and per-channel tables
@@ -49,7 +49,7 @@ struct isr_model {
     int table_next = 0;
     uint32_t *dcounts = nullptr;        // 2 * classes
     uint32_t *hcounts = nullptr;        // pinned, 2 * classes
-    BlockDesc *dblocks = nullptr;       // descriptors of the identity-block chains of plan[1]
+    BlockDesc *dblocks = nullptr;       // descriptors of the identity-block chains of plan[1] and plan[2]
     // batched calls: item descriptors and per-item vote counters, grown on demand
     NoiseItem *ditems = nullptr, *hitems = nullptr;
     uint32_t *dcounts_b = nullptr, *hcounts_b = nullptr;   // 2 * items_cap * classes each
@@ -211,7 +211,7 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
                     bp.w1 = c1.w; bp.bias1 = c1.bias; bp.m0s1 = c1.m0s; bp.chi1 = c1.chi; bp.shm11 = c1.shm1;
                     bp.w2 = c2.w; bp.bias2 = c2.bias; bp.m0s2 = c2.m0s; bp.chi2 = c2.chi; bp.shm12 = c2.shm1;
                     bp.zpad = c1.zpad;
-                    bp.Cin_p = c1.Cin_p; bp.H = c1.H; bp.W = c1.W; bp.B = (int32_t)bn; bp.tail = d.bneck == 2;
+                    bp.Cin_p = c1.Cin_p; bp.H = c1.H; bp.W = c1.W; bp.B = (int32_t)bn; bp.tail = d.bneck >= 2;
                     bp.zp_t1 = c1.zp_out;
                     bp.lo1 = c1.relu ? c1.zp_out : -128;
                     bp.lo2 = c2.relu ? c2.zp_out : -128;
@@ -224,7 +224,8 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
                         bp.add_k = c3.add_k; bp.add_sh = c3.add_sh; bp.add_lo = c3.add_lo;
                         bp.tie_free = bp.tie_free && c3.tie_free && c3.add_tie_free;
                     }
-                    HIP_TRY(launch_bottleneck(bp, m->stream));
+                    if (d.bneck == 3) HIP_TRY(launch_bottleneck128(bp, m->stream));
+                    else HIP_TRY(launch_bottleneck(bp, m->stream));
                     break;
                 }
                 ConvParams c = d.conv;
@@ -436,10 +437,12 @@ int isr_load_model(const void *blob_host, size_t bytes, isr_model **out) {
     if (e != hipSuccess) { g_last_hip_error = (int)e; return cleanup(ISR_ERR_DEVICE); }
     rebase_device_ops(m->ops, m->dconst);
     m->plan[0].ops = m->ops;
-    build_fused_plan(m->pm, m->ops, m->plan[1].ops);
+    build_fused_plan(m->pm, m->ops, m->plan[1].ops, false);
+    build_fused_plan(m->pm, m->ops, m->plan[2].ops, true);
     {   // descriptors of the identity-block chains, in device memory
         std::vector<BlockDesc> descs;
-        for (DevOp &d : m->plan[1].ops) {
+        for (int pi = 1; pi <= 2; ++pi)
+        for (DevOp &d : m->plan[pi].ops) {
             if (!d.block) continue;
             d.chain_off = descs.size();
             for (const auto &blk : d.chain) {
@@ -466,7 +469,8 @@ int isr_load_model(const void *blob_host, size_t bytes, isr_model **out) {
 
 int isr_set_fusion(isr_model *m, int enable) {
     if (!m) return ISR_ERR_ARG;
-    m->use_fused = enable ? 1 : 0;
+    if (enable < 0 || enable > 2) return ISR_ERR_ARG;
+    m->use_fused = enable;
     return ISR_OK;
 }
 
@@ -563,10 +567,10 @@ int isr_model_info(const isr_model *m, int *C, int *H, int *W, int *num_classes)
 size_t isr_workspace_bytes(const isr_model *m, uint32_t chunk_samples) {
     if (!m || chunk_samples == 0) return 0;
     size_t need = 0;
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < 3; ++i) {
         Plan pl;
         pl.ops = m->plan[i].ops;
-        if (i == 1) plan_segments(m->pm, chunk_samples, pl);
+        if (i >= 1) plan_segments(m->pm, chunk_samples, pl);
         plan_workspace(m->pm, chunk_samples, pl);
         need = std::max(need, pl.bytes);
     }
@@ -581,7 +585,8 @@ int isr_set_workspace(isr_model *m, void *workspace_device, size_t bytes, uint32
         if ((uint64_t)chunk_samples * t.H * t.W * std::max(t.Cp, 16) >= (1ull << 31)) return ISR_ERR_ARG;
     if (bytes < isr_workspace_bytes(m, chunk_samples)) return ISR_ERR_WORKSPACE;
     plan_segments(m->pm, chunk_samples, m->plan[1]);
-    for (int i = 0; i < 2; ++i) plan_workspace(m->pm, chunk_samples, m->plan[i]);
+    plan_segments(m->pm, chunk_samples, m->plan[2]);
+    for (int i = 0; i < 3; ++i) plan_workspace(m->pm, chunk_samples, m->plan[i]);
     m->ws = (uint8_t *)workspace_device;
     m->ws_bytes = bytes;
     m->chunk = chunk_samples;
@@ -718,7 +723,7 @@ int isr_debug_tensor(isr_model *m, const uint8_t *x_device, uint32_t sigma, uint
     const DeviceNoiseTable *table = nullptr;
     if ((rc = get_table(m, sigma, &table)) != ISR_OK) return rc;
     // tensors that the fused plan never materialises come from the op-by-op plan
-    const Plan &pl = (m->use_fused && m->plan[1].has[tensor_id]) ? m->plan[1] : m->plan[0];
+    const Plan &pl = (m->use_fused && m->plan[m->use_fused].has[tensor_id]) ? m->plan[m->use_fused] : m->plan[0];
     if ((rc = run_range(m, pl, x_device, table, seed, image_id, phase, sample, 1, nullptr, nullptr, nullptr, tensor_id)) != ISR_OK) return rc;
     const TensorDesc &t = pm.tensors[tensor_id];
     const size_t hw = (size_t)t.H * t.W;
@@ -733,7 +738,7 @@ int isr_debug_tensor(isr_model *m, const uint8_t *x_device, uint32_t sigma, uint
 int isr_debug_tensor_source(const isr_model *m, int32_t tensor_id, int *from_fused_out) {
     if (!m || !from_fused_out || tensor_id < 0 || tensor_id >= (int)m->pm.tensors.size()) return ISR_ERR_ARG;
     if (m->plan[1].has.empty()) return ISR_ERR_WORKSPACE;   // plans are placed by isr_set_workspace
-    *from_fused_out = (m->use_fused && m->plan[1].has[tensor_id]) ? 1 : 0;
+    *from_fused_out = (m->use_fused && m->plan[m->use_fused].has[tensor_id]) ? 1 : 0;
     return ISR_OK;
 }
 

@@ -150,14 +150,14 @@ struct BlockParams {
     int32_t tie_free;        // every convolution and add of the chain is free of rounding ties
 };
 
-// Bottleneck block with 64 middle channels in one kernel (bottleneck.hip): conv1x1 -> conv3x3
-// [-> conv1x1 + residual add with the block input when tail != 0].
+// Bottleneck block in one kernel: conv1x1 -> conv3x3 [-> conv1x1 + residual add with the block input
+// when tail != 0]; 64 middle channels (bottleneck.hip) or 128 (bottleneck128.hip, tail only).
 struct BneckParams {
     const int8_t *in;        // [B][H][W][Cin_p] block input x (also the residual of the tail)
     int8_t *out;             // tail: [B][H][W][Cout_p]; else the 3x3 output [B][H][W][64]
-    const int8_t *w1;        // [>= 64][Cin_p] rows in MFMA row order
-    const int8_t *w2;        // [>= 64][576], K = (tap, channel)
-    const int8_t *w3;        // [>= Cout_p][64] (tail)
+    const int8_t *w1;        // [>= Cmid][Cin_p] rows in MFMA row order
+    const int8_t *w2;        // [>= Cmid][9 Cmid], K = (tap, channel)
+    const int8_t *w3;        // [>= Cout_p][Cmid] (tail)
     const int32_t *bias1, *m0s1, *chi1, *shm11;   // as in ConvParams, per convolution
     const int32_t *bias2, *m0s2, *chi2, *shm12;
     const int32_t *bias3, *m0s3, *chi3, *shm13;
@@ -269,6 +269,8 @@ hipError_t launch_basic_block(const BlockParams &p, hipStream_t st);
 bool basic_block_supported(int channels, int size);
 hipError_t launch_bottleneck(const BneckParams &p, hipStream_t st);
 bool bottleneck_supported(int cin_p, int cmid_p, int cout_p, int tail);
+hipError_t launch_bottleneck128(const BneckParams &p, hipStream_t st);   // 128 middle channels, identity blocks (bottleneck128.hip)
+bool bottleneck128_supported(int cin_p, int cmid_p, int cout_p);
 hipError_t launch_trans_block(const TransParams &p, hipStream_t st);
 bool trans_block_supported(int cout, int size_out);
 hipError_t launch_add(const AddParams &p, hipStream_t st);

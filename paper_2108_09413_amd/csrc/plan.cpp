@@ -279,10 +279,11 @@ void fuse_trans_blocks(const ParsedModel &pm, std::vector<DevOp> &ops) {
     }
 }
 
-// Folds conv1x1 (-> 64 channels) -> conv3x3 (64 -> 64) of a bottleneck block into one kernel,
-// and with them the closing conv1x1 + residual add when the residual is the block input.
+// Folds conv1x1 (-> 64 or 128 channels) -> conv3x3 of a bottleneck block into one kernel, and with
+// them the closing conv1x1 + residual add when the residual is the block input (with 128 middle
+// channels only whole blocks are folded).
 // Runs on the list in which the adds are already folded into their convolutions.
-void fuse_bottlenecks(const ParsedModel &pm, std::vector<DevOp> &ops) {
+void fuse_bottlenecks(const ParsedModel &pm, std::vector<DevOp> &ops, bool wide) {
     std::vector<int> uses(pm.tensors.size(), 0);
     for (const DevOp &d : ops) {
         if (d.a >= 0) uses[d.a]++;
@@ -296,28 +297,40 @@ void fuse_bottlenecks(const ParsedModel &pm, std::vector<DevOp> &ops) {
         const DevOp &b = ops[i + 1];
         if (!plain(a) || !plain(b) || a.conv.fuse_add || b.conv.fuse_add) continue;
         const ConvParams &c1 = a.conv, &c2 = b.conv;
-        if (c1.k != 1 || c1.stride != 1 || c1.pad != 0 || c1.Kp != c1.Cin_p || c1.Cout_p != 64) continue;
-        if (c2.k != 3 || c2.stride != 1 || c2.pad != 1 || c2.Cin_p != 64 || c2.Cout_p != 64 || c2.Kp != 576) continue;
-        if (b.a != a.out || uses[a.out] != 1 || !bottleneck_supported(c1.Cin_p, 64, 0, 0)) continue;
+        const int cm = c1.Cout_p;
+        if (cm != 64 && !(cm == 128 && wide)) continue;
+        if (c1.k != 1 || c1.stride != 1 || c1.pad != 0 || c1.Kp != c1.Cin_p) continue;
+        if (c2.k != 3 || c2.stride != 1 || c2.pad != 1 || c2.Cin_p != cm || c2.Cout_p != cm || c2.Kp != 9 * cm) continue;
+        if (b.a != a.out || uses[a.out] != 1) continue;
+        // the closing 1x1 convolution + residual add with the block input, if the list goes on with it
+        const DevOp *c = i + 2 < ops.size() ? &ops[i + 2] : nullptr;
+        bool tail = false;
+        if (c) {
+            const ConvParams &c3 = c->conv;
+            tail = plain(*c) && c3.fuse_add == 1 && c3.k == 1 && c3.stride == 1 && c3.pad == 0 && c3.Cin_p == cm && c3.Kp == cm &&
+                   c->a == b.out && c->b == a.a && uses[b.out] == 1;
+        }
+        if (cm == 64) {
+            if (!bottleneck_supported(c1.Cin_p, 64, 0, 0)) continue;
+            tail = tail && bottleneck_supported(c1.Cin_p, 64, c->conv.Cout_p, 1);
+        } else {
+            // 128 middle channels: the whole block or nothing
+            if (!tail || !bottleneck128_supported(c1.Cin_p, 128, c->conv.Cout_p)) continue;
+        }
+        const DevOp cc = tail ? *c : DevOp{};
         a.bneck = 1;
         a.conv2 = c2;
         a.ops_per_sample += b.ops_per_sample;
         a.bytes_per_sample = (double)pm.tensors[a.a].C * c1.H * c1.W + (double)pm.tensors[b.out].C * c1.H * c1.W;
         a.out = b.out;
-        ops.erase(ops.begin() + i + 1);
-        if (i + 1 < ops.size()) {
-            const DevOp &c = ops[i + 1];
-            const ConvParams &c3 = c.conv;
-            if (plain(c) && c3.fuse_add == 1 && c3.k == 1 && c3.stride == 1 && c3.pad == 0 && c3.Cin_p == 64 && c3.Kp == 64 &&
-                c.a == a.out && c.b == a.a && uses[a.out] == 1 && bottleneck_supported(c1.Cin_p, 64, c3.Cout_p, 1)) {
-                a.bneck = 2;
-                a.conv3 = c3;
-                a.ops_per_sample += c.ops_per_sample;
-                a.bytes_per_sample = 2.0 * pm.tensors[a.a].C * c1.H * c1.W;
-                a.out = c.out;
-                ops.erase(ops.begin() + i + 1);
-            }
+        if (tail) {
+            a.bneck = cm == 64 ? 2 : 3;
+            a.conv3 = cc.conv;
+            a.ops_per_sample += cc.ops_per_sample;
+            a.bytes_per_sample = 2.0 * pm.tensors[a.a].C * c1.H * c1.W;
+            a.out = cc.out;
         }
+        ops.erase(ops.begin() + i + 1, ops.begin() + i + (tail ? 3 : 2));
     }
 }
 
@@ -520,7 +533,7 @@ void rebase_device_ops(std::vector<DevOp> &ops, const uint8_t *base) {
     }
 }
 
-void build_fused_plan(const ParsedModel &pm, const std::vector<DevOp> &plain, std::vector<DevOp> &fused) {
+void build_fused_plan(const ParsedModel &pm, const std::vector<DevOp> &plain, std::vector<DevOp> &fused, bool wide_bottlenecks) {
     fuse_adds(pm, plain, fused);
     fuse_stem_pool(pm, fused);
     if (!fused.empty()) {
@@ -533,7 +546,7 @@ void build_fused_plan(const ParsedModel &pm, const std::vector<DevOp> &plain, st
     fuse_basic_blocks(pm, fused);
     chain_basic_blocks(pm, fused);
     fuse_trans_blocks(pm, fused);
-    fuse_bottlenecks(pm, fused);
+    fuse_bottlenecks(pm, fused, wide_bottlenecks);
 }
 
 }  // namespace isr

@@ -21,7 +21,7 @@ struct DevOp {
     std::vector<std::pair<ConvParams, ConvParams>> chain;   // block != 0: the blocks of the chain this op runs (each feeds the next)
     size_t chain_off = 0;               // first BlockDesc of the chain in the model's device array
     int trans = 0;                      // down-sampling block: this conv (3x3/2), conv2 (3x3) and conv3 (1x1/2 + add) in one kernel
-    int bneck = 0;                      // 1: this 1x1 conv and the 3x3 conv2 in one kernel; 2: plus conv3 (1x1 + residual add)
+    int bneck = 0;                      // 1: this 1x1 conv and the 3x3 conv2 in one kernel; 2: plus conv3 (1x1 + residual add); 3: as 2 with 128 middle channels
     ConvParams conv2{};
     ConvParams conv3{};
     AddParams add{};
@@ -57,8 +57,10 @@ struct ConstArena {
 int build_device_ops(const ParsedModel &pm, std::vector<DevOp> &ops, ConstArena &arena);
 // Arena offsets -> pointers into the uploaded arena at `base`.
 void rebase_device_ops(std::vector<DevOp> &ops, const uint8_t *base);
-// The op list with every fusion the kernels cover applied (from the rebased op-by-op list).
-void build_fused_plan(const ParsedModel &pm, const std::vector<DevOp> &plain, std::vector<DevOp> &fused);
+// The op list with the fusions the kernels cover applied (from the rebased op-by-op list).
+// wide_bottlenecks: also fold identity bottleneck blocks with 128 middle channels into one kernel
+// (correct, but at present slower than their three separate kernels: off in the default plan).
+void build_fused_plan(const ParsedModel &pm, const std::vector<DevOp> &plain, std::vector<DevOp> &fused, bool wide_bottlenecks);
 // Chooses the sub-chunk segments of a plan for chunks of B samples (before plan_workspace).
 void plan_segments(const ParsedModel &pm, uint32_t B, Plan &pl);
 // Offsets of every tensor of a chunk of B samples in the workspace.

@@ -128,7 +128,7 @@ def test_device_sampler_law_at_scale(isr, sigma):
 
 # ---- S3-S6: layer tensors ----------------------------------------------------
 
-def _check_all_tensors(isr, blob, x, sigma, seed=3, image=1, phase=1, sample=17, chunk=4, min_fused=0):
+def _check_all_tensors(isr, blob, x, sigma, seed=3, image=1, phase=1, sample=17, chunk=4, min_fused=0, fusion=1):
     """Every tensor of one noisy copy against the oracle.  With fusion on (the default) a tensor that
     a fused kernel stores is that kernel's own output; a tensor that no fused kernel stores (the
     output of a convolution folded into a residual add, the 112x112 first-layer output under the
@@ -138,6 +138,7 @@ def _check_all_tensors(isr, blob, x, sigma, seed=3, image=1, phase=1, sample=17,
     this copy below, and by the multi-copy logits check that follows every fused-kernel test.
     min_fused: at least that many tensors must come from fused kernels (guards the test's premise)."""
     m = _load(isr, blob, chunk)
+    isr.isr_set_fusion(m, fusion)
     om = oracle.Model(blob)
     a0 = oracle.noisy(x, sigma, seed, image, phase, sample)
     logits, tensors = om.forward(a0)
@@ -353,6 +354,49 @@ def test_bottleneck_blocks_in_one_kernel(isr, shape):
     lg, am, cnt = isr.isr_debug_forward(m, x, 64, 3, 1, 1, 50, 5)
     olg, oam, ocnt = om.mc(x, 64, 3, 1, 1, 50, 5)
     assert np.array_equal(lg, olg) and np.array_equal(cnt, ocnt)
+    m.close()
+
+
+@pytest.mark.parametrize("shape", [(30, 20), (28, 28), (5, 40)])
+def test_bottleneck_blocks_with_128_middle_channels_in_one_kernel(isr, shape):
+    """conv1x1 -> conv3x3 (128 middle channels) -> conv1x1 + add with the block input as one kernel on
+    14 x 14 pixel tiles: images with ragged tiles in both directions, one exactly two tiles wide, one
+    lower than a tile; block widths 512 / 256 / 192 (eight, four and three K steps; 192 leaves the
+    last round of output-channel passes to two of the four waves); zero-points on every tensor, ReLU
+    on and off, a block with power-of-two multipliers (rounding ties)."""
+    h, w = shape
+    _say(f"layer parity fused bottleneck blocks, 128 middle channels, {h}x{w}")
+    b = NetBuilder(rng=np.random.default_rng(83), in_shape=(3, h, w), num_classes=5)
+    t = b.conv(b.tensor(3, h, w, 0, 74.0), 64, 3, 1, 1, True)
+    t = b.conv(t, 512, 1, 1, 0, True)
+    def block(x, cx, z1, z2, z3, zo, relu12=True, relu_out=True, pow2=False):
+        kw = dict(m0=np.full(128, 1 << 30, dtype=np.int64), sh=np.full(128, 9)) if pow2 else {}
+        u = b.conv(x, 128, 1, 1, 0, relu12, zp_out=z1, **kw)
+        u = b.conv(u, 128, 3, 1, 1, relu12, zp_out=z2, **kw)
+        u = b.conv(u, cx, 1, 1, 0, False, zp_out=z3)
+        if pow2:
+            return b.add(x, u, relu_out, ma=1 << 19, mb=1 << 19, sh=20, zp_out=zo)
+        return b.add(x, u, relu_out, zp_out=zo)
+    t = block(t, 512, -128, -128, 0, -128)
+    t = block(t, 512, 9, -20, -6, 11, relu12=False, relu_out=False)
+    t = block(t, 512, -128, -128, 4, -128, pow2=True)
+    t = b.conv(t, 256, 1, 1, 0, True)
+    t = block(t, 256, -100, 7, 3, -128)
+    t = b.conv(t, 192, 1, 1, 0, True)
+    t = block(t, 192, -128, -90, 0, -128)
+    b.fc(b.gap(t), 5)
+    blob = b.blob()
+    x = np.random.default_rng(15).integers(0, 256, size=(3, h, w)).astype(np.uint8)
+    _check_all_tensors(isr, blob, x, 64, sample=2, chunk=3, min_fused=5, fusion=2)
+    m = _load(isr, blob, 5)
+    isr.isr_set_fusion(m, 2)
+    om = oracle.Model(blob)
+    lg, am, cnt = isr.isr_debug_forward(m, x, 64, 3, 1, 1, 50, 5)
+    olg, oam, ocnt = om.mc(x, 64, 3, 1, 1, 50, 5)
+    assert np.array_equal(lg, olg) and np.array_equal(cnt, ocnt)
+    isr.isr_set_fusion(m, False)
+    lg2, _, _ = isr.isr_debug_forward(m, x, 64, 3, 1, 1, 50, 5)
+    assert np.array_equal(lg2, olg)
     m.close()
 
 
