@@ -179,35 +179,115 @@ void isr_oracle_free(omodel *m) {
     free(m->blob); free(m->t); free(m->ops); free(m);
 }
 
+/* Output extent of a sliding window: floor((in + 2 pad - k) / stride) + 1. */
+static int32_t window_out(int32_t in, int32_t k, int32_t stride, int32_t pad) { return (in + 2 * pad - k) / stride + 1; }
+
+/* Structural checks of one op against the tensor table; payload = the op's `len` bytes.
+ * Returns 1 when the op is well-formed (ids in range, inputs produced earlier, output not
+ * yet produced, shapes consistent, payload exactly as long as its fields and arrays). */
+static int op_is_sound(const omodel *m, const oop *o, const char *made, size_t len) {
+    const int32_t nt = m->nt;
+#define ID_OK(id) ((id) >= 0 && (id) < nt)
+    switch (o->type) {
+    case OP_CONV: {
+        if (!ID_OK(o->a) || !ID_OK(o->out) || !made[o->a] || made[o->out]) return 0;
+        const otensor *ti = &m->t[o->a], *to = &m->t[o->out];
+        if (o->k < 1 || o->k > 15 || o->stride < 1 || o->stride > 8 || o->pad < 0 || o->pad >= o->k) return 0;
+        if (o->relu != 0 && o->relu != 1) return 0;
+        if (ti->H + 2 * o->pad < o->k || ti->W + 2 * o->pad < o->k) return 0;
+        if (to->H != window_out(ti->H, o->k, o->stride, o->pad) || to->W != window_out(ti->W, o->k, o->stride, o->pad)) return 0;
+        size_t wb = (size_t)to->C * ti->C * o->k * o->k;
+        if (len != 24 + ((wb + 3) & ~(size_t)3) + 3 * (size_t)to->C * 4) return 0;
+        int64_t worst = (int64_t)ti->C * o->k * o->k * 255 * 127;   /* largest |sum of products| of int8 operands */
+        for (int32_t c = 0; c < to->C; ++c) {
+            if (o->M0[c] < (1 << 30) || o->shift[c] < 0 || o->shift[c] > 31) return 0;
+            int64_t ab = o->bias[c] < 0 ? -(int64_t)o->bias[c] : o->bias[c];
+            if (worst + ab >= ((int64_t)1 << 31)) return 0;           /* the int32 accumulator must not overflow */
+        }
+        for (size_t i = 0; i < wb; ++i)
+            if (o->w[i] == -128) return 0;
+        return 1; }
+    case OP_ADD: {
+        if (len != 28 || !ID_OK(o->a) || !ID_OK(o->b) || !ID_OK(o->out) || !made[o->a] || !made[o->b] || made[o->out]) return 0;
+        const otensor *ta = &m->t[o->a], *tb = &m->t[o->b], *to = &m->t[o->out];
+        if (ta->C != tb->C || ta->H != tb->H || ta->W != tb->W || ta->C != to->C || ta->H != to->H || ta->W != to->W) return 0;
+        return o->sh >= 0 && o->sh <= 40 && (o->relu == 0 || o->relu == 1); }
+    case OP_MAXPOOL: {
+        if (len != 20 || !ID_OK(o->a) || !ID_OK(o->out) || !made[o->a] || made[o->out]) return 0;
+        const otensor *ti = &m->t[o->a], *to = &m->t[o->out];
+        if (o->k < 1 || o->k > 15 || o->stride < 1 || o->stride > 8 || o->pad < 0 || o->pad >= o->k) return 0;
+        if (ti->H + 2 * o->pad < o->k || ti->W + 2 * o->pad < o->k || to->C != ti->C || to->zp != ti->zp) return 0;
+        return to->H == window_out(ti->H, o->k, o->stride, o->pad) && to->W == window_out(ti->W, o->k, o->stride, o->pad); }
+    case OP_GAP: {
+        if (len != 16 || !ID_OK(o->a) || !ID_OK(o->out) || !made[o->a] || made[o->out]) return 0;
+        const otensor *ti = &m->t[o->a], *to = &m->t[o->out];
+        if ((int64_t)ti->H * ti->W * 255 >= ((int64_t)1 << 31)) return 0;   /* the int32 sum must not overflow */
+        return to->C == ti->C && to->H == 1 && to->W == 1 && o->Ma >= (1 << 30) && o->sh >= 0 && o->sh <= 31; }
+    case OP_FC: {
+        if (!ID_OK(o->a) || !ID_OK(o->out) || !made[o->a] || made[o->out]) return 0;
+        const otensor *ti = &m->t[o->a], *to = &m->t[o->out];
+        if (to->C != m->classes || to->H != 1 || to->W != 1) return 0;
+        size_t wb = (size_t)to->C * ti->C * ti->H * ti->W;
+        if (len != 8 + ((wb + 3) & ~(size_t)3) + (size_t)to->C * 4) return 0;
+        int64_t worst = (int64_t)ti->C * ti->H * ti->W * 255 * 127;
+        for (int32_t c = 0; c < to->C; ++c) {
+            int64_t ab = o->bias[c] < 0 ? -(int64_t)o->bias[c] : o->bias[c];
+            if (worst + ab >= ((int64_t)1 << 31)) return 0;
+        }
+        for (size_t i = 0; i < wb; ++i)
+            if (o->w[i] == -128) return 0;
+        return 1; }
+    default: return 0;
+    }
+#undef ID_OK
+}
+
+/* Parses a blob; NULL when it is truncated, inconsistent or outside the format's ranges
+ * (no field of a rejected blob is ever used as an index or a size). */
 omodel *isr_oracle_load(const void *blob, size_t bytes) {
-    if (bytes < 32) return NULL;
+    if (!blob || bytes < 32) return NULL;
     omodel *m = (omodel *)calloc(1, sizeof(omodel));
+    char *made = NULL;   /* per tensor: produced by an earlier op (or the input) */
+    if (!m) return NULL;
     m->blob = (uint8_t *)malloc(bytes);
+    if (!m->blob) { free(m); return NULL; }
     memcpy(m->blob, blob, bytes);
     const uint8_t *p = m->blob, *end = m->blob + bytes;
-    if (rd32(p) != 0x4D525349 || rd32(p + 4) != 1) { isr_oracle_free(m); return NULL; }
+    if (rd32(p) != 0x4D525349 || rd32(p + 4) != 1) goto reject;
     m->C = rd32(p + 8); m->H = rd32(p + 12); m->W = rd32(p + 16);
     m->classes = rd32(p + 20); m->nt = rd32(p + 24); m->nops = rd32(p + 28);
     p += 32;
+    if (m->nt < 2 || m->nt > 100000 || m->nops < 1 || m->nops > 100000 || m->classes < 1) goto reject;
+    if ((size_t)(end - p) < (size_t)m->nt * 16) goto reject;
     m->t = (otensor *)calloc((size_t)m->nt, sizeof(otensor));
     m->ops = (oop *)calloc((size_t)m->nops, sizeof(oop));
+    made = (char *)calloc((size_t)m->nt, 1);
+    if (!m->t || !m->ops || !made) goto reject;
     for (int i = 0; i < m->nt; ++i, p += 16) {
-        if (p + 16 > end) { isr_oracle_free(m); return NULL; }
-        m->t[i].C = rd32(p); m->t[i].H = rd32(p + 4); m->t[i].W = rd32(p + 8); m->t[i].zp = rd32(p + 12);
+        otensor *t = &m->t[i];
+        t->C = rd32(p); t->H = rd32(p + 4); t->W = rd32(p + 8); t->zp = rd32(p + 12);
+        if (t->C < 1 || t->C > 65536 || t->H < 1 || t->H > 4096 || t->W < 1 || t->W > 4096 || t->zp < -128 || t->zp > 127) goto reject;
     }
+    if (m->t[0].C != m->C || m->t[0].H != m->H || m->t[0].W != m->W) goto reject;
+    made[0] = 1;
     for (int i = 0; i < m->nops; ++i) {
-        if (p + 8 > end) { isr_oracle_free(m); return NULL; }
+        if ((size_t)(end - p) < 8) goto reject;
         oop *o = &m->ops[i];
         o->type = rd32(p);
         int32_t len = rd32(p + 4);
         const uint8_t *q = p + 8;
-        if (q + len > end) { isr_oracle_free(m); return NULL; }
+        if (len < 0 || (len & 3) || (size_t)(end - q) < (size_t)len) goto reject;
+        if (i > 0 && m->ops[i - 1].type == OP_FC) goto reject;   /* the logits end the network */
+        /* fixed fields first (their count is checked against len), arrays only after the ids are known good */
         switch (o->type) {
         case OP_CONV: {
+            if (len < 24) goto reject;
             o->a = rd32(q); o->out = rd32(q + 4); o->k = rd32(q + 8); o->stride = rd32(q + 12);
             o->pad = rd32(q + 16); o->relu = rd32(q + 20);
+            if (o->a < 0 || o->a >= m->nt || o->out < 0 || o->out >= m->nt || o->k < 1 || o->k > 15) goto reject;
             int32_t cin = m->t[o->a].C, cout = m->t[o->out].C;
             size_t wb = (size_t)cout * cin * o->k * o->k;
+            if ((size_t)len != 24 + ((wb + 3) & ~(size_t)3) + 3 * (size_t)cout * 4) goto reject;
             o->w = (const int8_t *)(q + 24);
             const uint8_t *r = q + 24 + ((wb + 3) & ~(size_t)3);
             o->bias = (const int32_t *)r;
@@ -215,28 +295,42 @@ omodel *isr_oracle_load(const void *blob, size_t bytes) {
             o->shift = o->M0 + cout;
             break; }
         case OP_ADD:
+            if (len != 28) goto reject;
             o->a = rd32(q); o->b = rd32(q + 4); o->out = rd32(q + 8); o->Ma = rd32(q + 12);
             o->Mb = rd32(q + 16); o->sh = rd32(q + 20); o->relu = rd32(q + 24);
             break;
         case OP_MAXPOOL:
+            if (len != 20) goto reject;
             o->a = rd32(q); o->out = rd32(q + 4); o->k = rd32(q + 8); o->stride = rd32(q + 12);
             o->pad = rd32(q + 16);
             break;
         case OP_GAP:
+            if (len != 16) goto reject;
             o->a = rd32(q); o->out = rd32(q + 4); o->Ma = rd32(q + 8); o->sh = rd32(q + 12);
             break;
         case OP_FC: {
+            if (len < 8) goto reject;
             o->a = rd32(q); o->out = rd32(q + 4);
+            if (o->a < 0 || o->a >= m->nt || o->out < 0 || o->out >= m->nt) goto reject;
             otensor ti = m->t[o->a];
             size_t wb = (size_t)m->t[o->out].C * ti.C * ti.H * ti.W;
+            if ((size_t)len != 8 + ((wb + 3) & ~(size_t)3) + (size_t)m->t[o->out].C * 4) goto reject;
             o->w = (const int8_t *)(q + 8);
             o->bias = (const int32_t *)(q + 8 + ((wb + 3) & ~(size_t)3));
             break; }
-        default: isr_oracle_free(m); return NULL;
+        default: goto reject;
         }
+        if (!op_is_sound(m, o, made, (size_t)len)) goto reject;
+        made[o->out] = 1;
         p = q + len;
     }
+    if (p != end || m->ops[m->nops - 1].type != OP_FC) goto reject;
+    free(made);
     return m;
+reject:
+    free(made);
+    isr_oracle_free(m);
+    return NULL;
 }
 
 void isr_oracle_info(const omodel *m, int32_t *C, int32_t *H, int32_t *W, int32_t *classes, int32_t *nt) {

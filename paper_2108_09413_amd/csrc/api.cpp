@@ -159,6 +159,17 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
                     sp.w = d.conv.w; sp.bias = d.conv.bias; sp.m0s = d.conv.m0s; sp.chi = d.conv.chi; sp.shm1 = d.conv.shm1;
                     sp.H = d.conv.H; sp.W = d.conv.W; sp.Ho = d.conv.Ho; sp.Wo = d.conv.Wo; sp.Hp = to.H; sp.Wp = to.W;
                     sp.zp_in = d.conv.zp_in; sp.zp_out = d.conv.zp_out; sp.relu = d.conv.relu; sp.tie_free = d.conv.tie_free; sp.B = (int32_t)bn;
+                    sp.fused_noise = d.noise_fused;
+                    sp.noise = NoiseSource{};
+                    if (d.noise_fused) {
+                        NoiseSource &ns = sp.noise;
+                        ns.x = x; ns.table = table; ns.items = nullptr;
+                        ns.key0 = (uint32_t)seed; ns.key1 = (uint32_t)(seed >> 32);
+                        ns.image = image; ns.phase = phase; ns.sample_begin = begin + (uint32_t)done + j0;
+                        ns.n_per_item = 0; ns.slot_begin = 0;
+                        ns.C = pm.C; ns.H = pm.H; ns.W = pm.W;
+                        if (bc) { ns.items = bc->items; ns.n_per_item = bc->n_per_item; ns.slot_begin = done + j0; }
+                    }
                     HIP_TRY(launch_stem_pool(sp, m->stream));
                     break;
                 }
@@ -294,9 +305,11 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
                 sub = std::max<uint32_t>(1, std::min(cnt, pl.segments[sg].sub));
             }
             if (op1 < op0) op1 = op0;
+            // no noise launch when the first op of the plan draws its own input (and runs at all)
+            const bool own_noise = nops > 0 && !pl.ops.empty() && pl.ops[0].noise_fused;
             for (uint32_t j0 = 0; j0 < cnt; j0 += sub) {
                 const uint32_t bn = std::min(sub, cnt - j0);
-                if (!noise_done && (prc = run_noise(j0, bn)) != ISR_OK) return prc;
+                if (!noise_done && !own_noise && (prc = run_noise(j0, bn)) != ISR_OK) return prc;
                 for (size_t i = op0; i < op1; ++i)
                     if ((prc = run_op(pl.ops[i], j0, bn)) != ISR_OK) return prc;
             }
@@ -471,20 +484,6 @@ int isr_set_fusion(isr_model *m, int enable) {
     if (!m) return ISR_ERR_ARG;
     if (enable < 0 || enable > 2) return ISR_ERR_ARG;
     m->use_fused = enable;
-    return ISR_OK;
-}
-
-int isr_discrete_quantile(uint32_t sigma, double p_lower, int32_t *t_out, uint64_t *radius_sq_out) {
-    if (sigma < 1 || sigma > 1024 || !(p_lower >= 0.0 && p_lower <= 1.0)) return ISR_ERR_ARG;
-    const auto tab = cached_noise_table(sigma);
-    if (!tab) return ISR_ERR_ARG;
-    // floor(2^64 p): exact for a double below 1 (53 significant bits, scaled by a power of two)
-    const uint64_t u = p_lower >= 1.0 ? ~0ull : (uint64_t)std::ldexp(p_lower, 64);
-    // thresholds ascend: the number of entries <= u by binary search
-    const int64_t below = std::upper_bound(tab->T.begin(), tab->T.end(), u) - tab->T.begin();
-    const int64_t t = -(int64_t)tab->R - 1 + below;
-    if (t_out) *t_out = (int32_t)t;
-    if (radius_sq_out) *radius_sq_out = t > 0 ? (uint64_t)(t * t) : 0;
     return ISR_OK;
 }
 

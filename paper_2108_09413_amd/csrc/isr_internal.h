@@ -40,6 +40,25 @@ bool build_bank_table(uint32_t sigma, std::vector<uint32_t> &words, uint32_t &n_
 void set_last_device_error(int hip_error);
 bool build_device_table(uint32_t sigma, DeviceNoiseTable &out);
 
+// One (image, sigma) pair of a batched call.
+struct NoiseItem {
+    uint32_t image;          // index into the array of clean images
+    uint32_t table_slot;     // index into the array of noise tables
+    uint32_t image_id;       // counter word of the random stream
+};
+
+// Which image, table and sample index copy `copy` of a chunk draws from.  Single pair: the call's
+// own; batch mode (items != null): copy s is slot slot_begin + s of a list in which item i owns
+// the n_per_item slots from i * n_per_item on.
+struct NoiseSource {
+    const uint8_t *x;                // [C][H][W] clean image ([images][C][H][W] in batch mode)
+    const DeviceNoiseTable *table;   // the table (batch mode: table 0 of the array indexed by table_slot)
+    const NoiseItem *items;
+    uint32_t key0, key1, image, phase, sample_begin, n_per_item;
+    uint64_t slot_begin;
+    int32_t C, H, W;
+};
+
 // ---- parsed model (host) ---------------------------------------------------
 enum OpType : int32_t { OP_CONV = 1, OP_ADD = 2, OP_MAXPOOL = 3, OP_GAP = 4, OP_FC = 5 };
 
@@ -118,6 +137,10 @@ struct StemPoolParams {
     const int32_t *bias, *m0s, *chi, *shm1;   // as in ConvParams (single-multiply requantisation)
     int32_t H, W, Ho, Wo, Hp, Wp;
     int32_t zp_in, zp_out, relu, tie_free, B;
+    // fused_noise != 0: `in` is unused; the kernel draws the noisy input rows of its band itself (the
+    // sampler of the noise stage on the same counter-based stream), copy b of the launch from `noise`
+    int32_t fused_noise;
+    NoiseSource noise;
 };
 
 // First convolution of the narrow small-image nets: 3x3 stride 1 pad 1 on the NHWC4 image
@@ -219,12 +242,6 @@ struct FcParams {
     uint64_t slot_begin;
 };
 
-// One (image, sigma) pair of a batched call.
-struct NoiseItem {
-    uint32_t image;          // index into the array of clean images
-    uint32_t table_slot;     // index into the array of noise tables
-    uint32_t image_id;       // counter word of the random stream
-};
 
 struct NoiseParams {
     const uint8_t *x;        // [C][H][W] clean image ([images][C][H][W] in batch mode)

@@ -1,6 +1,8 @@
 // Inverse-CDF threshold table of the discrete Gaussian N_Z(0, sigma^2)
 // (Def. 3.3 with location 0), integer arithmetic only, and the compact form
 // of it the device sampler reads.
+#include <algorithm>
+#include <cmath>
 #include <cstdint>
 #include <map>
 #include <memory>
@@ -126,3 +128,19 @@ extern "C" int isr_noise_table(uint32_t sigma, uint64_t *T_host, size_t cap, uin
     for (size_t i = 0; i < cap && i < tab->T.size(); ++i) T_host[i] = tab->T[i];
     return ISR_OK;
 }
+
+// Inverse cdf of the discrete law by lookup in the same table (Thm 3.2, proof steps 2 and 3).
+extern "C" int isr_discrete_quantile(uint32_t sigma, double p_lower, int32_t *t_out, uint64_t *radius_sq_out) {
+    if (sigma < 1 || sigma > 1024 || !(p_lower >= 0.0 && p_lower <= 1.0)) return ISR_ERR_ARG;
+    const auto tab = isr::cached_noise_table(sigma);
+    if (!tab) return ISR_ERR_ARG;
+    // floor(2^64 p): exact for a double below 1 (53 significant bits, scaled by a power of two)
+    const uint64_t u = p_lower >= 1.0 ? ~0ull : (uint64_t)std::ldexp(p_lower, 64);
+    // thresholds ascend: the number of entries <= u by binary search
+    const int64_t below = std::upper_bound(tab->T.begin(), tab->T.end(), u) - tab->T.begin();
+    const int64_t t = -(int64_t)tab->R - 1 + below;
+    if (t_out) *t_out = (int32_t)t;
+    if (radius_sq_out) *radius_sq_out = t > 0 ? (uint64_t)(t * t) : 0;
+    return ISR_OK;
+}
+

@@ -543,6 +543,12 @@ void build_fused_plan(const ParsedModel &pm, const std::vector<DevOp> &plain, st
             stem16_supported(c.k, c.stride, c.pad, c.Cout_p, c.H, c.W, c.fast_requant))
             f.stem16 = 1;
     }
+    // the fused first layer draws its own noisy input when it is the only reader of the input tensor
+    if (!fused.empty() && fused[0].stem_pool && fused[0].a == 0) {
+        int readers = 0;
+        for (const DevOp &d : fused) readers += (d.a == 0) + (d.b == 0);
+        if (readers == 1) fused[0].noise_fused = 1;
+    }
     fuse_basic_blocks(pm, fused);
     chain_basic_blocks(pm, fused);
     fuse_trans_blocks(pm, fused);

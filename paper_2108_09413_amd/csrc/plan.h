@@ -16,6 +16,7 @@ struct DevOp {
     double ops_per_sample = 0.0, bytes_per_sample = 0.0;   // algorithmic, for the timing report
     ConvParams conv{};
     int stem_pool = 0;                  // conv fused with the max pooling after it (out = the pooled tensor)
+    int noise_fused = 0;                // the kernel of this (first) op draws the noisy input itself: no noise launch, tensor 0 never stored
     int stem16 = 0;                     // first 3x3 convolution into 16 channels: the LDS-resident kernel
     int block = 0;                      // identity residual block: this conv, conv2 and the add in one kernel
     std::vector<std::pair<ConvParams, ConvParams>> chain;   // block != 0: the blocks of the chain this op runs (each feeds the next)

@@ -20,6 +20,7 @@
 #include <climits>
 
 #include "conv_device.h"
+#include "noise_device.h"
 
 namespace isr {
 
@@ -36,6 +37,7 @@ __global__ __launch_bounds__(256, 3) void stem_pool_kernel(const StemPoolParams 
     __shared__ __attribute__((aligned(16))) int8_t Wl[64 * SP_KP];
     __shared__ __attribute__((aligned(16))) int8_t In[SP_IN_BYTES];
     __shared__ int prm[4][64];
+    __shared__ NoiseLds ntab;                 // the sampler's table when the kernel draws its own input
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nstrips = (p.Wp + SP_STRIP - 1) / SP_STRIP;       // 1 or 2 (checked by the launcher)
@@ -56,12 +58,32 @@ __global__ __launch_bounds__(256, 3) void stem_pool_kernel(const StemPoolParams 
     if (tid < 64) { prm[0][tid] = p.bias[tid]; prm[1][tid] = p.m0s[tid]; prm[2][tid] = p.chi[tid]; prm[3][tid] = p.shm1[tid]; }
     // input band: pixel (row r, input column x) at patch column x + 3
     const int wchunks = p.W >> 2;             // 16-byte chunks (4 pixels) per input row
-    for (int i = tid; i < IR * wchunks; i += 256) {
-        const int r = i / wchunks, c = i - r * wchunks, iy = iy0 + r;
-        v4i v = {(int)zb, (int)zb, (int)zb, (int)zb};
-        if ((unsigned)iy < (unsigned)p.H) v = *(const v4i *)(p.in + (((long)b * p.H + iy) * p.W + 4 * c) * 4);
-        int *dst = (int *)(&In[(r * PW + 3 + 4 * c) * 4]);
-        dst[0] = v[0]; dst[1] = v[1]; dst[2] = v[2]; dst[3] = v[3];
+    if (p.fused_noise) {
+        // the noisy rows are drawn here instead of being read back from memory: the stream is counter-based,
+        // so the rows that neighbouring bands share are simply drawn again, bit for bit the same
+        const uint8_t *xim;
+        const DeviceNoiseTable *tab;
+        uint32_t image_id, sample;
+        resolve_noise_source(p.noise, b, xim, tab, image_id, sample);
+        stage_noise_table(ntab, tab, tid, 256);
+        const int n = (int)tab->n, dmin = tab->dmin;
+        __syncthreads();
+        for (int i = tid; i < IR * wchunks; i += 256) {
+            const int r = i / wchunks, c = i - r * wchunks, iy = iy0 + r;
+            uint32_t v[4] = {zb, zb, zb, zb};
+            if ((unsigned)iy < (unsigned)p.H)
+                noisy_quad(ntab, n, dmin, xim, p.noise.C, p.H, p.W, iy, c, sample, image_id, p.noise.phase, p.noise.key0, p.noise.key1, v);
+            int *dst = (int *)(&In[(r * PW + 3 + 4 * c) * 4]);
+            dst[0] = (int)v[0]; dst[1] = (int)v[1]; dst[2] = (int)v[2]; dst[3] = (int)v[3];
+        }
+    } else {
+        for (int i = tid; i < IR * wchunks; i += 256) {
+            const int r = i / wchunks, c = i - r * wchunks, iy = iy0 + r;
+            v4i v = {(int)zb, (int)zb, (int)zb, (int)zb};
+            if ((unsigned)iy < (unsigned)p.H) v = *(const v4i *)(p.in + (((long)b * p.H + iy) * p.W + 4 * c) * 4);
+            int *dst = (int *)(&In[(r * PW + 3 + 4 * c) * 4]);
+            dst[0] = v[0]; dst[1] = v[1]; dst[2] = v[2]; dst[3] = v[3];
+        }
     }
     for (int i = tid; i < IR * 8; i += 256) {   // 3 columns left, 5 right of the image
         const int r = i >> 3, c = i & 7;
@@ -159,13 +181,19 @@ hipError_t launch_stem_pool(const StemPoolParams &p, hipStream_t st) {
     if (p.B <= 0) return hipSuccess;
     // geometry the kernel assumes: 7x7/2 pad 3 then 3x3/2 pad 1, at most two strips of pooled columns
     if (p.W % 4 != 0 || p.W < 8 || p.W > SP_WMAX || p.Ho != (p.H - 1) / 2 + 1 || p.Wo != (p.W - 1) / 2 + 1 ||
-        p.Hp != (p.Ho - 1) / 2 + 1 || p.Wp != (p.Wo - 1) / 2 + 1 || p.Wp > 2 * SP_STRIP || !p.in || !p.out || !p.w)
+        p.Hp != (p.Ho - 1) / 2 + 1 || p.Wp != (p.Wo - 1) / 2 + 1 || p.Wp > 2 * SP_STRIP || !p.out || !p.w)
         return hipErrorInvalidValue;
+    if (p.fused_noise) {
+        const NoiseSource &ns = p.noise;
+        if (!ns.x || !ns.table || ns.C < 1 || ns.C > 3 || ns.H != p.H || ns.W != p.W || (ns.items && ns.n_per_item == 0)) return hipErrorInvalidValue;
+    } else if (!p.in) {
+        return hipErrorInvalidValue;
+    }
     const int nstrips = (p.Wp + SP_STRIP - 1) / SP_STRIP, P = 2 * (4 / nstrips);
     if ((4 * P + 7) * (p.W + 8) * 4 > SP_IN_BYTES) return hipErrorInvalidValue;
     const long blocks = (long)p.B * ((p.Hp + P - 1) / P);
     if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
-    set_kernel_name("stem_pool_kernel");
+    set_kernel_name(p.fused_noise ? "stem_pool_kernel (+noise)" : "stem_pool_kernel");
     hipLaunchKernelGGL(stem_pool_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p);
     return hipGetLastError();
 }

@@ -756,6 +756,41 @@ def test_batched_pairs_resnet20_small_n(isr):
     m.close()
 
 
+@pytest.mark.parametrize("chunk", [16, 200])
+def test_batched_pairs_with_the_noise_drawn_inside_the_first_layer(isr, chunk):
+    """A net whose first layer is the 7x7/2 convolution + max pooling kernel, which draws the noisy
+    input rows itself (no separate noise launch, the noisy copy is never stored): batched pairs over
+    four images and three noise levels, chunks that split a pair's run (16) and chunks that span
+    several pairs (200); every pair against the oracle and against the single-pair call; per-sample
+    logits of a range against the oracle with and without the fusions."""
+    _say(f"batched certify / predict, noise drawn in the first layer, chunk {chunk}")
+    b = NetBuilder(rng=np.random.default_rng(33), in_shape=(3, 36, 28), num_classes=5)
+    t1 = b.conv(b.tensor(3, 36, 28, 0, 74.0), 61, 7, 2, 3, True, zp_out=-100)
+    t3 = b.conv(b.maxpool(t1, 3, 2, 1), 64, 1, 1, 0, True)
+    b.fc(b.gap(t3), 5)
+    blob = b.blob()
+    om = oracle.Model(blob)
+    m = _load(isr, blob, chunk)
+    xs = np.stack([np.random.default_rng(40 + i).integers(0, 256, size=(3, 36, 28)).astype(np.uint8) for i in range(4)])
+    items = [(0, 32, 0), (1, 64, 7), (3, 256, 3), (2, 32, 9), (0, 64, 11)]
+    res, c0, c1 = _check_batch_against_oracle(isr, m, om, xs, items, 13, 57, seed=6)
+    for i, (img, sigma, image_id) in enumerate(items):
+        one, s0, s1 = isr.isr_certify(m, xs[img], sigma, 13, 57, ALPHA, seed=6, image_id=image_id)
+        assert np.array_equal(s0, c0[i]) and np.array_equal(s1, c1[i])
+    lg, am, cnt = isr.isr_debug_forward(m, xs[1], 128, 9, 4, 1, 99990, 37)
+    olg, oam, ocnt = om.mc(xs[1], 128, 9, 4, 1, 99990, 37)
+    assert np.array_equal(lg, olg) and np.array_equal(cnt, ocnt)
+    isr.isr_set_fusion(m, False)
+    lg2, _, _ = isr.isr_debug_forward(m, xs[1], 128, 9, 4, 1, 99990, 37)
+    assert np.array_equal(lg2, olg)
+    # the noisy copy itself is still available through the debug hook (the separate noise kernel)
+    isr.isr_set_fusion(m, True)
+    got = isr.isr_debug_noisy(m, xs[2], 64, 6, 9, 1, 5, 3)
+    for s in range(3):
+        assert np.array_equal(got[s], oracle.noisy(xs[2], 64, 6, 9, 1, 5 + s))
+    m.close()
+
+
 def test_batched_call_argument_errors(isr):
     blob = synth.build_model(0)
     m = _load(isr, blob, 32)
