@@ -228,12 +228,24 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
                     bp.lo2 = c2.relu ? c2.zp_out : -128;
                     bp.tie_free = c1.tie_free && c2.tie_free;
                     if (bp.tail) {
-                        bp.w3 = c3.w; bp.bias3 = c3.bias; bp.m0s3 = c3.m0s; bp.chi3 = c3.chi; bp.shm13 = c3.shm1;
+                        // the closing 1x1 convolution; with a projection shortcut (bneck == 4) conv3 carries two
+                        // convolutions, and either of them may be the one that reads the block input
+                        const bool swap = d.bneck == 4 && d.proj_is_main;
+                        bp.w3 = swap ? c3.w2 : c3.w; bp.bias3 = swap ? c3.bias2 : c3.bias; bp.m0s3 = swap ? c3.m0s2 : c3.m0s;
+                        bp.chi3 = swap ? c3.chi2 : c3.chi; bp.shm13 = swap ? c3.shm12 : c3.shm1;
                         bp.Cout_p = c3.Cout_p;
-                        bp.lo3 = c3.relu ? c3.zp_out : -128;
-                        bp.add_mul_self = c3.add_mul_self; bp.add_mul_res = c3.add_mul_res; bp.add_c0 = c3.add_c0;
-                        bp.add_k = c3.add_k; bp.add_sh = c3.add_sh; bp.add_lo = c3.add_lo;
-                        bp.tie_free = bp.tie_free && c3.tie_free && c3.add_tie_free;
+                        const int lo_main = c3.relu ? c3.zp_out : -128;
+                        bp.lo3 = swap ? c3.lo2 : lo_main;
+                        bp.add_mul_self = swap ? c3.add_mul_res : c3.add_mul_self;   // "self" in the kernel = the closing convolution
+                        bp.add_mul_res = swap ? c3.add_mul_self : c3.add_mul_res;
+                        bp.add_c0 = c3.add_c0; bp.add_k = c3.add_k; bp.add_sh = c3.add_sh; bp.add_lo = c3.add_lo;
+                        bp.tie_free = bp.tie_free && c3.tie_free && c3.add_tie_free && (d.bneck != 4 || c3.tie_free2);
+                        if (d.bneck == 4) {
+                            bp.proj = 1;
+                            bp.wp = swap ? c3.w : c3.w2; bp.biasp = swap ? c3.bias : c3.bias2; bp.m0sp = swap ? c3.m0s : c3.m0s2;
+                            bp.chip = swap ? c3.chi : c3.chi2; bp.shm1p = swap ? c3.shm1 : c3.shm12;
+                            bp.lop = swap ? lo_main : c3.lo2;
+                        }
                     }
                     if (d.bneck == 3) HIP_TRY(launch_bottleneck128(bp, m->stream));
                     else HIP_TRY(launch_bottleneck(bp, m->stream));

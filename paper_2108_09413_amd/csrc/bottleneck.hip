@@ -36,14 +36,18 @@ constexpr int NH_FR = 10;                      // fragments (of 32 GEMM columns)
 constexpr int NP_FR = 7;                       // fragments covering the 224 output pixels, all full
 constexpr int W2_CHUNKS = 37;                  // 16-byte chunks per 3x3 weight row in LDS: 36 + 1 pad (bank spread)
 
-template <bool TAIL, bool TF>
+// MODE 0: head (t2 stored); 1: whole identity block (residual = x); 2: whole first block of a stage --
+// the residual is itself a 1x1 convolution of x (projection shortcut, Cin = 64), computed here as well.
+template <int MODE, bool TF>
 __global__ __launch_bounds__(256, 2) void bottleneck_kernel(const BneckParams p) {
+    constexpr bool TAIL = MODE != 0, PROJ = MODE == 2;
     constexpr int KB = 64, STAGE = (64 + 32 * NH_FR) * KB;            // 64 weight rows + 320 pixel rows per stage
     static_assert(64 * W2_CHUNKS * 16 <= 2 * STAGE, "3x3 weights fit the operand stages");
     __shared__ __attribute__((aligned(16))) int8_t Ls[2 * STAGE];     // step 1: two stages (A rows, then B rows); step 3: 3x3 weights
     __shared__ __attribute__((aligned(16))) int8_t T[32 * NH_FR * 64]; // t1: [halo pixel][channel chunk ^ swizzle]; later t2: [output pixel][...]
     __shared__ int prm[2][4][64];                                     // bias, M0, chi, shift-1 of the first two convolutions
     __shared__ __attribute__((aligned(16))) int prm3[TAIL ? 4 : 1][TAIL ? 256 : 4];
+    __shared__ __attribute__((aligned(16))) int prmp[PROJ ? 4 : 1][PROJ ? 256 : 4];   // the same for the projection
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l = lane & 31, half = lane >> 5;
@@ -67,6 +71,7 @@ __global__ __launch_bounds__(256, 2) void bottleneck_kernel(const BneckParams p)
     if constexpr (TAIL)
         for (int i = tid; i < p.Cout_p; i += 256) {
             prm3[0][i] = p.bias3[i]; prm3[1][i] = p.m0s3[i]; prm3[2][i] = p.chi3[i]; prm3[3][i] = p.shm13[i];
+            if constexpr (PROJ) { prmp[0][i] = p.biasp[i]; prmp[1][i] = p.m0sp[i]; prmp[2][i] = p.chip[i]; prmp[3][i] = p.shm1p[i]; }
         }
 
     // ---- step 1: t1 accumulators over the halo, K = Cin_p in steps of 64 ----
@@ -112,7 +117,9 @@ __global__ __launch_bounds__(256, 2) void bottleneck_kernel(const BneckParams p)
     // which are exactly the input channels of K step w of this GEMM: while that step's pixel rows sit in the
     // LDS stage the wave copies its residual values (its 64 channels of the seven fragments' pixels) into
     // registers, so x is not read from memory a second time.
-    v4i resid[TAIL ? NP_FR : 1][2];
+    // (With a projection shortcut x has only 64 channels and is the pixel operand of a second GEMM: it is
+    // read again from memory -- cache hits, a fifth of the block's traffic at most -- rather than held in 56 registers.)
+    v4i resid[MODE == 1 ? NP_FR : 1][2];
     {
         int aoff[2], boffs[2][5];   // [K half of the step][fragment]
 #pragma unroll
@@ -132,7 +139,7 @@ __global__ __launch_bounds__(256, 2) void bottleneck_kernel(const BneckParams p)
             __builtin_amdgcn_s_barrier();   // every wave's loads of step ks landed; every wave is done with step ks - 1
             if (ks >= 1 && ks + 1 < nk) issue(ks + 1, (ks + 1) & 1);
             const int8_t *base = &Ls[(ks & 1) * STAGE];
-            if constexpr (TAIL) {
+            if constexpr (MODE == 1) {
                 if (ks == wave) {   // wave-uniform
 #pragma unroll
                     for (int f = 0; f < NP_FR; ++f) {
@@ -259,22 +266,57 @@ __global__ __launch_bounds__(256, 2) void bottleneck_kernel(const BneckParams p)
         ConvParams ap{};   // the fused add reads its constants from here
         ap.add_mul_self = p.add_mul_self; ap.add_mul_res = p.add_mul_res; ap.add_c0 = p.add_c0; ap.add_k = p.add_k;
         ap.add_sh = p.add_sh; ap.add_lo = p.add_lo;
-        long opix[NP_FR];   // element offset of the lane's pixel of fragment f in x and y; -1: outside the image
-        v4i fbt[NP_FR][2];  // the lane's pixel operands (64 channels of t2 = two K halves) of every fragment
+        int opix[NP_FR];    // index (image, row, column) of the lane's pixel of fragment f; -1: outside the image
+        v4i fbt[PROJ ? 1 : NP_FR][2];  // the lane's pixel operands (64 channels of t2 = two K halves) of every fragment
 #pragma unroll
         for (int f = 0; f < NP_FR; ++f) {
             const int o = f * 32 + l, oy = o / TW, ox = o - oy * TW;
             const bool st = oy0 + oy < p.H && ox0 + ox < p.W;
-            opix[f] = st ? (((long)b * p.H + oy0 + oy) * p.W + ox0 + ox) * p.Cout_p : -1;
+            opix[f] = st ? ((b * p.H + oy0 + oy) * p.W + ox0 + ox) : -1;
+            if constexpr (!PROJ) {
 #pragma unroll
-            for (int ksub = 0; ksub < 2; ++ksub) fbt[f][ksub] = *(const v4i *)(&T[o * 64 + (((ksub * 2 + half) ^ swz<4>(o)) << 4)]);
+                for (int ksub = 0; ksub < 2; ++ksub) fbt[f][ksub] = *(const v4i *)(&T[o * 64 + (((ksub * 2 + half) ^ swz<4>(o)) << 4)]);
+            }
         }
         // this wave's 64 output channels (Cout <= 256 = four waves x 64): two groups of 32
         const int nmf = p.Cout_p >> 5;   // 32-channel groups of the output
-        if (2 * wave < nmf) {
+        // one group of 32 output channels; mi is a compile-time constant for the identity block (it selects
+        // registers of the residual copy) and a loop variable for the projection block
+        auto channel_group = [&](auto mi) {
+            {
+                const int m0 = (2 * wave + (int)mi) * 32, c0 = m0 + 16 * half;   // the lane's 16 channels
+                v4i rpack[NP_FR];   // the residual of every fragment, packed int8
+                if constexpr (PROJ) {
+                    // projection shortcut first: r = clamp(requant(Wp x)), kept packed
+                    v4i fp[2];
 #pragma unroll
-            for (int mi = 0; mi < 2; ++mi) {
-                const int m0 = (2 * wave + mi) * 32, c0 = m0 + 16 * half;   // the lane's 16 channels
+                    for (int ksub = 0; ksub < 2; ++ksub) fp[ksub] = *(const v4i *)(p.wp + (long)(m0 + l) * 64 + ksub * 32 + half * 16);
+                    int mm[16], ch[16], ss[16];
+                    v16i init;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) { init[i] = prmp[0][c0 + i]; mm[i] = prmp[1][c0 + i]; ch[i] = prmp[2][c0 + i]; ss[i] = prmp[3][c0 + i]; }
+                    v4i xn[2];   // x at the lane's pixel of the next fragment (pixels outside the image read pixel 0: in bounds, unused)
+#pragma unroll
+                    for (int ksub = 0; ksub < 2; ++ksub) xn[ksub] = *(const v4i *)(p.in + (long)(opix[0] >= 0 ? opix[0] : 0) * 64 + ksub * 32 + half * 16);
+#pragma unroll
+                    for (int f = 0; f < NP_FR; ++f) {
+                        const v4i x0 = xn[0], x1 = xn[1];
+                        if (f + 1 < NP_FR) {
+#pragma unroll
+                            for (int ksub = 0; ksub < 2; ++ksub) xn[ksub] = *(const v4i *)(p.in + (long)(opix[f + 1] >= 0 ? opix[f + 1] : 0) * 64 + ksub * 32 + half * 16);
+                        }
+                        v16i a = __builtin_amdgcn_mfma_i32_32x32x32_i8(fp[0], x0, init, 0, 0, 0);
+                        a = __builtin_amdgcn_mfma_i32_32x32x32_i8(fp[1], x1, a, 0, 0, 0);
+                        int q[16];
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) q[i] = clamp3(requant_q<TF>(a[i], mm[i], ch[i], ss[i]), p.lop, 127);
+                        rpack[f] = v4i{(int)pack4(q[0], q[1], q[2], q[3]), (int)pack4(q[4], q[5], q[6], q[7]),
+                                       (int)pack4(q[8], q[9], q[10], q[11]), (int)pack4(q[12], q[13], q[14], q[15])};
+                    }
+                } else {
+#pragma unroll
+                    for (int f = 0; f < NP_FR; ++f) rpack[f] = resid[f][decltype(mi)::value];
+                }
                 v4i fa[2];
 #pragma unroll
                 for (int ksub = 0; ksub < 2; ++ksub) fa[ksub] = *(const v4i *)(p.w3 + (long)(m0 + l) * 64 + ksub * 32 + half * 16);
@@ -284,9 +326,17 @@ __global__ __launch_bounds__(256, 2) void bottleneck_kernel(const BneckParams p)
                 for (int i = 0; i < 16; ++i) { init[i] = prm3[0][c0 + i]; mm[i] = prm3[1][c0 + i]; ch[i] = prm3[2][c0 + i]; ss[i] = prm3[3][c0 + i]; }
 #pragma unroll
                 for (int f = 0; f < NP_FR; ++f) {
-                    const v4i res = resid[f][mi];
-                    v16i a = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[0], fbt[f][0], init, 0, 0, 0);
-                    a = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[1], fbt[f][1], a, 0, 0, 0);
+                    const v4i res = rpack[f];
+                    v4i fb[2];
+                    if constexpr (PROJ) {   // the pixel operands are re-read from the t2 tile: the registers hold x
+                        const int o = f * 32 + l;
+#pragma unroll
+                        for (int ksub = 0; ksub < 2; ++ksub) fb[ksub] = *(const v4i *)(&T[o * 64 + (((ksub * 2 + half) ^ swz<4>(o)) << 4)]);
+                    } else {
+                        fb[0] = fbt[f][0]; fb[1] = fbt[f][1];
+                    }
+                    v16i a = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[0], fb[0], init, 0, 0, 0);
+                    a = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[1], fb[1], a, 0, 0, 0);
                     int q[16];
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
@@ -295,9 +345,18 @@ __global__ __launch_bounds__(256, 2) void bottleneck_kernel(const BneckParams p)
                         q[i] = fused_add<TF>(qc, r8, ap);
                     }
                     if (opix[f] >= 0)
-                        *(v4i *)(p.out + opix[f] + c0) = v4i{(int)pack4(q[0], q[1], q[2], q[3]), (int)pack4(q[4], q[5], q[6], q[7]),
+                        *(v4i *)(p.out + (long)opix[f] * p.Cout_p + c0) = v4i{(int)pack4(q[0], q[1], q[2], q[3]), (int)pack4(q[4], q[5], q[6], q[7]),
                                                             (int)pack4(q[8], q[9], q[10], q[11]), (int)pack4(q[12], q[13], q[14], q[15])};
                 }
+            }
+        };
+        if (2 * wave < nmf) {
+            if constexpr (PROJ) {
+#pragma unroll 1
+                for (int mi = 0; mi < 2; ++mi) channel_group(mi);
+            } else {
+                channel_group(std::integral_constant<int, 0>{});
+                channel_group(std::integral_constant<int, 1>{});
             }
         }
     }
@@ -310,25 +369,33 @@ __global__ __launch_bounds__(256, 2) void bottleneck_kernel(const BneckParams p)
 // channel count (at most 256) with the block input as residual.
 bool bottleneck_supported(int cin_p, int cmid_p, int cout_p, int tail) {
     if (cin_p % 64 != 0 || cin_p < 64 || cin_p > 1024 || cmid_p != 64) return false;
+    if (tail == 2) return cin_p == 64 && cout_p % 64 == 0 && cout_p >= 64 && cout_p <= 256;   // projection shortcut from 64 channels
     return !tail || (cout_p == cin_p && cout_p <= 256);
 }
 
 hipError_t launch_bottleneck(const BneckParams &p, hipStream_t st) {
     if (p.B <= 0) return hipSuccess;
     if (!p.in || !p.out || !p.w1 || !p.w2 || !p.zpad || p.H < 1 || p.W < 1 ||
-        !bottleneck_supported(p.Cin_p, 64, p.Cout_p, p.tail) || (p.tail && !p.w3))
+        !bottleneck_supported(p.Cin_p, 64, p.Cout_p, p.tail ? (p.proj ? 2 : 1) : 0) || (p.tail && !p.w3) ||
+        (p.proj && (!p.tail || !p.wp || !p.biasp || !p.m0sp || !p.chip || !p.shm1p)))
         return hipErrorInvalidValue;
     const long tiles = (long)p.B * ((p.H + TH - 1) / TH) * ((p.W + TW - 1) / TW);
     if (tiles > 0x7fffffffL || (long)p.B * p.H * p.W * (p.Cin_p > 64 ? p.Cin_p : 64) >= (1L << 31)) return hipErrorInvalidValue;
     const dim3 grid((unsigned)tiles), block(256);
-    set_kernel_name(p.tail ? (p.tie_free ? "bottleneck_kernel<true, true>" : "bottleneck_kernel<true, false>")
-                           : (p.tie_free ? "bottleneck_kernel<false, true>" : "bottleneck_kernel<false, false>"));
-    if (p.tail) {
-        if (p.tie_free) hipLaunchKernelGGL((bottleneck_kernel<true, true>), grid, block, 0, st, p);
-        else hipLaunchKernelGGL((bottleneck_kernel<true, false>), grid, block, 0, st, p);
+    const int mode = p.tail ? (p.proj ? 2 : 1) : 0;
+    static const char *const names[3][2] = {{"bottleneck_kernel<head, false>", "bottleneck_kernel<head, true>"},
+                                            {"bottleneck_kernel<block, false>", "bottleneck_kernel<block, true>"},
+                                            {"bottleneck_kernel<block + projection, false>", "bottleneck_kernel<block + projection, true>"}};
+    set_kernel_name(names[mode][p.tie_free ? 1 : 0]);
+    if (mode == 2) {
+        if (p.tie_free) hipLaunchKernelGGL((bottleneck_kernel<2, true>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((bottleneck_kernel<2, false>), grid, block, 0, st, p);
+    } else if (mode == 1) {
+        if (p.tie_free) hipLaunchKernelGGL((bottleneck_kernel<1, true>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((bottleneck_kernel<1, false>), grid, block, 0, st, p);
     } else {
-        if (p.tie_free) hipLaunchKernelGGL((bottleneck_kernel<false, true>), grid, block, 0, st, p);
-        else hipLaunchKernelGGL((bottleneck_kernel<false, false>), grid, block, 0, st, p);
+        if (p.tie_free) hipLaunchKernelGGL((bottleneck_kernel<0, true>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((bottleneck_kernel<0, false>), grid, block, 0, st, p);
     }
     return hipGetLastError();
 }

@@ -184,6 +184,11 @@ struct BneckParams {
     const int32_t *bias1, *m0s1, *chi1, *shm11;   // as in ConvParams, per convolution
     const int32_t *bias2, *m0s2, *chi2, *shm12;
     const int32_t *bias3, *m0s3, *chi3, *shm13;
+    // proj != 0 (with tail): the residual is not x but clamp(requant(conv1x1_p(x))), a projection shortcut
+    // from 64 input channels computed in the same kernel; its weights [>= Cout_p][64] and constants:
+    const int8_t *wp;
+    const int32_t *biasp, *m0sp, *chip, *shm1p;
+    int32_t proj, lop;       // lop: lower clamp of the projection's int8 result
     const int8_t *zpad;      // 16 readable bytes (source of halo pixels outside the image)
     int32_t Cin_p, Cout_p, H, W, B, tail;
     int32_t zp_t1;           // zero-point of the first convolution's output (padding value of the 3x3)

@@ -331,6 +331,25 @@ void fuse_bottlenecks(const ParsedModel &pm, std::vector<DevOp> &ops, bool wide)
             a.out = cc.out;
         }
         ops.erase(ops.begin() + i + 1, ops.begin() + i + (tail ? 3 : 2));
+        // First block of a stage: the head is followed by the closing 1x1 convolution whose residual is a
+        // projection 1x1 convolution of the block input (already folded into one dual-convolution op): when the
+        // block input has 64 stored channels the whole block runs in the bottleneck kernel.
+        if (a.bneck == 1 && i + 1 < ops.size()) {
+            const DevOp &m = ops[i + 1];
+            const ConvParams &c3 = m.conv;
+            if (m.type == OP_CONV && !m.stem_pool && !m.stem16 && !m.block && !m.trans && !m.bneck && c3.fuse_add == 2 &&
+                c3.k == 1 && c3.stride == 1 && c3.pad == 0 && c3.Cin_p == 64 && c3.Kp == 64 && c3.Cin2_p == 64 && c3.fast_requant &&
+                ((m.a == a.out && m.b == a.a) || (m.a == a.a && m.b == a.out)) && uses[a.out] == 1 && c1.Cin_p == 64 &&
+                bottleneck_supported(64, 64, c3.Cout_p, 2)) {
+                a.bneck = 4;
+                a.proj_is_main = m.a == a.a;   // which of the dual op's two convolutions reads the block input
+                a.conv3 = c3;
+                a.ops_per_sample += m.ops_per_sample;
+                a.bytes_per_sample = (double)pm.tensors[a.a].C * c1.H * c1.W + (double)pm.tensors[m.out].C * c1.H * c1.W;
+                a.out = m.out;
+                ops.erase(ops.begin() + i + 1);
+            }
+        }
     }
 }
 

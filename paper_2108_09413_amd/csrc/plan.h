@@ -22,7 +22,8 @@ struct DevOp {
     std::vector<std::pair<ConvParams, ConvParams>> chain;   // block != 0: the blocks of the chain this op runs (each feeds the next)
     size_t chain_off = 0;               // first BlockDesc of the chain in the model's device array
     int trans = 0;                      // down-sampling block: this conv (3x3/2), conv2 (3x3) and conv3 (1x1/2 + add) in one kernel
-    int bneck = 0;                      // 1: this 1x1 conv and the 3x3 conv2 in one kernel; 2: plus conv3 (1x1 + residual add); 3: as 2 with 128 middle channels
+    int bneck = 0;                      // 1: this 1x1 conv and the 3x3 conv2 in one kernel; 2: plus conv3 (1x1 + residual add); 3: as 2 with 128 middle channels; 4: as 2 with the residual computed by a projection 1x1 convolution of the block input (conv3 carries it as its second convolution)
+    int proj_is_main = 0;               // bneck == 4: conv3's first convolution is the projection of the block input, its second the closing 1x1
     ConvParams conv2{};
     ConvParams conv3{};
     AddParams add{};
