@@ -18,6 +18,7 @@
  *     Philox4x32-10 word pair addressed by (seed, image, phase, sample, pixel);
  *   - x + delta is saturated to [0, 255] before the network sees it.
  */
+#include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -492,5 +493,258 @@ int isr_oracle_mc(const omodel *m, const uint8_t *x, uint32_t sigma, uint64_t se
         if (counts) counts[am[s]] += 1;
     }
     free(am); free(T);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* The two floating-point comparison systems of the paper's evaluation       */
+/* (section "Experiments": FloatRS-quant and FloatRS-fp): standard           */
+/* randomized smoothing with continuous Gaussian noise N(0, sigma^2 I),      */
+/*   FloatRS-quant: the noisy image is rounded back onto the 8-bit pixel     */
+/*                  grid and classified by the quantized network;            */
+/*   FloatRS-fp:    the noisy image is classified by the float network.      */
+/* The paper fixes the law only.  How a counter turns into a float32 normal  */
+/* draw is this build's specification, written so that every step is an      */
+/* IEEE-754 binary32 operation (+, -, *, /, sqrt, each rounded once, none    */
+/* contracted) and therefore has one result on every conforming machine:     */
+/*   Philox4x32-10, counter (p >> 2, sample, image, 8 + phase), key = seed;  */
+/*   words (w0, w1) give the draws of elements p&3 = 0, 1, words (w2, w3)    */
+/*   those of elements 2, 3 by the Box-Muller transform                      */
+/*   z_a = sqrt(-2 ln u) cos(2 pi v), z_b = sqrt(-2 ln u) sin(2 pi v) with   */
+/*   u = ((w_a >> 8) + 1) / 2^24 in (0, 1], v = (w_b >> 8) / 2^24 in [0, 1); */
+/*   ln by range reduction to [sqrt(1/2), sqrt(2)] and the atanh series,     */
+/*   cos / sin by octant and the Taylor polynomials on [0, pi/4).            */
+
+static float f32_from_bits(uint32_t b) { float f; memcpy(&f, &b, 4); return f; }
+static uint32_t f32_bits(float f) { uint32_t b; memcpy(&b, &f, 4); return b; }
+
+/* -ln(n / 2^24) for an integer n in [1, 2^24], in binary32 steps. */
+float isr_oracle_neg_log_u24(uint32_t n) {
+    float f = (float)n;                       /* exact: n <= 2^24 */
+    uint32_t bits = f32_bits(f);
+    int32_t E = (int32_t)(bits >> 23) - 127;  /* n = m 2^E, m in [1, 2) */
+    float m = f32_from_bits((bits & 0x7FFFFFu) | 0x3F800000u);
+    if (m > 1.41421354f) { m = m * 0.5f; E += 1; }
+    float k = (float)(24 - E);
+    float s = (m - 1.0f) / (m + 1.0f);        /* ln m = 2 atanh(s), |s| <= 0.1716 */
+    float s2 = s * s;
+    float p = 0.222222224f;                   /* 2/9 */
+    p = p * s2; p = p + 0.285714298f;         /* 2/7 */
+    p = p * s2; p = p + 0.400000006f;         /* 2/5 */
+    p = p * s2; p = p + 0.666666687f;         /* 2/3 */
+    p = p * s2; p = p + 2.0f;
+    float lnm = s * p;
+    float a = k * 0.693145752f;               /* ln 2 = hi + lo; k * hi is exact */
+    float b = k * 1.42860677e-06f;
+    float d = a - lnm;
+    return d + b;
+}
+
+/* cos and sin of the angle 2 pi t / 2^24, t in [0, 2^24), in binary32 steps. */
+void isr_oracle_cos_sin_turn24(uint32_t t, float *cos_out, float *sin_out) {
+    uint32_t octant = t >> 21, q = t & 0x1FFFFFu;
+    float phi = (float)q * 3.74507039e-07f;   /* (pi/4) / 2^21: phi in [0, pi/4) */
+    float x2 = phi * phi;
+    float c = -2.755732e-07f;                 /* -1/10! */
+    c = c * x2; c = c + 2.48015876e-05f;      /*  1/8!  */
+    c = c * x2; c = c - 0.00138888892f;       /* -1/6!  */
+    c = c * x2; c = c + 0.0416666679f;        /*  1/4!  */
+    c = c * x2; c = c - 0.5f;
+    c = c * x2; c = c + 1.0f;
+    float s = 2.75573188e-06f;                /*  1/9!  */
+    s = s * x2; s = s - 0.000198412701f;      /* -1/7!  */
+    s = s * x2; s = s + 0.00833333377f;       /*  1/5!  */
+    s = s * x2; s = s - 0.166666672f;         /* -1/3!  */
+    s = s * x2; s = s + 1.0f;
+    s = s * phi;
+    float d = c - s, e = c + s;
+    d = d * 0.707106769f;                     /* cos(pi/4 + phi) */
+    e = e * 0.707106769f;                     /* sin(pi/4 + phi) */
+    switch (octant) {
+    case 0: *cos_out = c; *sin_out = s; break;
+    case 1: *cos_out = d; *sin_out = e; break;
+    case 2: *cos_out = -s; *sin_out = c; break;
+    case 3: *cos_out = -e; *sin_out = d; break;
+    case 4: *cos_out = -c; *sin_out = -s; break;
+    case 5: *cos_out = -d; *sin_out = -e; break;
+    case 6: *cos_out = s; *sin_out = -c; break;
+    default: *cos_out = e; *sin_out = -d; break;
+    }
+}
+
+/* The Box-Muller pair of two 32-bit words. */
+void isr_oracle_box_muller(uint32_t wa, uint32_t wb, float *za, float *zb) {
+    float l = isr_oracle_neg_log_u24((wa >> 8) + 1u);
+    float r = sqrtf(2.0f * l);
+    float c, s;
+    isr_oracle_cos_sin_turn24(wb >> 8, &c, &s);
+    *za = r * c;
+    *zb = r * s;
+}
+
+/* The four standard-normal draws of elements 4 group .. 4 group + 3 of one noisy copy. */
+void isr_oracle_gauss4(uint64_t seed, uint32_t image, uint32_t phase, uint32_t sample, uint32_t group, float z[4]) {
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t ctr[4] = {group, sample, image, 8u + phase};
+    uint32_t w[4];
+    isr_oracle_philox4x32_10(ctr, key, w);
+    isr_oracle_box_muller(w[0], w[1], &z[0], &z[1]);
+    isr_oracle_box_muller(w[2], w[3], &z[2], &z[3]);
+}
+
+/* v = x + sigma z for every element of one noisy copy (binary32: one product, one sum). */
+void isr_oracle_noisy_float(const uint8_t *x, uint32_t npix, float sigma, uint64_t seed, uint32_t image,
+                            uint32_t phase, uint32_t sample, float *v) {
+    for (uint32_t p = 0; p < npix; ++p) {
+        float z[4];
+        isr_oracle_gauss4(seed, image, phase, sample, p >> 2, z);
+        float sz = sigma * z[p & 3];
+        v[p] = (float)x[p] + sz;
+    }
+}
+
+/* FloatRS-quant input: the noisy value rounded to the nearest pixel level (ties to even),
+ * saturated to [0, 255], recentred like the integer path's input. */
+void isr_oracle_noisy_quant(const uint8_t *x, uint32_t npix, float sigma, uint64_t seed, uint32_t image,
+                            uint32_t phase, uint32_t sample, int8_t *a0) {
+    float *v = (float *)malloc((size_t)npix * sizeof(float));
+    isr_oracle_noisy_float(x, npix, sigma, seed, image, phase, sample, v);
+    for (uint32_t p = 0; p < npix; ++p) {
+        float r = rintf(v[p]);
+        if (r < 0.0f) r = 0.0f;
+        if (r > 255.0f) r = 255.0f;
+        a0[p] = (int8_t)((int32_t)r - 128);
+    }
+    free(v);
+}
+
+/* The float network behind a quantized one: every tensor holds the real values r = q - z that
+ * the int8 codes stand for, every op is the quantized op without its rounding and without its
+ * saturation at the ends of the int8 range (a ReLU stays: the lower clamp at the zero-point is
+ * r >= 0):
+ *   CONV     r_out = act(M (bias + sum over in-bounds taps of r_in w)), M = M0 2^-(31 + shift)
+ *   ADD      r_out = act((Ma r_a + Mb r_b) 2^-shift)
+ *   MAXPOOL  max over in-bounds taps;   GAP  r_out = M sum over H x W of r_in
+ *   FC       logits = bias + sum r_in w
+ * evaluated here in binary64.  The input is r_0 = v - 128 - z_0 for the noisy pixel values v. */
+static double act(double v, int32_t relu) { return relu && v < 0.0 ? 0.0 : v; }
+
+int isr_oracle_forward_float(const omodel *m, const float *v, double *acts, double *logits) {
+    size_t *off = (size_t *)malloc((size_t)m->nt * sizeof(size_t));
+    for (int i = 0; i < m->nt; ++i) off[i] = isr_oracle_tensor_offset(m, i);
+    size_t n0 = (size_t)m->C * m->H * m->W;
+    for (size_t i = 0; i < n0; ++i) acts[i] = (double)v[i] - 128.0 - (double)m->t[0].zp;
+    for (int i = 0; i < m->nops; ++i) {
+        const oop *o = &m->ops[i];
+        otensor ti = m->t[o->a], to = m->t[o->out];
+        const double *in = acts + off[o->a];
+        double *out = acts + off[o->out];
+        switch (o->type) {
+        case OP_CONV:
+            for (int oc = 0; oc < to.C; ++oc) {
+                double M = ldexp((double)o->M0[oc], -(31 + o->shift[oc]));
+                for (int oy = 0; oy < to.H; ++oy)
+                    for (int ox = 0; ox < to.W; ++ox) {
+                        double acc = (double)o->bias[oc];
+                        for (int ic = 0; ic < ti.C; ++ic)
+                            for (int ky = 0; ky < o->k; ++ky) {
+                                int iy = oy * o->stride - o->pad + ky;
+                                if (iy < 0 || iy >= ti.H) continue;
+                                for (int kx = 0; kx < o->k; ++kx) {
+                                    int ix = ox * o->stride - o->pad + kx;
+                                    if (ix < 0 || ix >= ti.W) continue;
+                                    acc += in[((size_t)ic * ti.H + iy) * ti.W + ix] *
+                                           (double)o->w[(((size_t)oc * ti.C + ic) * o->k + ky) * o->k + kx];
+                                }
+                            }
+                        out[((size_t)oc * to.H + oy) * to.W + ox] = act(acc * M, o->relu);
+                    }
+            }
+            break;
+        case OP_ADD: {
+            const double *b = acts + off[o->b];
+            size_t n = (size_t)to.C * to.H * to.W;
+            for (size_t j = 0; j < n; ++j)
+                out[j] = act(ldexp(in[j] * (double)o->Ma + b[j] * (double)o->Mb, -o->sh), o->relu);
+            break; }
+        case OP_MAXPOOL:
+            for (int c = 0; c < to.C; ++c)
+                for (int oy = 0; oy < to.H; ++oy)
+                    for (int ox = 0; ox < to.W; ++ox) {
+                        double best = 0.0;
+                        int any = 0;
+                        for (int ky = 0; ky < o->k; ++ky)
+                            for (int kx = 0; kx < o->k; ++kx) {
+                                int iy = oy * o->stride - o->pad + ky, ix = ox * o->stride - o->pad + kx;
+                                if (iy < 0 || iy >= ti.H || ix < 0 || ix >= ti.W) continue;
+                                double q = in[((size_t)c * ti.H + iy) * ti.W + ix];
+                                if (!any || q > best) { best = q; any = 1; }
+                            }
+                        out[((size_t)c * to.H + oy) * to.W + ox] = best;
+                    }
+            break;
+        case OP_GAP:
+            for (int c = 0; c < ti.C; ++c) {
+                double S = 0.0;
+                for (int j = 0; j < ti.H * ti.W; ++j) S += in[(size_t)c * ti.H * ti.W + j];
+                out[c] = S * ldexp((double)o->Ma, -(31 + o->sh));
+            }
+            break;
+        case OP_FC: {
+            int cin = ti.C * ti.H * ti.W;
+            for (int oc = 0; oc < to.C; ++oc) {
+                double acc = (double)o->bias[oc];
+                for (int j = 0; j < cin; ++j) acc += in[j] * (double)o->w[(size_t)oc * cin + j];
+                logits[oc] = acc;
+            }
+            break; }
+        }
+    }
+    free(off);
+    return 0;
+}
+
+/* Monte-Carlo loop of a comparison system over sample indices [begin, begin + count) of one
+ * phase.  variant 1 = FloatRS-quant (int32 logits into logits_i), 2 = FloatRS-fp (binary64
+ * logits into logits_d); the unused logits pointer, argmax and counts may be NULL. */
+int isr_oracle_mc_float(const omodel *m, const uint8_t *x, float sigma, uint64_t seed, uint32_t image,
+                        uint32_t phase, uint32_t begin, uint32_t count, int variant, int32_t *logits_i,
+                        double *logits_d, int32_t *argmax, uint32_t *counts, int threads) {
+    if (variant != 1 && variant != 2) return -1;
+    uint32_t npix = (uint32_t)(m->C * m->H * m->W);
+    size_t total = isr_oracle_tensor_offset(m, m->nt);
+    int32_t *am = (int32_t *)malloc((size_t)count * sizeof(int32_t));
+    if (threads < 1) threads = 1;
+#pragma omp parallel num_threads(threads)
+    {
+        int8_t *a0 = (int8_t *)malloc(npix);
+        float *v = (float *)malloc((size_t)npix * sizeof(float));
+        int8_t *acts = (int8_t *)malloc(variant == 1 ? total : 1);
+        double *facts = (double *)malloc((variant == 2 ? total : 1) * sizeof(double));
+        int32_t *lg = (int32_t *)malloc((size_t)m->classes * sizeof(int32_t));
+        double *lf = (double *)malloc((size_t)m->classes * sizeof(double));
+#pragma omp for schedule(dynamic, 1)
+        for (uint32_t s = 0; s < count; ++s) {
+            if (variant == 1) {
+                isr_oracle_noisy_quant(x, npix, sigma, seed, image, phase, begin + s, a0);
+                isr_oracle_forward(m, a0, acts, lg);
+                am[s] = isr_oracle_argmax(lg, m->classes);
+                if (logits_i) memcpy(logits_i + (size_t)s * m->classes, lg, (size_t)m->classes * sizeof(int32_t));
+            } else {
+                isr_oracle_noisy_float(x, npix, sigma, seed, image, phase, begin + s, v);
+                isr_oracle_forward_float(m, v, facts, lf);
+                int32_t best = 0;
+                for (int32_t c = 1; c < m->classes; ++c) if (lf[c] > lf[best]) best = c;
+                am[s] = best;
+                if (logits_d) memcpy(logits_d + (size_t)s * m->classes, lf, (size_t)m->classes * sizeof(double));
+            }
+        }
+        free(a0); free(v); free(acts); free(facts); free(lg); free(lf);
+    }
+    for (uint32_t s = 0; s < count; ++s) {
+        if (argmax) argmax[s] = am[s];
+        if (counts) counts[am[s]] += 1;
+    }
+    free(am);
     return 0;
 }
