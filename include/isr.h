@@ -167,6 +167,54 @@ int isr_noise_bank_static(uint32_t sigma, uint64_t seed, uint32_t bank_id, uint3
                           uint32_t d, int16_t *out_device, void *hip_stream);
 size_t isr_noise_bank_static_capacity(void);
 
+/* ---- the paper's floating-point comparison systems ------------------------- */
+
+/* Section "Experiments" compares integer randomized smoothing with standard randomized smoothing
+ * (continuous Gaussian noise N(0, sigma^2 I), radius sigma * Phi^-1(p_A)) in two forms:
+ *   ISR_FLOATRS_QUANT  the noisy image is rounded back onto the 8-bit pixel grid (nearest level,
+ *                      ties to even, saturated to [0, 255]) and classified by the int8 network;
+ *   ISR_FLOATRS_FP     the noisy image is classified by the fp32 network behind the quantized one:
+ *                      every tensor holds the real values r = q - z that the int8 codes stand for
+ *                      and every op is the blob's op without its rounding and without saturation at
+ *                      the ends of the int8 range (a ReLU clamp at the zero-point stays as r >= 0):
+ *                      CONV r_out = act(M (bias + sum r_in w)), M = M0 2^-(31 + shift);
+ *                      ADD act((Ma r_a + Mb r_b) 2^-shift); MAXPOOL; GAP M sum r_in; FC bias + sum r_in w;
+ *                      input r_0 = x + sigma z - 128 - z_0.  Arithmetic: fp32, accumulation on the
+ *                      fp32 matrix cores.
+ * Both run Alg. 1 as isr_certify does (same two loops, same decision on the tallies).  The noise of
+ * copy s, logical element p = (c*H + y)*W + x, is sigma * z with z the binary32 standard-normal draw
+ * of Philox4x32-10 counter (p >> 2, s, image_id, 8 + phase), key = seed, element p & 3: words
+ * (w0, w1) give elements 0 and 1, (w2, w3) elements 2 and 3 by the Box-Muller transform with
+ * u = ((w_a >> 8) + 1) / 2^24, v = (w_b >> 8) / 2^24, every step one IEEE binary32 operation, so
+ * the draws -- and with them the rounded inputs and the int8 logits of ISR_FLOATRS_QUANT -- are
+ * reproducible bit for bit; the fp32 logits of ISR_FLOATRS_FP are reproducible up to the rounding
+ * of fp32 sums.  sigma: any float in [0, 4096] (grid units).  radius_int / radius_sq_int of the
+ * result are 0.  ISR_FLOATRS_FP keeps fp32 copies of all weights on the device from its first use
+ * and processes isr_float_chunk() copies at a time inside the workspace of isr_set_workspace, which
+ * must hold isr_float_workspace_bytes() bytes (ISR_ERR_WORKSPACE otherwise); ISR_ERR_UNSUPPORTED
+ * for a model whose FC layer reads a non-square tensor. */
+#define ISR_FLOATRS_QUANT 1
+#define ISR_FLOATRS_FP 2
+size_t isr_float_workspace_bytes(isr_model *m, uint32_t chunk_samples, int system);
+uint32_t isr_float_chunk(const isr_model *m, int system);
+int isr_float_certify(isr_model *m, const uint8_t *x_device, float sigma, uint32_t n0, uint32_t n, double alpha,
+                      uint64_t seed, uint32_t image_id, int system, isr_result *out, uint32_t *counts0_host,
+                      uint32_t *counts1_host);
+/* Parity hooks of the comparison systems, as isr_debug_noisy / isr_debug_forward / isr_debug_tensor:
+ * out_host of isr_float_debug_noisy is int8 [count][C][H][W] (ISR_FLOATRS_QUANT: the rounded,
+ * recentred input) or float [count][C][H][W] (ISR_FLOATRS_FP: x + sigma z itself), count <=
+ * isr_float_chunk(); logits_host of isr_float_debug_forward is int32 resp. float [count][classes];
+ * isr_float_debug_tensor returns one tensor of the fp32 network as float [C][H][W]
+ * (ISR_ERR_UNSUPPORTED for a convolution output that only feeds a residual add: the add runs in
+ * that convolution's kernel and the tensor is never stored). */
+int isr_float_debug_noisy(isr_model *m, const uint8_t *x_device, float sigma, uint64_t seed, uint32_t image_id,
+                          uint32_t phase, uint32_t sample_begin, uint32_t count, int system, void *out_host);
+int isr_float_debug_forward(isr_model *m, const uint8_t *x_device, float sigma, uint64_t seed, uint32_t image_id,
+                            uint32_t phase, uint32_t sample_begin, uint32_t count, int system, void *logits_host,
+                            int32_t *argmax_host, uint32_t *counts_host);
+int isr_float_debug_tensor(isr_model *m, const uint8_t *x_device, float sigma, uint64_t seed, uint32_t image_id,
+                           uint32_t phase, uint32_t sample, int32_t tensor_id, float *out_host);
+
 /* ---- parity / resume hooks (sample-index ranges are reproducible) -------- */
 
 /* Noisy copies for sample indices [sample_begin, sample_begin+count) of one

@@ -25,7 +25,11 @@ EXPORTS = [
     "isr_decide_certify", "isr_decide_predict", "isr_discrete_quantile", "isr_set_fusion", "isr_set_conv_tile", "isr_profile", "isr_profile_read", "isr_strerror",
     "isr_last_device_error", "isr_certify_batch", "isr_predict_batch", "isr_certified_metrics", "isr_noise_bank",
     "isr_noise_bank_static", "isr_noise_bank_static_capacity",
+    "isr_float_workspace_bytes", "isr_float_chunk", "isr_float_certify", "isr_float_debug_noisy",
+    "isr_float_debug_forward", "isr_float_debug_tensor",
 ]
+
+FLOATRS_QUANT, FLOATRS_FP = 1, 2   # the paper's two floating-point comparison systems
 
 
 class IsrError(RuntimeError):
@@ -96,6 +100,15 @@ def lib():
         L.isr_noise_bank_static.argtypes = [u32, u64, u32, u32, u32, u32, vp, vp]
         L.isr_noise_bank_static_capacity.argtypes = []
         L.isr_noise_bank_static_capacity.restype = sz
+        flt = C.c_float
+        L.isr_float_workspace_bytes.argtypes = [vp, u32, C.c_int]
+        L.isr_float_workspace_bytes.restype = sz
+        L.isr_float_chunk.argtypes = [vp, C.c_int]
+        L.isr_float_chunk.restype = u32
+        L.isr_float_certify.argtypes = [vp, vp, flt, u32, u32, dbl, u64, u32, C.c_int, C.POINTER(Result), vp, vp]
+        L.isr_float_debug_noisy.argtypes = [vp, vp, flt, u64, u32, u32, u32, u32, C.c_int, vp]
+        L.isr_float_debug_forward.argtypes = [vp, vp, flt, u64, u32, u32, u32, u32, C.c_int, vp, vp, vp]
+        L.isr_float_debug_tensor.argtypes = [vp, vp, flt, u64, u32, u32, u32, i32, vp]
         L.isr_set_fusion.argtypes = [vp, C.c_int]
         L.isr_set_conv_tile.argtypes = [vp, C.c_int]
         L.isr_profile.argtypes = [vp, u32]
@@ -104,7 +117,8 @@ def lib():
         L.isr_strerror.restype = C.c_char_p
         L.isr_last_device_error.argtypes = []
         for name in EXPORTS:
-            if name not in ("isr_workspace_bytes", "isr_strerror", "isr_noise_bank_static_capacity"):
+            if name not in ("isr_workspace_bytes", "isr_strerror", "isr_noise_bank_static_capacity",
+                            "isr_float_workspace_bytes", "isr_float_chunk"):
                 getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -228,11 +242,14 @@ def isr_workspace_bytes(model: Model, chunk_samples: int) -> int:
     return int(lib().isr_workspace_bytes(model.handle, chunk_samples))
 
 
-def isr_set_workspace(model: Model, chunk_samples: int, stream=None):
+def isr_set_workspace(model: Model, chunk_samples: int, stream=None, float_fp: bool = False):
     """Allocates the device scratch as a torch uint8 tensor and hands it over
-    together with the current (or given) torch stream."""
+    together with the current (or given) torch stream.  float_fp: also large enough for the
+    fp32 network of the FloatRS-fp comparison system."""
     import torch
     need = isr_workspace_bytes(model, chunk_samples)
+    if float_fp:
+        need = max(need, int(lib().isr_float_workspace_bytes(model.handle, chunk_samples, FLOATRS_FP)))
     if need == 0:
         raise IsrError(ISR_ERR_ARG, "isr_workspace_bytes")
     ws = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
@@ -361,6 +378,54 @@ def isr_debug_tensor(model: Model, x, sigma: int, seed: int, image_id: int, phas
     out = np.zeros(shape, dtype=np.int8)
     _check(lib().isr_debug_tensor(model.handle, C.c_void_p(x.data_ptr()), sigma, C.c_uint64(seed), image_id, phase,
                                   sample, tensor_id, _np_ptr(out)), "isr_debug_tensor")
+    return out
+
+
+def isr_float_chunk(model: Model, system: int) -> int:
+    return int(lib().isr_float_chunk(model.handle, system))
+
+
+def isr_float_certify(model: Model, x, sigma: float, n0: int, n: int, alpha: float, system: int, seed: int = 0,
+                      image_id: int = 0):
+    """Alg. 1 run by a comparison system (FLOATRS_QUANT / FLOATRS_FP).  Returns (result, counts0, counts1)."""
+    x = _dev_image(model, x)
+    res = Result()
+    c0 = np.zeros(model.classes, dtype=np.uint32)
+    c1 = np.zeros(model.classes, dtype=np.uint32)
+    _check(lib().isr_float_certify(model.handle, C.c_void_p(x.data_ptr()), C.c_float(sigma), n0, n, alpha, C.c_uint64(seed),
+                                   image_id, system, C.byref(res), _np_ptr(c0), _np_ptr(c1)), "isr_float_certify")
+    return res, c0, c1
+
+
+def isr_float_debug_noisy(model: Model, x, sigma: float, seed: int, image_id: int, phase: int, sample_begin: int,
+                          count: int, system: int):
+    x = _dev_image(model, x)
+    out = np.zeros((count, model.C, model.H, model.W), dtype=np.int8 if system == FLOATRS_QUANT else np.float32)
+    _check(lib().isr_float_debug_noisy(model.handle, C.c_void_p(x.data_ptr()), C.c_float(sigma), C.c_uint64(seed), image_id,
+                                       phase, sample_begin, count, system, _np_ptr(out)), "isr_float_debug_noisy")
+    return out
+
+
+def isr_float_debug_forward(model: Model, x, sigma: float, seed: int, image_id: int, phase: int, sample_begin: int,
+                            count: int, system: int, want_logits: bool = True):
+    x = _dev_image(model, x)
+    logits = None
+    if want_logits:
+        logits = np.zeros((count, model.classes), dtype=np.int32 if system == FLOATRS_QUANT else np.float32)
+    argmax = np.zeros(count, dtype=np.int32)
+    counts = np.zeros(model.classes, dtype=np.uint32)
+    _check(lib().isr_float_debug_forward(model.handle, C.c_void_p(x.data_ptr()), C.c_float(sigma), C.c_uint64(seed), image_id,
+                                         phase, sample_begin, count, system, _np_ptr(logits), _np_ptr(argmax),
+                                         _np_ptr(counts)), "isr_float_debug_forward")
+    return logits, argmax, counts
+
+
+def isr_float_debug_tensor(model: Model, x, sigma: float, seed: int, image_id: int, phase: int, sample: int,
+                           tensor_id: int, shape):
+    x = _dev_image(model, x)
+    out = np.zeros(shape, dtype=np.float32)
+    _check(lib().isr_float_debug_tensor(model.handle, C.c_void_p(x.data_ptr()), C.c_float(sigma), C.c_uint64(seed), image_id,
+                                        phase, sample, tensor_id, _np_ptr(out)), "isr_float_debug_tensor")
     return out
 
 

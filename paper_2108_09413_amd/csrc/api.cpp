@@ -9,6 +9,7 @@
 #include <string>
 
 #include "isr_internal.h"
+#include "model.h"
 #include "plan.h"
 
 using namespace isr;
@@ -26,8 +27,6 @@ thread_local int g_last_hip_error = 0;
         }                                                 \
     } while (0)
 
-constexpr int TABLE_SLOTS = 8;
-
 }  // namespace
 
 void isr::set_last_device_error(int hip_error) { g_last_hip_error = hip_error; }
@@ -36,35 +35,6 @@ namespace { thread_local const char *g_kernel_name = ""; }
 void isr::set_kernel_name(const char *name) { g_kernel_name = name; }
 const char *isr::last_kernel_name() { return g_kernel_name; }
 
-struct isr_model {
-    ParsedModel pm;
-    std::vector<DevOp> ops;             // one descriptor per op of the blob
-    Plan plan[3];                       // [0] op by op, [1] with the fusions that pay, [2] with every fusion the kernels cover
-    int use_fused = 1;
-    int conv_tile = 0;                  // forced conv output tile (0 = automatic)
-    uint8_t *dconst = nullptr;          // weights and per-channel tables
-    DeviceNoiseTable *dtables = nullptr;  // TABLE_SLOTS entries
-    DeviceNoiseTable *htables = nullptr;  // pinned staging, TABLE_SLOTS entries
-    uint32_t table_sigma[TABLE_SLOTS] = {0};
-    int table_next = 0;
-    uint32_t *dcounts = nullptr;        // 2 * classes
-    uint32_t *hcounts = nullptr;        // pinned, 2 * classes
-    BlockDesc *dblocks = nullptr;       // descriptors of the identity-block chains of plan[1] and plan[2]
-    // batched calls: item descriptors and per-item vote counters, grown on demand
-    NoiseItem *ditems = nullptr, *hitems = nullptr;
-    uint32_t *dcounts_b = nullptr, *hcounts_b = nullptr;   // 2 * items_cap * classes each
-    uint32_t items_cap = 0;
-    // workspace
-    uint8_t *ws = nullptr;
-    size_t ws_bytes = 0;
-    uint32_t chunk = 0;
-    hipStream_t stream = nullptr;
-    // per-kernel timing
-    uint32_t profile_every = 0;
-    uint64_t chunk_counter = 0;
-    std::vector<hipEvent_t> events;
-    std::map<std::string, isr_kernel_stat> stats;   // per kernel instance (name as a profiler prints it)
-};
 
 namespace {
 
@@ -141,7 +111,15 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
                 np.item_count = (uint32_t)((s0 + bn - 1) / bc->n_per_item) - np.item_first + 1;
             }
             if ((prc = mark()) != ISR_OK) return prc;
-            HIP_TRY(launch_noise(np, m->stream));
+            if (m->quant_sigma >= 0.f) {   // FloatRS-quant: continuous noise rounded onto the pixel grid (single pair only)
+                FloatNoiseParams fp{};
+                fp.x = x; fp.out = np.out; fp.C = pm.C; fp.H = pm.H; fp.W = pm.W;
+                fp.key0 = np.key0; fp.key1 = np.key1; fp.image = image; fp.phase = phase;
+                fp.sample_begin = np.sample_begin; fp.count = bn; fp.sigma = m->quant_sigma; fp.center = 0.f; fp.quant = 1;
+                HIP_TRY(launch_float_noise(fp, m->stream));
+            } else {
+                HIP_TRY(launch_noise(np, m->stream));
+            }
             ev_work.push_back({last_kernel_name(), 0, 0.0, (double)bn * pm.H * pm.W * 4});
             return ISR_OK;
         };
@@ -159,9 +137,9 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
                     sp.w = d.conv.w; sp.bias = d.conv.bias; sp.m0s = d.conv.m0s; sp.chi = d.conv.chi; sp.shm1 = d.conv.shm1;
                     sp.H = d.conv.H; sp.W = d.conv.W; sp.Ho = d.conv.Ho; sp.Wo = d.conv.Wo; sp.Hp = to.H; sp.Wp = to.W;
                     sp.zp_in = d.conv.zp_in; sp.zp_out = d.conv.zp_out; sp.relu = d.conv.relu; sp.tie_free = d.conv.tie_free; sp.B = (int32_t)bn;
-                    sp.fused_noise = d.noise_fused;
+                    sp.fused_noise = d.noise_fused && m->quant_sigma < 0.f;
                     sp.noise = NoiseSource{};
-                    if (d.noise_fused) {
+                    if (sp.fused_noise) {
                         NoiseSource &ns = sp.noise;
                         ns.x = x; ns.table = table; ns.items = nullptr;
                         ns.key0 = (uint32_t)seed; ns.key1 = (uint32_t)(seed >> 32);
@@ -318,7 +296,7 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
             }
             if (op1 < op0) op1 = op0;
             // no noise launch when the first op of the plan draws its own input (and runs at all)
-            const bool own_noise = nops > 0 && !pl.ops.empty() && pl.ops[0].noise_fused;
+            const bool own_noise = nops > 0 && !pl.ops.empty() && pl.ops[0].noise_fused && m->quant_sigma < 0.f;
             for (uint32_t j0 = 0; j0 < cnt; j0 += sub) {
                 const uint32_t bn = std::min(sub, cnt - j0);
                 if (!noise_done && !own_noise && (prc = run_noise(j0, bn)) != ISR_OK) return prc;
@@ -358,6 +336,20 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
     }
     return ISR_OK;
 }
+
+}  // namespace
+
+int isr::run_quant_range(isr_model *m, const uint8_t *x, float sigma, uint64_t seed, uint32_t image, uint32_t phase,
+                         uint32_t begin, uint64_t count, int32_t *logits_host, int32_t *argmax_host, uint32_t *dcounts,
+                         int stop_tensor) {
+    m->quant_sigma = sigma;
+    const int rc = run_range(m, m->plan[m->use_fused], x, nullptr, seed, image, phase, begin, count, logits_host, argmax_host,
+                             dcounts, stop_tensor);
+    m->quant_sigma = -1.f;
+    return rc;
+}
+
+namespace {
 
 // Makes the tables of every sigma in `sigmas` resident at once (at most TABLE_SLOTS
 // distinct values) and returns the slot of each.
@@ -562,6 +554,7 @@ int isr_free_model(isr_model *m) {
     if (m->hitems) (void)hipHostFree(m->hitems);
     if (m->dcounts_b) (void)hipFree(m->dcounts_b);
     if (m->hcounts_b) (void)hipHostFree(m->hcounts_b);
+    free_float_net(m->fnet);
     delete m;
     return ISR_OK;
 }

@@ -272,6 +272,44 @@ struct NoiseBankParams {
     uint32_t key0, key1, bank, first, count;
 };
 
+// ---- floating-point comparison systems (float_path.hip) ------------------------------------
+// Continuous Gaussian noise: copy s, logical element p = (c*H + y)*W + x gets x[p] + sigma z with z the
+// standard-normal draw of counter (p >> 2, sample_begin + s, image, 8 + phase), element p & 3.
+struct FloatNoiseParams {
+    const uint8_t *x;        // [C][H][W] clean image
+    void *out;               // quant: int8 [B][H][W][4], clamp(round(v), 0, 255) - 128; else float [B][H][W][4], v - center
+    int32_t C, H, W;
+    uint32_t key0, key1, image, phase, sample_begin, count;
+    float sigma, center;
+    int32_t quant;
+};
+
+// fp32 convolution as an implicit GEMM on the fp32 MFMA, NHWC activations:
+//   t = act((bias + sum over in-bounds taps of in * w) * scale);  out = res ? act_add(ma * t + mb * res) : t
+struct FConvParams {
+    const float *in;         // [B][H][W][Cin_p]
+    float *out;              // [B][Ho][Wo][Cout_p]
+    const float *res;        // [B][Ho][Wo][Cout_p] or null
+    const float *w;          // [Kq][Cout_pp][4]: quad kq holds k = 4 kq .. 4 kq + 3 of K = (tap, channel); rows in MFMA row order per 32 channels
+    const float *bias, *scale;   // [Cout_pp], by channel
+    const int32_t *ktab;     // [Kq]: dy << 24 | dx << 16 | channel offset of the quad; -1 = padding quad
+    int32_t H, W, Cin_p, Ho, Wo, Cout_p, Cout_pp, stride, pad, Kq;   // Kq a multiple of 4
+    int32_t npix;            // B * Ho * Wo
+    int32_t relu, add_relu;
+    float ma, mb;
+};
+struct FAddParams { const float *a, *b; float *out; float ma, mb; int32_t relu; int64_t n4; };
+struct FPoolParams { const float *in; float *out; int32_t H, W, Cp, Ho, Wo, k, stride, pad, B; };
+struct FGapParams { const float *in; float *out; int32_t HW, Cp, B; float scale; };
+struct FVoteParams { const float *logits; int32_t classes, stride, B; int32_t *argmax; uint32_t *counts; };
+hipError_t launch_float_noise(const FloatNoiseParams &p, hipStream_t st);
+hipError_t launch_fconv(const FConvParams &p, hipStream_t st);
+int fconv_tile_m(int cout_p);   // channels per output tile chosen for a layer (Cout_pp is a multiple of it)
+hipError_t launch_fadd(const FAddParams &p, hipStream_t st);
+hipError_t launch_fmaxpool(const FPoolParams &p, hipStream_t st);
+hipError_t launch_fgap(const FGapParams &p, hipStream_t st);
+hipError_t launch_fvote(const FVoteParams &p, hipStream_t st);
+
 // Name of the kernel instance the last launcher call on this thread enqueued (template arguments
 // included, as a profiler prints them); the per-kernel timing report is keyed by it.
 void set_kernel_name(const char *name);
