@@ -156,6 +156,55 @@ def run_config(isr, synth, torch, cfg_id, chunk, steps, profile_every, n_overrid
     return dt, steps * batch * (n0 + n), stats, results[-1], ctx
 
 
+FP32_MFMA_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak
+
+
+def run_float_system(isr, synth, torch, cfg_id, chunk, system, n, steps, profile_every=4):
+    """The paper's floating-point comparison systems on the same workload: Alg. 1 with continuous
+    Gaussian noise, FloatRS-quant (int8 network on the rounded input) or FloatRS-fp (fp32 network).
+    One warm-up step with a short run, then `steps` timed steps of n0 + n inferences."""
+    cfg = synth.CONFIGS[cfg_id]
+    n0, alpha = cfg["n0"], 0.001
+    model = isr.isr_load_model(synth.build_model(cfg_id))
+    isr.isr_set_workspace(model, chunk, float_fp=(system == isr.FLOATRS_FP))
+    n_img = min(cfg["images"], 10)
+    images = [torch.from_numpy(synth.make_image(cfg_id, i + 1)).cuda() for i in range(n_img)]
+    pairs = [(i, s) for i in range(n_img) for s in cfg["sigmas"]]
+    isr.isr_float_certify(model, images[0], float(pairs[0][1]), n0, 4 * chunk, alpha, system)      # warm-up (fp32 weights are built here)
+    isr.isr_profile(model, profile_every)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        i, sg = pairs[k % len(pairs)]
+        last = isr.isr_float_certify(model, images[i], float(sg), n0, n, alpha, system, seed=0, image_id=i + 1)[0]
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    stats = isr.isr_profile_read(model) if profile_every else []
+    isr.isr_profile(model, 0)
+    fchunk = isr.isr_float_chunk(model, system)
+    model.close()
+    inferences = steps * (n0 + n)
+    all_ms = sum(st["total_ms"] for st in stats)
+    out = {"system": "FloatRS-quant" if system == isr.FLOATRS_QUANT else "FloatRS-fp", "config": cfg_id, "arch": cfg["arch"],
+           "n0": n0, "n": n, "steps": steps, "chunk_samples": fchunk,
+           "inferences_per_s": round(inferences / dt, 1), "ms_per_step": round(dt / steps * 1e3, 2),
+           "dtype": "int8" if system == isr.FLOATRS_QUANT else "f32",
+           "last_result": {"cls": last.cls, "radius": last.radius, "n_top": last.n_top}}
+    if system == isr.FLOATRS_FP and all_ms > 0:
+        conv = [st for st in stats if st["is_conv"]]
+        dom = max(conv, key=lambda st: st["total_ms"])
+        tf = dom["alg_ops"] / (dom["total_ms"] * 1e-3) / 1e12
+        ops, ms = sum(st["alg_ops"] for st in conv), sum(st["total_ms"] for st in conv)
+        out["roofline"] = {"bound": "mfma", "kernel": dom["name"], "achieved": round(tf, 2), "peak": FP32_MFMA_PEAK_TFLOPS,
+                           "unit": "TFLOP/s", "frac": round(tf / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                           "launches_timed": dom["launches"], "avg_launch_us": round(dom["total_ms"] * 1e3 / dom["launches"], 2),
+                           "time_share_of_all_kernels": round(dom["total_ms"] / all_ms, 4)}
+        out["all_conv_TFLOP/s"] = round(ops / (ms * 1e-3) / 1e12, 2)
+        out["all_conv_frac_of_fp32_peak"] = round(ops / (ms * 1e-3) / 1e12 / FP32_MFMA_PEAK_TFLOPS, 4)
+        out["per_kernel"] = kernel_table(stats, all_ms)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -170,6 +219,10 @@ def main():
                     help="(image, sigma) pairs per step; above 1 a step is one batched call over that many pairs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true", help="skip the short runs of the other workload configurations")
+    ap.add_argument("--no-comparison-systems", action="store_true",
+                    help="skip the short runs of the paper's floating-point comparison systems (FloatRS-quant, FloatRS-fp)")
+    ap.add_argument("--system", default="int", choices=["int", "quant", "fp"],
+                    help="int: the integer path (the headline metric); quant / fp: run only that comparison system on the workload")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference for HBM byte counters)")
     ap.add_argument("--profile-every", type=int, default=16,
@@ -190,6 +243,18 @@ def main():
         return bench_noise_bank(args, isr, torch)
     cfg_id, chunk, oracle_samples = WORKLOADS[args.workload]
     chunk = args.chunk or chunk
+    if args.system != "int":
+        system = isr.FLOATRS_QUANT if args.system == "quant" else isr.FLOATRS_FP
+        n = args.n or (synth.CONFIGS[cfg_id]["n"] if system == isr.FLOATRS_QUANT else 20000)
+        r = run_float_system(isr, synth, torch, cfg_id, chunk, system, n, args.steps, args.profile_every)
+        print(json.dumps({"metric": f"noisy {r['dtype']} inferences/sec ({r['system']})", "value": r["inferences_per_s"],
+                          "unit": "inferences/s", "n_gpus": 1, "steps": args.steps, "warmup": 1, "ms_per_step": r["ms_per_step"],
+                          "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": r["dtype"],
+                          "data": "synthetic", "config": {"workload": f"config {cfg_id}: {r['arch']}, {r['system']}, n0={r['n0']}, n={r['n']}",
+                                                          "chunk_samples": r["chunk_samples"]},
+                          "roofline": r.get("roofline"), "all_conv_TFLOP/s": r.get("all_conv_TFLOP/s"),
+                          "per_kernel": r.get("per_kernel"), "cpu_baseline": None, "last_result": r["last_result"]}))
+        return
 
     if args.copy_calibration_mib:
         # random (non-zero) source far larger than the caches, evicted from them by a second buffer first
@@ -262,6 +327,14 @@ def main():
                            "conv_frac_of_int8_peak": round(otops / INT8_MFMA_PEAK_TOPS, 4) if otops else None,
                            "last_result": {"cls": olast.cls, "radius": olast.radius, "n_top": olast.n_top}})
 
+    systems = None
+    if not args.no_comparison_systems and args.mode == "certify" and args.batch == 1:
+        # the paper's efficiency comparison (int8 against float inference, section "Efficiency Evaluation"), same GPU, same workload
+        systems = [run_float_system(isr, synth, torch, cfg_id, chunk, isr.FLOATRS_QUANT, n, 1, 0),
+                   run_float_system(isr, synth, torch, cfg_id, chunk, isr.FLOATRS_FP, min(n, 20000), 1, 4)]
+        for r in systems:
+            r["int8_path_speedup_over_it"] = round(value / r["inferences_per_s"], 3)
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -299,6 +372,7 @@ def main():
         "roofline_hbm": roofline_hbm,
         "per_kernel": table,
         "other_configs": others,
+        "comparison_systems": systems,
         "cpu_baseline": cpu,
         "paper_context": "int8 over fp32 on a desktop CPU: 3.5x (ResNet-20, 55.8 s vs 194.4 s per image at N = 100000) to "
                          "5.4x (ResNet-50): other hardware, not a target",
