@@ -166,11 +166,12 @@ def run_float_system(isr, synth, torch, cfg_id, chunk, system, n, steps, profile
     cfg = synth.CONFIGS[cfg_id]
     n0, alpha = cfg["n0"], 0.001
     model = isr.isr_load_model(synth.build_model(cfg_id))
-    isr.isr_set_workspace(model, chunk, float_fp=(system == isr.FLOATRS_FP))
+    # fp32 tensors take four times the bytes of a chunk's int8 tensors: a four times larger workspace keeps the copies per chunk
+    isr.isr_set_workspace(model, chunk * (4 if system == isr.FLOATRS_FP else 1), float_fp=(system == isr.FLOATRS_FP))
     n_img = min(cfg["images"], 10)
     images = [torch.from_numpy(synth.make_image(cfg_id, i + 1)).cuda() for i in range(n_img)]
     pairs = [(i, s) for i in range(n_img) for s in cfg["sigmas"]]
-    isr.isr_float_certify(model, images[0], float(pairs[0][1]), n0, 4 * chunk, alpha, system)      # warm-up (fp32 weights are built here)
+    isr.isr_float_certify(model, images[0], float(pairs[0][1]), n0, 2 * chunk, alpha, system)      # warm-up (fp32 weights are built here)
     isr.isr_profile(model, profile_every)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -300,7 +301,10 @@ def main():
             "bound": "mfma", "kernel": "all convolution kernel instances (see per_kernel)",
             "achieved": round(achieved, 2), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
             "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4),
-            "traffic": round(traffic["conv_per_inference"] * chunk / (conv_launches / max(sum(s["launches"] for s in stats if s["name"] == "noise_kernel"), 1)))
+            # HBM bytes of an average conv launch: bytes per inference x copies per chunk / conv launches per chunk
+            # (timed chunks = launches of a kernel that runs once per chunk)
+            "traffic": round(traffic["conv_per_inference"] * chunk /
+                             (conv_launches / max(max((s["launches"] for s in stats if s["name"].startswith("gap_kernel")), default=1), 1)))
             if traffic and chunk == 668 else None,
             "launches_timed": conv_launches, "avg_launch_us": round(conv_ms * 1e3 / max(conv_launches, 1), 2),
             "alg_ops_per_launch": round(conv_ops / max(conv_launches, 1)),

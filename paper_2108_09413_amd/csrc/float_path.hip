@@ -171,8 +171,13 @@ __global__ __launch_bounds__(256, 2) void fconv_kernel(const FConvParams p) {
     const int wm = wave % WM, wn = wave / WM;
     const int half = lane >> 5, l32 = lane & 31;
     const int mtiles = p.Cout_pp / BM;
-    const long bid = blockIdx.x;
-    const int ch0 = (int)(bid % mtiles) * BM;                  // channel tiles of one pixel tile are neighbours in launch order
+    // Workgroup ids are dealt round-robin over the 8 XCDs (each with its own L2): renumber them so that an XCD
+    // works on a contiguous run of tiles, in which the channel tiles of one pixel tile are neighbours and
+    // share that pixel tile through the XCD's L2.
+    const long nb = gridDim.x, per = nb >> 3, rem = nb & 7;
+    const long xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const long bid = xcd * per + (xcd < rem ? xcd : rem) + slot;   // XCD x owns per (+1 for x < rem) consecutive ids
+    const int ch0 = (int)(bid % mtiles) * BM;
     const long px0 = (bid / mtiles) * BN;
 
     const int bq = tid & 3;
