@@ -280,6 +280,17 @@ __global__ __launch_bounds__(256, 2) void bottleneck_kernel(const BneckParams p)
         }
         // this wave's 64 output channels (Cout <= 256 = four waves x 64): two groups of 32
         const int nmf = p.Cout_p >> 5;   // 32-channel groups of the output
+        // weight fragments of both groups, fetched before the first group's stores: a load issued behind stores
+        // waits for them as well (loads and stores share one counter)
+        v4i fa_pre[2][2];
+        if (2 * wave < nmf) {
+#pragma unroll
+            for (int g = 0; g < 2; ++g)
+#pragma unroll
+                for (int ksub = 0; ksub < 2; ++ksub) {
+                    fa_pre[g][ksub] = *(const v4i *)(p.w3 + (long)((2 * wave + g) * 32 + l) * 64 + ksub * 32 + half * 16);
+                }
+        }
         // one group of 32 output channels; mi is a compile-time constant for the identity block (it selects
         // registers of the residual copy) and a loop variable for the projection block
         auto channel_group = [&](auto mi) {
@@ -319,7 +330,7 @@ __global__ __launch_bounds__(256, 2) void bottleneck_kernel(const BneckParams p)
                 }
                 v4i fa[2];
 #pragma unroll
-                for (int ksub = 0; ksub < 2; ++ksub) fa[ksub] = *(const v4i *)(p.w3 + (long)(m0 + l) * 64 + ksub * 32 + half * 16);
+                for (int ksub = 0; ksub < 2; ++ksub) fa[ksub] = mi == 0 ? fa_pre[0][ksub] : fa_pre[1][ksub];
                 int mm[16], ch[16], ss[16];
                 v16i init;
 #pragma unroll

@@ -12,11 +12,14 @@ namespace isr {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-// 16-byte chunk swizzle inside an LDS row of CPR chunks: spreads equal chunk
-// indices of neighbouring rows over different banks for the 128-bit fragment reads
-// (8 consecutive rows must cover all 32 banks).
+// 16-byte chunk swizzle inside an LDS row of CPR chunks (64 or 128 bytes): spreads equal chunk indices of
+// neighbouring rows over different banks for the 128-bit fragment reads.  The LDS serves such a read 16
+// consecutive lanes at a time from 64 banks of 4 bytes, so 16 consecutive rows reading one logical chunk must
+// cover 256 bytes exactly once: the rows that share a 256-byte line (4 rows of 64 bytes, 2 of 128) keep the
+// chunk, each next group of rows moves it on by one (measured: as fast as contiguous reads; XOR with the
+// low row bits instead costs 13-14 % of the read rate).
 template <int CPR>
-__device__ __forceinline__ int swz(int row) { return CPR == 4 ? (((row >> 1) ^ (row >> 3)) & 3) : (row & 7); }
+__device__ __forceinline__ int swz(int row) { return CPR == 4 ? ((row >> 2) & 3) : ((row >> 1) & 7); }
 
 // RHA(acc * M0, 31 + shift) on magnitude and sign, 32x32->64 multiply-add:
 //   |acc| * (M0 << 1) + 2^(31+shift) = 2 * (|acc| * M0 + 2^(30+shift)),

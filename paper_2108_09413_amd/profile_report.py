@@ -4,10 +4,11 @@ The raw output (CSV files of `rocprofv3 --kernel-trace --stats` and `--pmc` runs
 produced on the GPU machine by the commands that each summary quotes; this script only reads those
 files and the JSON line bench.py printed in the same run.  Usage, from the repository root:
 
-    python -m paper_2108_09413_amd.profile_report --raw gpurun_out/profile
+    python -m paper_2108_09413_amd.profile_report --raw <directory>
 
 where the directory holds what the quoted commands wrote: stats/ fetch/ write/ mfma/ fp_stats/
-(rocprofv3 -d targets) and the *.log files with bench.py's output.  Missing parts are skipped.
+(rocprofv3 -d targets) and the *.log files with bench.py's output (stats.log, fp_stats.log).
+Missing parts are skipped.  The summaries quote the commands with the directory as given here.
 """
 from __future__ import annotations
 
@@ -74,6 +75,9 @@ def find(dirname, suffix):
     return hits[0] if hits else None
 
 
+RAW = "<raw>"   # the raw-output directory as named on the command line; quoted in the commands of each summary
+
+
 def kernel_stats(raw, sub, out_name, title, command, bench_log, peak, unit):
     path = find(os.path.join(raw, sub), "_kernel_stats.csv")
     if not path:
@@ -133,8 +137,8 @@ def hbm_traffic(raw, chunk=668, n=1236, n0=100):
     ninf = n + n0 + 8
     lines = ["# HBM traffic of the ResNet-50 int8 certification path (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)", "",
              "Commands (two runs, one counter each):", "",
-             "    " + PRE + "rocprofv3 --pmc FETCH_SIZE -d gpurun_out/profile/fetch -o f --output-format csv -- " + cmd,
-             "    " + PRE + "rocprofv3 --pmc WRITE_SIZE -d gpurun_out/profile/write -o w --output-format csv -- " + cmd, "",
+             "    " + PRE + "rocprofv3 --pmc FETCH_SIZE -d " + RAW + "/fetch -o f --output-format csv -- " + cmd,
+             "    " + PRE + "rocprofv3 --pmc WRITE_SIZE -d " + RAW + "/write -o w --output-format csv -- " + cmd, "",
              "sources_sha256: " + sources_sha256(), "",
              "Workload: one certification with n0=%d, n=%d (%d noisy inferences = two full chunks of %d) plus the 8 one-sample "
              "warm-up calls that upload the noise tables." % (n0, n, n + n0, chunk),
@@ -188,7 +192,7 @@ def mfma_utilisation(raw, chunk=668):
             agg[k][name] += v
     lines = ["# int8 MFMA utilisation of the convolution kernels (rocprofv3 --pmc)", "", "Command:", "",
              "    " + PRE + "rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES SQ_INSTS_VALU_MFMA_MOPS_I8 SQ_ACTIVE_INST_VALU "
-             "GRBM_GUI_ACTIVE -d gpurun_out/profile/mfma -o m --output-format csv -- " + BENCH_PMC, "",
+             "GRBM_GUI_ACTIVE -d " + RAW + "/mfma -o m --output-format csv -- " + BENCH_PMC, "",
              "sources_sha256: " + sources_sha256(), "",
              "Workload: one certification with n0=100, n=1236 (two full chunks of %d noisy ResNet-50/224 inferences) plus 8 one-sample "
              "calls; small dispatches are included; a kernel instance covers all layers that use it." % chunk,
@@ -214,15 +218,17 @@ def mfma_utilisation(raw, chunk=668):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--raw", default=os.path.join(ROOT, "gpurun_out", "profile"))
+    ap.add_argument("--raw", required=True, help="directory with the raw rocprofv3 output and bench.py logs")
     args = ap.parse_args()
+    global RAW
+    RAW = os.path.relpath(args.raw, ROOT) if os.path.isabs(args.raw) else args.raw.rstrip("/")
     kernel_stats(args.raw, "stats", "conv_resnet50_certify_kernel_stats.md",
                  "rocprofv3 kernel statistics: ResNet-50 int8 certification (bench.py headline workload)",
-                 "rocprofv3 --kernel-trace --stats -d gpurun_out/profile/stats -o r50 --output-format csv -- " + BENCH_STATS,
+                 "rocprofv3 --kernel-trace --stats -d " + RAW + "/stats -o r50 --output-format csv -- " + BENCH_STATS,
                  "stats.log", 5000, "TOP/s")
     kernel_stats(args.raw, "fp_stats", "fconv_resnet50_floatrs_fp_kernel_stats.md",
                  "rocprofv3 kernel statistics: ResNet-50 FloatRS-fp comparison system (fp32 network on the fp32 MFMA)",
-                 "rocprofv3 --kernel-trace --stats -d gpurun_out/profile/fp_stats -o fp --output-format csv -- " + BENCH_FP,
+                 "rocprofv3 --kernel-trace --stats -d " + RAW + "/fp_stats -o fp --output-format csv -- " + BENCH_FP,
                  "fp_stats.log", 157.3, "TFLOP/s")
     hbm_traffic(args.raw)
     mfma_utilisation(args.raw)
