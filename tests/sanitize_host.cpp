@@ -21,6 +21,11 @@ void isr_oracle_info(const omodel *m, int32_t *C, int32_t *H, int32_t *W, int32_
 size_t isr_oracle_tensor_offset(const omodel *m, int32_t id);
 int isr_oracle_forward(const omodel *m, const int8_t *a0, int8_t *acts, int32_t *logits);
 int isr_oracle_noise_table(uint32_t sigma, uint64_t *T, size_t cap, uint32_t *R);
+void isr_oracle_noisy_float(const uint8_t *x, uint32_t npix, float sigma, uint64_t seed, uint32_t image, uint32_t phase,
+                            uint32_t sample, float *v);
+void isr_oracle_noisy_quant(const uint8_t *x, uint32_t npix, float sigma, uint64_t seed, uint32_t image, uint32_t phase,
+                            uint32_t sample, int8_t *a0);
+int isr_oracle_forward_float(const omodel *m, const float *v, double *acts, double *logits);
 }
 
 // The planner asks the kernel files which shapes their kernels cover; those files are device code
@@ -97,6 +102,15 @@ static int oracle_side(const std::vector<uint8_t> &blob) {
         std::vector<int8_t> a0((size_t)C * H * W, 17), acts(total + 16);
         std::vector<int32_t> logits(classes);
         isr_oracle_forward(m, a0.data(), acts.data(), logits.data());
+        if (accepted % 64 == 1) {   // and, less often, the two comparison systems: continuous noise, rounded input, float network
+            std::vector<uint8_t> x((size_t)C * H * W, 200);
+            std::vector<float> v(x.size());
+            std::vector<double> facts(total + 16), flogits(classes);
+            isr_oracle_noisy_float(x.data(), (uint32_t)x.size(), 255.0f, 7, 1, 1, 3, v.data());
+            isr_oracle_noisy_quant(x.data(), (uint32_t)x.size(), 255.0f, 7, 1, 1, 3, a0.data());
+            isr_oracle_forward(m, a0.data(), acts.data(), logits.data());
+            isr_oracle_forward_float(m, v.data(), facts.data(), flogits.data());
+        }
     }
     isr_oracle_free(m);
     return 0;
