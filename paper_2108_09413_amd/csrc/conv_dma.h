@@ -25,7 +25,8 @@ inline const char *conv_dma_name() {
 // residual computed here by a second (1x1, stride 1) convolution.
 // WTM x WTN: output block of one wave (channels x pixels): 64 x 64 = 2 x 2 MFMA tiles, 128 x 64 = 4 x 2,
 // 128 x 128 = 4 x 4.  A larger block reads fewer operand bytes from LDS per multiply.
-template <int BM, int BN, int KB, int NST, int FUSE, int MINB, bool TF, int WTM = 64, int WTN = 64>
+// TF: the convolutions' requantisations are free of rounding ties (single-multiply form); TFA: so is the fused add.
+template <int BM, int BN, int KB, int NST, int FUSE, int MINB, bool TF, int WTM = 64, int WTN = 64, bool TFA = TF>
 __global__ __launch_bounds__((BM / WTM) * (BN / WTN) * 64, MINB) void conv_dma_kernel(const ConvParams p) {
     constexpr int MT = 32;
     constexpr int WGM = BM / WTM, WGN = BN / WTN, NT = WGM * WGN * 64;
@@ -388,7 +389,7 @@ __global__ __launch_bounds__((BM / WTM) * (BN / WTN) * 64, MINB) void conv_dma_k
 #pragma unroll
                     for (int i = 0; i < ACC; ++i) {
                         int r8 = (int)(int8_t)((uint32_t)rv[i >> 2] >> (8 * (i & 3)));
-                        q[i] = fused_add<TF>(q[i], r8, p);
+                        q[i] = fused_add<TFA>(q[i], r8, p);
                     }
                 }
                 int8_t *dst = p.out + n * p.Cout_p + oc;

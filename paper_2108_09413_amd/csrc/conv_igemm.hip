@@ -364,8 +364,12 @@ static hipError_t launch_dma_fused(const ConvParams &p, hipStream_t st) {
     if (p.fuse_add == 2) {
         if (!p.in2 || !p.w2 || p.Cin2_p < 64 || p.Cin2_p % 64 != 0) return hipErrorInvalidValue;
         set_kernel_name(conv_dma_name<BM, BN, 64, 2, 2, MINB2, 64, 64>());
-        if (p.tie_free && p.add_tie_free && p.tie_free2)
+        // the tie-free forms are chosen separately for the two convolutions and for the add: an add that can
+        // meet an exact half costs two more instructions per output, a convolution that can costs a 64-bit multiply
+        if (p.tie_free && p.tie_free2 && p.add_tie_free)
             hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 2, 2, MINB2, true>), grid, dim3(NT), 0, st, p);
+        else if (p.tie_free && p.tie_free2)
+            hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 2, 2, MINB2, true, 64, 64, false>), grid, dim3(NT), 0, st, p);
         else
             hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 2, 2, MINB2, false>), grid, dim3(NT), 0, st, p);
     } else if (BM == 128 && p.Kp == 128) {
@@ -375,6 +379,8 @@ static hipError_t launch_dma_fused(const ConvParams &p, hipStream_t st) {
             set_kernel_name(conv_dma_name<BM, BN, 64, 3, 1, 3, 64, 64>());
             if (p.tie_free && p.add_tie_free)
                 hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 3, 1, 3, true>), grid, dim3(NT), 0, st, p);
+            else if (p.tie_free)
+                hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 3, 1, 3, true, 64, 64, false>), grid, dim3(NT), 0, st, p);
             else
                 hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 3, 1, 3, false>), grid, dim3(NT), 0, st, p);
         }
@@ -382,6 +388,8 @@ static hipError_t launch_dma_fused(const ConvParams &p, hipStream_t st) {
         set_kernel_name(conv_dma_name<BM, BN, 64, 2, 1, MINB, 64, 64>());
         if (p.tie_free && p.add_tie_free)
             hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 2, 1, MINB, true>), grid, dim3(NT), 0, st, p);
+        else if (p.tie_free)
+            hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 2, 1, MINB, true, 64, 64, false>), grid, dim3(NT), 0, st, p);
         else
             hipLaunchKernelGGL((conv_dma_kernel<BM, BN, 64, 2, 1, MINB, false>), grid, dim3(NT), 0, st, p);
     }
