@@ -43,7 +43,7 @@ def library_name(profiler_name: str) -> str:
     """The name the library's timing report uses for a kernel as the profiler prints it."""
     n = profiler_name.replace("void ", "").replace("isr::", "").replace("(anonymous namespace)::", "")
     n = re.sub(r"\(.*\)$", "", n)
-    m = re.match(r"conv_dma_kernel<(\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (?:true|false), (\d+), (\d+)>", n)
+    m = re.match(r"conv_dma_kernel<(\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (?:true|false), (\d+), (\d+)(?:, (?:true|false))?>", n)
     if m:
         return "conv_dma_kernel<%s, %s, %s, %s, %s, %s, %sx%s>" % m.groups()
     m = re.match(r"bottleneck_kernel<(\d), (true|false)>", n)
