@@ -299,8 +299,11 @@ int isr_set_fusion(isr_model *m, int enable);
  * channels.  0 (the default) lets the library choose per launch; 1..4 force
  * 128x128, 128x256, 256x128, 256x256 (channels x pixels; the 256-channel tiles
  * only where a layer has more than 128 channels); 5 forces 256x256 computed by
- * four waves of 128x128 each instead of sixteen of 64x64.  Results are identical
- * for every choice.  ISR_ERR_ARG for other values. */
+ * four waves of 128x128 each instead of sixteen of 64x64, 6 by eight waves of
+ * 128x64; 7 forces, on 3x3 stride-1 layers with at least 256 output channels and
+ * a multiple of 128 input channels, the kernel that stages a tile's pixel rows
+ * once per channel slice (automatic choice elsewhere).  Results are identical for
+ * every choice.  ISR_ERR_ARG for other values. */
 int isr_set_conv_tile(isr_model *m, int tile);
 
 /* ---- per-kernel timing (HIP events on the model's stream) ------------------ */

@@ -517,7 +517,7 @@ int isr_noise_bank(uint32_t sigma, uint64_t seed, uint32_t bank_id, uint32_t fir
 }
 
 int isr_set_conv_tile(isr_model *m, int tile) {
-    if (!m || tile < 0 || tile > 6) return ISR_ERR_ARG;
+    if (!m || tile < 0 || tile > 7) return ISR_ERR_ARG;
     m->conv_tile = tile;
     return ISR_OK;
 }

@@ -412,13 +412,23 @@ int conv_k_step(int kreal, int cin_p, int cout_p, int fast_requant) {
 // bytes per multiply, so their K loop runs faster, but a layer with few tiles then
 // leaves CUs idle or pays for a mostly empty last round; the epilogue of a shallow
 // (small K) layer hides better behind several small workgroups.
-enum DmaTile { T64x256, T128x128, T128x256, T256x128, T256x256, T256x256W, T256x256H };   // W: four waves of 128 x 128 (conv_deep.hip); H: eight of 128 x 64
+// W: four waves of 128 x 128 (conv_deep.hip); H: eight of 128 x 64; P: 3x3 stride-1 layers with a tile's pixel rows
+// staged once per channel slice (conv_patch.hip)
+enum DmaTile { T64x256, T128x128, T128x256, T256x128, T256x256, T256x256W, T256x256H, T256x256P };
 
 static DmaTile pick_tile(const ConvParams &p) {
     const int forced = p.force_tile;
     if (p.Cout_p <= 64) return T64x256;
     if (forced >= T128x128 && forced <= T256x256H && !(p.Cout_p <= 128 && forced >= T256x128))
         return (DmaTile)forced;
+    if (forced == T256x256P && conv_patch_supported(p)) return T256x256P;
+    static const char *deep = std::getenv("ISR_DEEP_TILE");   // A/B switch for tuning: W, H, N (no conv_patch.hip) or unset
+    // 3x3 layers: the staged-rows kernel moves about 40 % fewer bytes into LDS per multiply (measured 7-10 % faster on
+    // the 14 x 14 and 28 x 28 layers of a ResNet-50); its tile is 256 pixels wide, so it wants launches that give
+    // at least half of the CUs a tile
+    if (!(deep && deep[0] == 'N') && conv_patch_supported(p) &&
+        ((long)(p.npix + 255) / 256) * ((p.Cout_p + 255) / 256) >= 128)
+        return T256x256P;
     if (p.Cout_p > 128 && p.Kp < 1024) return T128x128;
     // cost of a candidate: workgroups per CU (rounded up: the last round costs a full
     // one) x tile area / relative K-loop throughput of the tile, as measured
@@ -435,7 +445,6 @@ static DmaTile pick_tile(const ConvParams &p) {
         if (best_cost == 0 || cost < best_cost) { best_cost = cost; best = c.t; }
     }
     // deep layers on whole 256 x 256 tiles: four waves of 128 x 128 read half the LDS bytes per multiply
-    static const char *deep = std::getenv("ISR_DEEP_TILE");   // A/B switch for tuning: W, H or unset
     if (best == T256x256 && p.kb == 128 && deep) best = deep[0] == 'W' ? T256x256W : deep[0] == 'H' ? T256x256H : best;
     return best;
 }
@@ -465,6 +474,7 @@ hipError_t launch_conv(const ConvParams &p, hipStream_t st) {
             return k128 ? launch_dma<256, 128, 128, 2, 1>(p, st) : launch_dma<256, 128, 64, 3, 2>(p, st);
         case T256x256: return k128 ? launch_dma<256, 256, 128, 2, 1>(p, st) : launch_dma<256, 256, 64, 3, 1>(p, st);
         case T256x256W: return launch_conv_deep(p, st);
+        case T256x256P: return launch_conv_patch(p, st);
         case T256x256H: {
             const dim3 grid((unsigned)(((p.npix + 255) / 256) * ((p.Cout_p + 255) / 256)));
             set_kernel_name(k128 ? conv_dma_name<256, 256, 128, 2, 0, 1, 128, 64>() : conv_dma_name<256, 256, 64, 3, 0, 1, 128, 64>());

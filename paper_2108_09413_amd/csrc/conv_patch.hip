@@ -1,0 +1,250 @@
+// 3x3 stride-1 pad-1 convolutions of the deeper layers (at least 128 output channels, input channels a
+// multiple of the K step) with the activations staged ONCE per channel slice instead of once per tap.
+//
+// The implicit-GEMM kernel of conv_dma.h gathers, for each of the nine taps, the channel bytes of every
+// pixel of its tile again: per 128 input channels a 256 x 256 tile moves 9 x (32 KB of weights + 32 KB of
+// activations) from L2 into LDS, and issuing and awaiting that transfer is what its K step spends most of
+// its time on.  In the flat pixel order of an NHWC tensor the neighbour (dy, dx) of pixel n is pixel
+// n + dy W + dx whenever it lies in the image, so the nine shifted views of a tile of 256 consecutive pixels
+// all lie in the 256 + 2 (W + 1) pixel rows around it.  This kernel stages those rows once per slice of KB
+// channels and lets the fragment reads of tap (dy, dx) address row  i + (W + 1) + dy W + dx,  or zero
+// points for a neighbour outside the image: with KB = 128, 9 x 32 KB + 40 KB instead of 9 x 64 KB per
+// slice.  The weights stream as before, one [BM channels][KB bytes] block per (slice, tap); integer
+// accumulation makes the changed K order (slice-major, tap-minor) exact.
+//
+// LDS: two weight buffers, two activation buffers of 320 rows + 256 bytes of zero points, the per-channel
+// constants.  <256 channels, 128-byte slices>: 148 KB, sixteen waves of 64 x 64, one workgroup per CU;
+// <128, 64>: 58 KB, eight waves, two workgroups per CU.  Chunk swizzle and epilogue as in conv_dma.h.
+#include "conv_device.h"
+
+namespace isr {
+
+namespace {
+
+constexpr int PBN = 256;                         // pixels per tile
+constexpr int PROWS = 320;                       // staged pixel rows per buffer: 256 + 2 (W + 1) <= 320 for W <= 31
+constexpr int PZBYTES = 256;                     // zero points behind them: one pass over the 64 LDS banks
+
+// Wave-uniform LDS byte address of `p` as a plain integer.  The direct-to-LDS loads below take their destination
+// from it: the compiler then cannot tie them to the array and puts no vmcnt(0) in front of every fragment read
+// of that array (which would serialise refill and compute); the waits and barriers of the K loop order them.
+__device__ __forceinline__ uint32_t lds_address(const void *p) {
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)(uintptr_t)(const __attribute__((address_space(3))) void *)p);
+}
+#define ISR_GLOBAL_TO_LDS16_AT(gptr, lds_u32)                                                       \
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gptr),        \
+                                     (__attribute__((address_space(3))) void *)(uintptr_t)(lds_u32), 16, 0, 0)
+
+template <int BM, int KB, int MINB, bool TF>
+__global__ __launch_bounds__((BM / 64) * (PBN / 64) * 64, MINB) void conv_patch_kernel(const ConvParams p) {
+    constexpr int WGM = BM / 64, NW = WGM * (PBN / 64), NT = NW * 64;
+    constexpr int CPR = KB / 16;                 // 16-byte chunks per row
+    constexpr int RPP = NT / CPR;                // rows covered by one pass of all threads
+    constexpr int NA = BM / RPP;                 // weight loads per lane per step
+    constexpr int KS = KB / 32;
+    constexpr int ABUF = BM * KB, ZOFF = PROWS * KB, BBUF = ZOFF + PZBYTES;
+    static_assert(RPP == 128 && BM % RPP == 0 && (KB == 64 || KB == 128) && ZOFF % 256 == 0, "tile shape");
+
+    __shared__ __attribute__((aligned(256))) int8_t Bs[2][BBUF];
+    __shared__ __attribute__((aligned(16))) int8_t As[2][ABUF];
+    __shared__ __attribute__((aligned(16))) int prm_s[4][BM];   // bias, M0, chi, shift-1 of this M tile
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WGM, wn = wave / WGM;
+    // same XCD-aware tile order as the other convolution kernels
+    const int nblk = gridDim.x, mt = (p.Cout_p + BM - 1) / BM;
+    const int xcd = blockIdx.x & 7, per = nblk >> 3, extra = nblk & 7;
+    const int logical = xcd * per + (xcd < extra ? xcd : extra) + (blockIdx.x >> 3);
+    const int m0 = (logical % mt) * BM;
+    const int n0 = (logical / mt) * PBN;
+    const int W = p.W, halo = W + 1;
+    const int nslice = p.Cin_p / KB, nk = 9 * nslice;
+
+    // ---- loader side: lane (row0, col) of a pass of all threads fetches chunk col ^ swz(row0) of row row0 + 128 j ----
+    const int col = tid % CPR, row0 = tid / CPR;
+    const int cl = col ^ swz<CPR>(row0);
+    const int8_t *wrow[NA];
+#pragma unroll
+    for (int j = 0; j < NA; ++j) {
+        const int r = m0 + row0 + RPP * j;
+        wrow[j] = p.w + (long)(r < p.Mp ? r : 0) * p.Kp + cl * 16;   // rows past Mp re-read row 0; never stored
+    }
+    // staged row rho holds pixel n0 - halo + rho; pixels outside the tensor are clamped (only taps outside the image would read them)
+    uint32_t prow[3];
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+        int g = n0 - halo + row0 + RPP * j;
+        g = g < 0 ? 0 : (g >= p.npix ? p.npix - 1 : g);
+        prow[j] = (uint32_t)g * (uint32_t)p.Cin_p + cl * 16;
+    }
+    const uint32_t a_lds = lds_address(&As[0][wave * 1024]), b_lds = lds_address(&Bs[0][wave * 1024]);
+    // weights of step t = (slice, tap) into buffer t & 1: NA loads per lane
+    auto issue_a = [&](int slice, int tap, int buf) {
+        const uint32_t sa = a_lds + buf * ABUF;
+        const long koff = (long)tap * p.Cin_p + slice * KB;
+#pragma unroll
+        for (int j = 0; j < NA; ++j) ISR_GLOBAL_TO_LDS16_AT(wrow[j] + koff, sa + j * (NT * 16));
+    };
+    // pass j (128 rows; the third pass covers rows 256..319 with the first half of the waves) of a slice's pixel rows
+    auto issue_b = [&](int slice, int j, int buf) {
+        if (j < 2 || wave < NW / 2) ISR_GLOBAL_TO_LDS16_AT(p.in + (prow[j] + (uint32_t)(slice * KB)), b_lds + buf * BBUF + j * (NT * 16));
+    };
+
+    issue_b(0, 0, 0); issue_b(0, 1, 0); issue_b(0, 2, 0);
+    issue_a(0, 0, 0);
+    issue_a(0, 1, 1);   // step 1 is tap 1 of slice 0
+
+    for (int i = tid; i < BM; i += NT) {
+        const bool in = m0 + i < p.Mp;
+        prm_s[0][i] = in ? p.bias[m0 + i] : 0;
+        prm_s[1][i] = in ? p.m0s[m0 + i] : 0;
+        prm_s[2][i] = in ? p.chi[m0 + i] : 0;
+        prm_s[3][i] = in ? p.shm1[m0 + i] : 1;
+    }
+    if (tid < 2 * (PZBYTES / 4)) *(int *)(&Bs[tid / (PZBYTES / 4)][ZOFF + (tid % (PZBYTES / 4)) * 4]) = (p.zp_in & 0xFF) * 0x01010101;
+    __syncthreads();   // prm_s and the zero points visible
+
+    // ---- compute side ----
+    int aoff[KS][2];
+#pragma unroll
+    for (int ksub = 0; ksub < KS; ++ksub) {
+        const int c = ksub * 2 + (lane >> 5);
+#pragma unroll
+        for (int fm = 0; fm < 2; ++fm) {
+            const int r = wm * 64 + fm * 32 + (lane & 31);
+            aoff[ksub][fm] = r * KB + ((c ^ swz<CPR>(r)) << 4);
+        }
+    }
+    // pixel i of the tile sits in staged row i + halo; bit (dy + 1) * 3 + (dx + 1) of `inside` says that its neighbour
+    // (dy, dx) lies in the image
+    int rho0[2];
+    uint32_t inside[2];
+    {
+        const int HW = p.H * W;
+#pragma unroll
+        for (int fn = 0; fn < 2; ++fn) {
+            const int i = wn * 64 + fn * 32 + (lane & 31);
+            const int n = n0 + i, rem = n % HW, y = rem / W, x = rem - y * W;
+            const uint32_t rowok = (y > 0 ? 1u : 0u) | 2u | (y + 1 < p.H ? 4u : 0u);
+            const uint32_t colok = (x > 0 ? 1u : 0u) | 2u | (x + 1 < W ? 4u : 0u);
+            uint32_t m = 0;
+#pragma unroll
+            for (int ty = 0; ty < 3; ++ty)
+                if (rowok >> ty & 1) m |= colok << (3 * ty);
+            inside[fn] = m;
+            rho0[fn] = i + halo;
+        }
+    }
+    auto lane_oc = [&](int fm) { return wm * 64 + fm * 32 + 16 * (lane >> 5); };
+    v16i acc[2][2];
+#pragma unroll
+    for (int fm = 0; fm < 2; ++fm) {
+        v16i init;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) init[i] = prm_s[0][lane_oc(fm) + i];
+        acc[fm][0] = init;
+        acc[fm][1] = init;
+    }
+
+    const int half = (lane >> 5);
+    int t = 0;
+#pragma unroll 1
+    for (int slice = 0; slice < nslice; ++slice) {
+        const int8_t *bbase = Bs[slice & 1];
+#pragma unroll 1
+        for (int tap = 0; tap < 9; ++tap, ++t) {
+            // Outstanding at this point: step t's weights, (t = 0: also step 1's), the pixel-row passes issued during the
+            // previous step.  Step 1's weights were issued last at t = 0, everything else must have landed.
+            if (t == 0) wait_vmcnt<NA>();
+            else wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();   // every wave's loads of step t landed; every wave is done with step t - 1
+            if (t >= 1 && t + 1 < nk) {
+                const int nt = tap + 1 == 9 ? 0 : tap + 1;
+                issue_a(slice + (tap + 1 == 9 ? 1 : 0), nt, (t + 1) & 1);
+            }
+            // the other activation buffer was last read in the previous slice: refill it during the first three taps
+            if (tap < 3 && slice + 1 < nslice) issue_b(slice + 1, tap, (slice + 1) & 1);
+
+            const int ty = tap / 3, tx = tap - 3 * ty;
+            const int shift = (ty - 1) * W + (tx - 1);
+            // Byte offset of the lane's first fragment of this tap in the activation buffer.  A neighbour outside the image
+            // reads the zero points at the same offset modulo 256, i.e. from the banks its in-image read would have used:
+            // the 16 lanes that the LDS serves together then still cover the 64 banks exactly once.
+            int brow[2];
+#pragma unroll
+            for (int fn = 0; fn < 2; ++fn) {
+                const int rho = rho0[fn] + shift;
+                const int off = rho * KB + ((half ^ swz<CPR>(rho)) << 4);
+                brow[fn] = (inside[fn] >> tap & 1) ? off : ZOFF + (off & (PZBYTES - 1));
+            }
+            const int8_t *abase = As[t & 1];
+#pragma unroll
+            for (int ksub = 0; ksub < KS; ++ksub) {
+                v4i fa[2], fb[2];
+#pragma unroll
+                for (int fm = 0; fm < 2; ++fm) fa[fm] = *(const v4i *)(abase + aoff[ksub][fm]);
+                // chunk (2 ksub + half) ^ swz = (half ^ swz) ^ 2 ksub: bits 5..6 of the byte offset
+#pragma unroll
+                for (int fn = 0; fn < 2; ++fn) fb[fn] = *(const v4i *)(bbase + (brow[fn] ^ (ksub << 5)));
+#pragma unroll
+                for (int fm = 0; fm < 2; ++fm)
+#pragma unroll
+                    for (int fn = 0; fn < 2; ++fn)
+                        acc[fm][fn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[fm], fb[fn], acc[fm][fn], 0, 0, 0);
+            }
+        }
+    }
+
+    // epilogue: requantise, clamp, pack, store (NHWC)
+    const int lo = p.relu ? p.zp_out : -128;
+#pragma unroll
+    for (int fm = 0; fm < 2; ++fm) {
+        const int oc = m0 + lane_oc(fm);
+        if (oc >= p.Cout_p) continue;
+        int mm[16], ch[16], ss[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            mm[i] = prm_s[1][oc - m0 + i]; ch[i] = prm_s[2][oc - m0 + i]; ss[i] = prm_s[3][oc - m0 + i];
+        }
+#pragma unroll
+        for (int fn = 0; fn < 2; ++fn) {
+            const long n = (long)n0 + wn * 64 + fn * 32 + (lane & 31);
+            if (n >= p.npix) continue;
+            int q[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) q[i] = clamp3(requant_q<TF>(acc[fm][fn][i], mm[i], ch[i], ss[i]), lo, 127);
+            *(v4i *)(p.out + n * p.Cout_p + oc) = v4i{(int)pack4(q[0], q[1], q[2], q[3]), (int)pack4(q[4], q[5], q[6], q[7]),
+                                                       (int)pack4(q[8], q[9], q[10], q[11]), (int)pack4(q[12], q[13], q[14], q[15])};
+        }
+    }
+}
+
+template <int BM, int KB, int MINB>
+hipError_t launch_patch(const ConvParams &p, hipStream_t st, const char *name) {
+    const dim3 grid((unsigned)(((p.npix + PBN - 1) / PBN) * ((p.Cout_p + BM - 1) / BM)));
+    set_kernel_name(name);
+    if (p.tie_free) hipLaunchKernelGGL((conv_patch_kernel<BM, KB, MINB, true>), grid, dim3((BM / 64) * (PBN / 64) * 64), 0, st, p);
+    else hipLaunchKernelGGL((conv_patch_kernel<BM, KB, MINB, false>), grid, dim3((BM / 64) * (PBN / 64) * 64), 0, st, p);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// 3x3, stride 1, pad 1, same-size output; whole channel slices; a tile's pixel rows fit the staging buffer;
+// 256-channel tiles step through K in 128-byte slices, 128-channel tiles in 64-byte slices
+bool conv_patch_supported(const ConvParams &p) {
+    if (!(p.k == 3 && p.stride == 1 && p.pad == 1 && p.H == p.Ho && p.W == p.Wo && p.W >= 2 && 2 * (p.W + 1) + PBN <= PROWS))
+        return false;
+    if (p.fuse_add || !p.fast_requant || p.c4 || p.Kp != 9 * p.Cin_p || (long)p.npix * p.Cin_p >= (1l << 31)) return false;
+    if (p.Cout_p >= 256) return p.kb == 128 && p.Cin_p % 128 == 0;
+    return p.Cout_p == 128 && p.kb == 64 && p.Cin_p % 64 == 0;
+}
+
+hipError_t launch_conv_patch(const ConvParams &p, hipStream_t st) {
+    if (p.npix <= 0) return hipSuccess;
+    if (!conv_patch_supported(p) || p.Mp < p.Cout_p) return hipErrorInvalidValue;
+    if (p.Cout_p >= 256) return launch_patch<256, 128, 1>(p, st, "conv_patch_kernel<256, 256, 128>");
+    return launch_patch<128, 64, 2>(p, st, "conv_patch_kernel<128, 256, 64>");
+}
+
+}  // namespace isr

@@ -121,7 +121,7 @@ struct ConvParams {
     const int8_t *zpad;      // 16 bytes of z_in: source of out-of-image taps for loads that go straight to LDS
     int32_t H, W, Cin_p, Ho, Wo, Cout_p;
     int32_t k, stride, pad, Kp, Mp;   // k: kernel size (k x k taps)
-    int32_t force_tile;      // 0: the launcher picks the output tile; 1..5: 128x128, 128x256, 256x128, 256x256, 256x256 with 128x128 per wave
+    int32_t force_tile;      // 0: the launcher picks the output tile; 1..7: 128x128, 128x256, 256x128, 256x256, 256x256 with 128x128 / 128x64 per wave, 256x256 of conv_patch.hip
     int32_t kb;              // K bytes per step of the kernel (64 or 128); Kp is a multiple of it
     int32_t zp_in, zp_out, relu;
     int32_t npix;            // B * Ho * Wo
@@ -319,6 +319,8 @@ const char *last_kernel_name();
 hipError_t launch_noise_bank(const NoiseBankParams &p, hipStream_t st);
 hipError_t launch_noise(const NoiseParams &p, hipStream_t st);
 hipError_t launch_conv(const ConvParams &p, hipStream_t st);
+bool conv_patch_supported(const ConvParams &p);
+hipError_t launch_conv_patch(const ConvParams &p, hipStream_t st);   // deep 3x3 layers, pixel rows staged once per channel slice (conv_patch.hip)
 hipError_t launch_conv_deep(const ConvParams &p, hipStream_t st);   // 256 x 256 tiles, 128 x 128 per wave (conv_deep.hip)
 hipError_t launch_stem_pool(const StemPoolParams &p, hipStream_t st);
 bool stem_pool_supported(int k, int stride, int pad, int cout_p, int H, int W, int fast_requant, int pool_k,

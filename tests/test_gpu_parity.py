@@ -637,7 +637,7 @@ def test_resnet50_in_the_benchmarked_launch_configuration(isr):
     olg, oam = _oracle_at(om, x, 128, 0, 2, 1, [20000 + i for i in picks])
     for j, i in enumerate(picks):
         assert np.array_equal(lg[i], olg[j]) and am[i] == oam[j], i
-    for tile in (1, 2, 3, 4, 5, 6):
+    for tile in (1, 2, 3, 4, 5, 6, 7):
         _say(f"  forced tile {tile}")
         isr.isr_set_conv_tile(m, tile)
         lg2, am2, cnt2 = isr.isr_debug_forward(m, x, 128, 0, 2, 1, 20000, 668)
@@ -669,7 +669,7 @@ def test_cifar_nets_in_the_benchmarked_launch_configuration(isr, cfg, chunk):
     m.close()
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5, 6, 7])
 def test_every_conv_tile_against_the_oracle(isr, tile):
     """Layers deep enough for 128-byte K steps and for every output tile of the
     direct-to-LDS kernel, channel counts that leave a ragged last M tile, a ragged
@@ -699,6 +699,37 @@ def test_every_conv_tile_against_the_oracle(isr, tile):
     m.close()
     if tile == 4:
         _check_all_tensors(isr, blob, x, 64)
+
+
+@pytest.mark.parametrize("in_shape,stride,copies", [((28, 28), 2, 37), ((28, 28), 4, 150), ((28, 28), 1, 11), ((12, 20), 2, 61),
+                                                    ((36, 124), 4, 13), ((10, 4), 2, 333)])
+def test_3x3_layers_with_staged_pixel_rows_against_the_oracle(isr, in_shape, stride, copies):
+    """The 3x3 kernel that stages a tile's pixel rows once per channel slice (forced tile 7) and addresses the
+    nine taps as shifted rows: its tiles of 256 consecutive pixels straddle image rows and whole images, so
+    every border case of the shift arithmetic occurs -- square and non-square maps, the widest map its staging
+    buffer takes (31), a map narrower than the kernel, a ragged last tile.  128-channel (64-byte slices, two
+    slices) and 256-channel tiles (128-byte slices; one and two slices; a ragged second M tile).  The final
+    layer is fully connected over all pixels, so one wrong activation anywhere changes the logits."""
+    h, w = in_shape                                     # maps of 14x14, 7x7, 28x28, 6x10, 9x31, 5x2 behind the strided first layer
+    _say(f"staged-rows 3x3 parity, input {h}x{w} stride {stride}, {copies} copies")
+    b = NetBuilder(rng=np.random.default_rng(77 + h), in_shape=(3, h, w), num_classes=9)
+    t0 = b.tensor(3, h, w, 0, 74.0)
+    t1 = b.conv(t0, 128, 3, stride, 1, True)
+    t2 = b.conv(t1, 128, 3, 1, 1, True, zp_out=-100)    # 128-channel tile, K = 1152
+    t3 = b.conv(t2, 256, 3, 1, 1, False, zp_out=7)      # 256-channel tile, one slice of 128 channels
+    t4 = b.conv(t3, 272, 3, 1, 1, True)                 # two slices, ragged second M tile
+    t5 = b.conv(t4, 16, 1, 1, 0, True)
+    b.fc(t5, 9)
+    blob = b.blob()
+    x = np.random.default_rng(h * 100 + w).integers(0, 256, size=(3, h, w)).astype(np.uint8)
+    om = oracle.Model(blob)
+    olg, oam, ocnt = om.mc(x, 64, 2, 1, 1, 3, copies)
+    m = _load(isr, blob, copies)
+    for tile in (7, 0):
+        isr.isr_set_conv_tile(m, tile)
+        lg, am, cnt = isr.isr_debug_forward(m, x, 64, 2, 1, 1, 3, copies)
+        assert np.array_equal(lg, olg) and np.array_equal(am, oam) and np.array_equal(cnt, ocnt), tile
+    m.close()
 
 
 # ---- many (image, sigma) pairs in one pass -------------------------------------
