@@ -46,7 +46,7 @@ def library_name(profiler_name: str) -> str:
     m = re.match(r"conv_dma_kernel<(\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (?:true|false), (\d+), (\d+)(?:, (?:true|false))?>", n)
     if m:
         return "conv_dma_kernel<%s, %s, %s, %s, %s, %s, %sx%s>" % m.groups()
-    m = re.match(r"conv_patch_kernel<(\d+), (\d+), \d+, (?:true|false)>", n)
+    m = re.match(r"conv_patch_kernel<(\d+), (\d+), \d+, (?:true|false), (?:true|false)>", n)
     if m:
         return "conv_patch_kernel<%s, 256, %s>" % m.groups()      # channels x pixels of the tile, K bytes per step
     m = re.match(r"bottleneck_kernel<(\d), (true|false)>", n)

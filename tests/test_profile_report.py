@@ -18,7 +18,7 @@ def test_profiler_names_map_to_the_librarys_instance_names():
         "conv_dma_kernel<128, 128, 64, 2, 2, 3, 64x64>"
     assert f("void isr::conv_dma_kernel<256, 256, 128, 2, 0, 1, false, 128, 64>(isr::ConvParams)") == \
         "conv_dma_kernel<256, 256, 128, 2, 0, 1, 128x64>"
-    assert f("void isr::(anonymous namespace)::conv_patch_kernel<128, 64, 2, false>(isr::ConvParams)") == \
+    assert f("void isr::(anonymous namespace)::conv_patch_kernel<128, 64, 2, false, true>(isr::ConvParams)") == \
         "conv_patch_kernel<128, 256, 64>"
     assert f("void isr::(anonymous namespace)::bottleneck_kernel<2, true>(isr::BneckParams)") == \
         "bottleneck_kernel<block + projection, true>"
