@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libisr.so")
-SOURCES = ["api.cpp", "plan.cpp", "model_parse.cpp", "noise_table.cpp", "host_stats.cpp", "kernels.hip", "conv_igemm.hip", "stem_pool.hip", "basic_block.hip", "bottleneck.hip", "bottleneck128.hip", "stem16.hip", "trans_block.hip", "noise_bank_static.hip", "conv_deep.hip", "conv_patch.hip", "float_api.cpp", "float_path.hip"]
+SOURCES = ["api.cpp", "plan.cpp", "model_parse.cpp", "noise_table.cpp", "host_stats.cpp", "kernels.hip", "conv_igemm.hip", "stem_pool.hip", "basic_block.hip", "bottleneck.hip", "bottleneck128.hip", "stem16.hip", "trans_block.hip", "noise_bank_static.hip", "conv_deep.hip", "conv_patch.hip", "expand_reduce.hip", "float_api.cpp", "float_path.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 # kernels: gfx950 only; packed-FP32 instruction selection is switched off; MFMA results go to

@@ -88,6 +88,16 @@ __device__ __forceinline__ uint32_t pack4(int a, int b, int c, int d) {
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gptr),        \
                                      (__attribute__((address_space(3))) void *)(lptr), 16, 0, 0)
 
+// Wave-uniform LDS byte address of `p` as a plain integer, and a direct-to-LDS load that takes its destination
+// from one: the compiler then cannot tie the load to the array and puts no vmcnt(0) in front of every later
+// read of that array (which would serialise refill and compute); the kernel's own waits and barriers order them.
+__device__ __forceinline__ uint32_t lds_address(const void *p) {
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)(uintptr_t)(const __attribute__((address_space(3))) void *)p);
+}
+#define ISR_GLOBAL_TO_LDS16_AT(gptr, lds_u32)                                                       \
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gptr),        \
+                                     (__attribute__((address_space(3))) void *)(uintptr_t)(lds_u32), 16, 0, 0)
+
 // The compiler does not order LDS reads after loads that write LDS; this wait does.
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }

@@ -25,16 +25,6 @@ constexpr int PBN = 256;                         // pixels per tile
 constexpr int PROWS = 320;                       // staged pixel rows per buffer: 256 + 2 (W + 1) <= 320 for W <= 31
 constexpr int PZBYTES = 256;                     // zero points behind them: one pass over the 64 LDS banks
 
-// Wave-uniform LDS byte address of `p` as a plain integer.  The direct-to-LDS loads below take their destination
-// from it: the compiler then cannot tie them to the array and puts no vmcnt(0) in front of every fragment read
-// of that array (which would serialise refill and compute); the waits and barriers of the K loop order them.
-__device__ __forceinline__ uint32_t lds_address(const void *p) {
-    return (uint32_t)__builtin_amdgcn_readfirstlane((int)(uintptr_t)(const __attribute__((address_space(3))) void *)p);
-}
-#define ISR_GLOBAL_TO_LDS16_AT(gptr, lds_u32)                                                       \
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gptr),        \
-                                     (__attribute__((address_space(3))) void *)(uintptr_t)(lds_u32), 16, 0, 0)
-
 template <int BM, int KB, int MINB, bool TF, bool DUTY>
 __global__ __launch_bounds__((BM / 64) * (PBN / 64) * 64, MINB) void conv_patch_kernel(const ConvParams p) {
     constexpr int WGM = BM / 64, NW = WGM * (PBN / 64), NT = NW * 64;

@@ -1,0 +1,208 @@
+// The closing 1x1 convolution + residual add of a bottleneck block with 128 middle channels and the opening
+// 1x1 convolution of the NEXT block in one kernel: y = add(requant(W3 t2), x) is written once and the next
+// block's t1' = relu(requant(W1' y)) is computed from the copy of y that is still in LDS, so the 512-channel
+// tensor is not read back from memory by a second kernel.
+//
+// A workgroup of eight waves owns 32 consecutive pixels with ALL 512 channels and walks over such tiles
+// (persistent grid).  Per tile:
+//   * x (32 x 512 bytes) and t2 (32 x 128 bytes) arrive by direct-to-LDS loads one tile ahead (two buffers);
+//   * expand: wave w computes channels 64 w .. 64 w + 63 of the 32 pixels (two 32x32x32 MFMA tiles, K = 128);
+//     its weight fragments stay in registers for the whole launch (fragment-major copy of the weights, made
+//     when the model is loaded), the pixel fragments come from the t2 tile;
+//   * the epilogue requantises, reads the residual from the x tile, adds, writes y to memory AND over x in LDS;
+//   * reduce: wave w computes output channels 16 w .. 16 w + 15 of the 32 pixels with v_mfma_i32_16x16x64_i8
+//     over K = 512 channels of the y tile (its weight fragments, too, stay in registers), requantises and
+//     stores t1'.
+// Two barriers per tile.  LDS rows of the x / y tile are 512 bytes: 16-byte chunk c of pixel p sits at chunk
+// c ^ (p & 15), so that 16 consecutive pixels reading one logical chunk cover the 64 banks exactly once, for the
+// epilogue's 32x32 layout and for the 16x16x64 fragment reads alike.
+#include "conv_device.h"
+
+namespace isr {
+
+namespace {
+
+constexpr int XK1 = 128, XC = 512, XN2 = 128, XPX = 32, XNW = 8, XNT = XNW * 64;
+constexpr int XNB = 3;   // tile buffers: loads run two tiles ahead
+typedef int v4acc __attribute__((ext_vector_type(4)));
+
+template <bool TFA>
+__global__ __launch_bounds__(XNT, 4) void expand_reduce_kernel(const XrParams p) {
+    __shared__ __attribute__((aligned(256))) int8_t XY[XNB][XPX * XC];
+    __shared__ __attribute__((aligned(16))) int8_t T2[XNB][XPX * XK1];
+    __shared__ __attribute__((aligned(16))) int prm1[4][XC];    // bias, M0, chi, shift-1 of the expanding convolution
+    __shared__ __attribute__((aligned(16))) int prm2[4][XN2];   // the same of the reducing convolution
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ntiles = (p.npix + XPX - 1) / XPX, G = gridDim.x;
+    const uint32_t xy_lds = lds_address(&XY[0][0]), t2_lds = lds_address(&T2[0][0]);
+
+    // direct-to-LDS loads of a tile: wave-load q of the x tile covers pixels 2 q, 2 q + 1 (wave w issues q = 2 w,
+    // 2 w + 1); wave-load q of the t2 tile covers pixels 8 q .. 8 q + 7 (waves 0 .. 3).  Pixels past the end
+    // re-read the last pixel; their results are never stored.
+    auto issue_tile = [&](int tile, int buf) {
+        const int n0 = tile * XPX;
+        int l = lane;
+        asm volatile("" : "+v"(l));   // recompute the per-lane offsets per call: kept across the tile loop they would be spilled
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int q = 2 * wave + j, px = 2 * q + (l >> 5), c = (l & 31) ^ (px & 15);
+            int n = n0 + px;
+            n = n < p.npix ? n : p.npix - 1;
+            ISR_GLOBAL_TO_LDS16_AT(p.x + ((uint32_t)n * (uint32_t)XC + (uint32_t)(c * 16)), xy_lds + buf * (XPX * XC) + q * 1024);
+        }
+        if (wave < 4) {
+            const int row = 8 * wave + (l >> 3), c = (l & 7) ^ swz<8>(row);
+            int n = n0 + row;
+            n = n < p.npix ? n : p.npix - 1;
+            ISR_GLOBAL_TO_LDS16_AT(p.t2 + ((uint32_t)n * (uint32_t)XK1 + (uint32_t)(c * 16)), t2_lds + buf * (XPX * XK1) + wave * 1024);
+        }
+    };
+
+    int tile = blockIdx.x;
+    if (tile < ntiles) issue_tile(tile, 0);
+    if (tile + G < ntiles) issue_tile(tile + G, 1);
+    for (int i = tid; i < XC; i += XNT) {
+        prm1[0][i] = p.bias1[i]; prm1[1][i] = p.m0s1[i]; prm1[2][i] = p.chi1[i]; prm1[3][i] = p.shm11[i];
+    }
+    if (tid < XN2) {
+        prm2[0][tid] = p.bias2[tid]; prm2[1][tid] = p.m0s2[tid]; prm2[2][tid] = p.chi2[tid]; prm2[3][tid] = p.shm12[tid];
+    }
+    // weight fragments, kept in registers for the whole launch: expand [fm][ksub] (32 output channels x 32 K bytes
+    // each), reduce [kstep] (16 output channels x 64 K bytes each)
+    const uint32_t lane16 = (uint32_t)lane * 16;
+    v4i a1[2][XK1 / 32], a2[XC / 64];
+#pragma unroll
+    for (int fm = 0; fm < 2; ++fm)
+#pragma unroll
+        for (int ks = 0; ks < XK1 / 32; ++ks)
+            a1[fm][ks] = *(const v4i *)(p.a1 + (size_t)wave * (2 * (XK1 / 32) * 1024) + (lane16 + (uint32_t)((fm * (XK1 / 32) + ks) * 1024)));
+#pragma unroll
+    for (int ks = 0; ks < XC / 64; ++ks) a2[ks] = *(const v4i *)(p.a2 + (size_t)wave * (XC / 64) * 1024 + (lane16 + (uint32_t)(ks * 1024)));
+    wait_vmcnt<0>();
+    __syncthreads();   // the constants are in LDS, the first tile has landed
+
+    int buf = 0;
+    for (int it = 0; tile < ntiles; tile += G, ++it) {
+        const int n0 = tile * XPX;
+        // per-lane positions, recomputed per tile (a handful of instructions) instead of held in registers next to the
+        // 64 registers of weight fragments
+        int l = lane;
+        asm volatile("" : "+v"(l));
+        const int half = l >> 5, px1 = l & 31;            // expand: the lane's pixel and channel half
+        const int g = l >> 4, px2 = l & 15;               // reduce: the lane's K / channel group and pixel
+        const int b_off1 = px1 * XK1 + ((half ^ swz<8>(px1)) << 4);   // t2 fragment of K sub-step 0; sub-step k flips bits 5..6 by k
+        const bool prefetch = tile + 2 * G < ntiles;
+        if (it > 0) {
+            // The loads of this tile were issued two tiles ago.  Vector memory operations complete in issue order, so
+            // they have landed once at most the operations issued after them are outstanding: the four stores of each of
+            // the two tiles since, and the loads of the tile issued one tile ago (three for waves 0 .. 3, two for the
+            // others).  Where the sequence differs (the second tile, which has one tile of stores behind it) the wave
+            // waits for everything.
+            if (it >= 2 && tile + G < ntiles) {
+                if (wave < 4) wait_vmcnt<11>();
+                else wait_vmcnt<10>();
+            } else {
+                wait_vmcnt<0>();
+            }
+            __builtin_amdgcn_s_barrier();    // every wave's loads of this tile landed; every wave is done with the previous tile's buffers
+        }
+        if (prefetch) issue_tile(tile + 2 * G, buf >= 1 ? buf - 1 : XNB - 1);   // the buffer of the previous tile
+
+        // ---- expand: 64 channels x 32 pixels per wave, 32 channels at a time ----
+        const int8_t *t2b = T2[buf];
+        int8_t *xyb = XY[buf];
+        const long n1 = (long)n0 + px1;
+#pragma unroll
+        for (int fm = 0; fm < 2; ++fm) {
+            const int oc = wave * 64 + fm * 32 + half * 16;
+            v16i acc;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] = prm1[0][oc + i];
+#pragma unroll
+            for (int ks = 0; ks < XK1 / 32; ++ks) {
+                const v4i fb = *(const v4i *)(t2b + (b_off1 ^ (ks << 5)));
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[fm][ks], fb, acc, 0, 0, 0);
+            }
+            int8_t *cell = xyb + px1 * XC + ((((oc >> 4)) ^ (px1 & 15)) << 4);
+            const v4i rv = *(const v4i *)cell;
+            v4i yv;
+            // four channels at a time: their constants are three 16-byte LDS reads, the results one packed dword
+#pragma unroll
+            for (int gi = 0; gi < 4; ++gi) {
+                const v4i mm = *(const v4i *)&prm1[1][oc + 4 * gi], ch = *(const v4i *)&prm1[2][oc + 4 * gi], ss = *(const v4i *)&prm1[3][oc + 4 * gi];
+                int q[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int v = clamp3(requant_tie_free(acc[4 * gi + i], mm[i], ch[i], ss[i]), p.lo1, 127);
+                    const int r8 = (int)(int8_t)((uint32_t)rv[gi] >> (8 * i));
+                    if constexpr (TFA) {
+                        const int s = __mul24(v, p.add_mul_self) + (p.add_c0 + p.add_k) + __mul24(r8, p.add_mul_res);
+                        q[i] = clamp3(s >> p.add_sh, p.add_lo, 127);
+                    } else {
+                        const int s = __mul24(v, p.add_mul_self) + p.add_c0 + __mul24(r8, p.add_mul_res);
+                        q[i] = clamp3((s + p.add_k + (s >> 31)) >> p.add_sh, p.add_lo, 127);
+                    }
+                }
+                yv[gi] = (int)pack4(q[0], q[1], q[2], q[3]);
+            }
+            *(v4i *)cell = yv;
+            if (n1 < p.npix) *(v4i *)(p.y + n1 * XC + oc) = yv;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave's part of the y tile is in LDS (its stores to memory may still be under way)
+        __builtin_amdgcn_s_barrier();                         // the y tile is complete
+        asm volatile("" ::: "memory");
+
+        // ---- reduce: 16 channels x 32 pixels per wave, K = 512 channels of the y tile ----
+        v4acc acc2[2];
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc2[nb][i] = prm2[0][wave * 16 + g * 4 + i];
+#pragma unroll
+        for (int ks = 0; ks < XC / 64; ++ks) {
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+                const int px = px2 + 16 * nb;
+                const v4i fb = *(const v4i *)(xyb + px * XC + (((4 * ks + g) ^ px2) << 4));
+                acc2[nb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a2[ks], fb, acc2[nb], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+            const long n2 = (long)n0 + px2 + 16 * nb;
+            int q[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int c = wave * 16 + g * 4 + i;
+                q[i] = clamp3(requant_tie_free(acc2[nb][i], prm2[1][c], prm2[2][c], prm2[3][c]), p.lo2, 127);
+            }
+            if (n2 < p.npix) *(uint32_t *)(p.t1n + n2 * XN2 + wave * 16 + g * 4) = pack4(q[0], q[1], q[2], q[3]);
+        }
+        buf = buf + 1 == XNB ? 0 : buf + 1;
+    }
+}
+
+}  // namespace
+
+// expand: 1x1, 128 -> 512 channels, fused residual add; reduce: 1x1 stride 1, 512 -> 128, reading the sum;
+// single-multiply tie-free requantisations (the add may meet ties); fragment-major weight copies present
+bool expand_reduce_supported(const ConvParams &e, const ConvParams &r) {
+    return e.k == 1 && e.stride == 1 && e.pad == 0 && e.Cin_p == XK1 && e.Kp == XK1 && e.Cout_p == XC && e.fuse_add == 1 &&
+           e.fast_requant && e.tie_free && !e.c4 && e.wfrag && r.k == 1 && r.stride == 1 && r.pad == 0 && r.Cin_p == XC &&
+           r.Kp == XC && r.Cout_p == XN2 && !r.fuse_add && r.fast_requant && r.tie_free && !r.c4 && r.wfrag &&
+           e.Ho == r.H && e.Wo == r.W && r.Ho == r.H && r.Wo == r.W;
+}
+
+hipError_t launch_expand_reduce(const XrParams &p, int add_tie_free, hipStream_t st) {
+    if (p.npix <= 0) return hipSuccess;
+    if ((long)p.npix * XC >= (1l << 32)) return hipErrorInvalidValue;   // 32-bit byte offsets inside the tensors
+    const int ntiles = (p.npix + XPX - 1) / XPX;
+    const dim3 grid((unsigned)(ntiles < 512 ? ntiles : 512));
+    set_kernel_name("expand_reduce_kernel<128, 512, 128>");
+    if (add_tie_free) hipLaunchKernelGGL((expand_reduce_kernel<true>), grid, dim3(XNT), 0, st, p);
+    else hipLaunchKernelGGL((expand_reduce_kernel<false>), grid, dim3(XNT), 0, st, p);
+    return hipGetLastError();
+}
+
+}  // namespace isr

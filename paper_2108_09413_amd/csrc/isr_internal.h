@@ -119,6 +119,9 @@ struct ConvParams {
     const uint32_t *ktab;    // [Kp/16] per 16-byte K chunk: ky | kx<<8, 0xFFFFFFFF = padding chunk; null = plain GEMM
     const int32_t *ktoff;    // [Kp/16] byte offset (ky*W + kx)*Cin_p + channel of the chunk
     const int8_t *zpad;      // 16 bytes of z_in: source of out-of-image taps for loads that go straight to LDS
+    // 1x1 layers of the shapes expand_reduce.hip serves: the weights once more, one 1 KB block per MFMA operand
+    // fragment (64 lanes x 16 bytes in lane order); null elsewhere
+    const int8_t *wfrag;
     int32_t H, W, Cin_p, Ho, Wo, Cout_p;
     int32_t k, stride, pad, Kp, Mp;   // k: kernel size (k x k taps)
     int32_t force_tile;      // 0: the launcher picks the output tile; 1..7: 128x128, 128x256, 256x128, 256x256, 256x256 with 128x128 / 128x64 per wave, 256x256 of conv_patch.hip
@@ -195,6 +198,21 @@ struct BneckParams {
     int32_t lo1, lo2, lo3;   // lower clamps of the three int8 results
     int32_t add_mul_self, add_mul_res, add_c0, add_k, add_sh, add_lo;   // as in ConvParams
     int32_t tie_free;        // every requantisation (and the add) is free of rounding ties
+};
+
+// Closing 1x1 convolution + residual add of one bottleneck block and the opening 1x1 convolution of the next
+// in one kernel (expand_reduce.hip): y = add(requant(W3 t2), x), t1n = requant(W1n y); 128 -> 512 -> 128 channels.
+struct XrParams {
+    const int8_t *t2;        // [npix][128] input of the expanding convolution
+    const int8_t *x;         // [npix][512] residual
+    int8_t *y;               // [npix][512] the sum (the next block's input and residual)
+    int8_t *t1n;             // [npix][128] output of the reducing convolution
+    const int8_t *a1, *a2;   // fragment-major weight copies (ConvParams::wfrag) of the two convolutions
+    const int32_t *bias1, *m0s1, *chi1, *shm11;   // as in ConvParams, expanding convolution [512]
+    const int32_t *bias2, *m0s2, *chi2, *shm12;   // reducing convolution [128]
+    int32_t lo1, lo2;        // lower clamps of the two convolutions' int8 results
+    int32_t add_mul_self, add_mul_res, add_c0, add_k, add_sh, add_lo;   // as in ConvParams
+    int32_t npix;
 };
 
 // Down-sampling residual block in one kernel (trans_block.hip): t = conv3x3/2(x), u = conv3x3(t),
@@ -331,7 +349,9 @@ hipError_t launch_basic_block(const BlockParams &p, hipStream_t st);
 bool basic_block_supported(int channels, int size);
 hipError_t launch_bottleneck(const BneckParams &p, hipStream_t st);
 bool bottleneck_supported(int cin_p, int cmid_p, int cout_p, int tail);
-hipError_t launch_bottleneck128(const BneckParams &p, hipStream_t st);   // 128 middle channels, identity blocks (bottleneck128.hip)
+hipError_t launch_bottleneck128(const BneckParams &p, hipStream_t st);
+bool expand_reduce_supported(const ConvParams &expand, const ConvParams &reduce);
+hipError_t launch_expand_reduce(const XrParams &p, int add_tie_free, hipStream_t st);   // expand_reduce.hip   // 128 middle channels, identity blocks (bottleneck128.hip)
 bool bottleneck128_supported(int cin_p, int cmid_p, int cout_p);
 hipError_t launch_trans_block(const TransParams &p, hipStream_t st);
 bool trans_block_supported(int cout, int size_out);

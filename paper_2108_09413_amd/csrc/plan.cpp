@@ -98,6 +98,7 @@ void plan_workspace(const ParsedModel &pm, uint32_t B, Plan &pl) {
         for (int j = i; j < end; ++j) {
             const DevOp &o = pl.ops[j];
             if (o.type != OP_FC) { pl.toff[o.out] = alloc(tbytes(o.out)); pl.has[o.out] = 1; }
+            if (o.out2 >= 0) { pl.toff[o.out2] = alloc(tbytes(o.out2)); pl.has[o.out2] = 1; }
         }
         for (int j = i; j < end; ++j) {
             const DevOp &o = pl.ops[j];
@@ -471,6 +472,29 @@ int build_device_ops(const ParsedModel &pm, std::vector<DevOp> &ops, ConstArena 
             c.tie_free = tie_free ? 1 : 0;
             const std::vector<int8_t> zfill(16, (int8_t)ti.zp);
             c.zpad = (const int8_t *)arena.put(zfill.data(), zfill.size());
+            // fragment-major copies for the kernel that runs an expanding 1x1 + add and the next reducing 1x1 together
+            // (expand_reduce.hip): one 1 KB block per MFMA operand fragment, 64 lanes x 16 bytes in lane order
+            c.wfrag = (const int8_t *)~(uintptr_t)0;
+            if (flat && fast && perm && cin_p == 128 && cout_p == 512 && Kp == 128) {
+                // 32x32x32 fragments [32-row block][K sub-step of 32]: lane l = row l & 31 (stored MFMA row order), K bytes 16 (l >> 5) ..
+                std::vector<int8_t> f((size_t)cout_p * Kp);
+                for (int blk = 0; blk < cout_p / 32; ++blk)
+                    for (int ks = 0; ks < Kp / 32; ++ks)
+                        for (int l = 0; l < 64; ++l)
+                            std::memcpy(&f[(((size_t)blk * (Kp / 32) + ks) * 64 + l) * 16],
+                                        &w[(size_t)(32 * blk + (l & 31)) * Kp + ks * 32 + 16 * (l >> 5)], 16);
+                c.wfrag = (const int8_t *)arena.put(f.data(), f.size());
+            } else if (flat && fast && perm && cin_p == 512 && cout_p == 128 && Kp == 512) {
+                // 16x16x64 fragments [16-channel block][K step of 64]: lane l = channel l & 15 of the block, K bytes 16 (l >> 4) ..
+                std::vector<int8_t> f((size_t)cout_p * Kp);
+                for (int mb = 0; mb < cout_p / 16; ++mb)
+                    for (int ks = 0; ks < Kp / 64; ++ks)
+                        for (int l = 0; l < 64; ++l) {
+                            const int oc = 16 * mb + (l & 15), row = (oc & ~31) + mfma32_row_of_channel(oc & 31);
+                            std::memcpy(&f[(((size_t)mb * (Kp / 64) + ks) * 64 + l) * 16], &w[(size_t)row * Kp + ks * 64 + 16 * (l >> 4)], 16);
+                        }
+                c.wfrag = (const int8_t *)arena.put(f.data(), f.size());
+            }
             c.ktab = flat ? (const uint32_t *)~(uintptr_t)0 : (const uint32_t *)arena.put(ktab.data(), ktab.size() * 4);
             c.ktoff = flat ? (const int32_t *)~(uintptr_t)0 : (const int32_t *)arena.put(ktoff.data(), ktoff.size() * 4);
             c.H = ti.H; c.W = ti.W; c.Cin_p = cin_p; c.Ho = to.H; c.Wo = to.W; c.Cout_p = cout_p;
@@ -545,12 +569,37 @@ void rebase_device_ops(std::vector<DevOp> &ops, const uint8_t *base) {
             rebase(d.conv.w, base); rebase(d.conv.bias, base); rebase(d.conv.m0x2, base);
             rebase(d.conv.rnd_lo, base); rebase(d.conv.rnd_hi, base); rebase(d.conv.shift, base);
             rebase(d.conv.ktab, base); rebase(d.conv.ktoff, base); rebase(d.conv.zpad, base);
-            rebase(d.conv.m0s, base); rebase(d.conv.chi, base); rebase(d.conv.shm1, base);
+            rebase(d.conv.m0s, base); rebase(d.conv.chi, base); rebase(d.conv.shm1, base); rebase(d.conv.wfrag, base);
         } else if (d.type == OP_FC) {
             rebase(d.fc.w, base); rebase(d.fc.bias, base);
         }
     }
 }
+
+namespace {
+
+// Folds an expanding 1x1 convolution + residual add (the end of a bottleneck block) and the reducing 1x1
+// convolution that reads the sum (the start of the next block) into one kernel: the sum is still written (the
+// next block's add reads it), but not read back by a second kernel.
+void fuse_expand_reduce(const ParsedModel &pm, std::vector<DevOp> &ops) {
+    auto plain = [](const DevOp &d) {
+        return d.type == OP_CONV && !d.stem_pool && !d.stem16 && !d.block && !d.trans && !d.bneck && !d.xr;
+    };
+    for (size_t i = 0; i + 1 < ops.size(); ++i) {
+        DevOp &a = ops[i];
+        const DevOp &b = ops[i + 1];
+        if (!plain(a) || !plain(b) || b.a != a.out || !expand_reduce_supported(a.conv, b.conv)) continue;
+        const TensorDesc &ty = pm.tensors[a.out];
+        a.xr = 1;
+        a.conv2 = b.conv;
+        a.out2 = b.out;
+        a.ops_per_sample += b.ops_per_sample;
+        a.bytes_per_sample += b.bytes_per_sample - (double)ty.C * ty.H * ty.W;   // the sum is not read back
+        ops.erase(ops.begin() + i + 1);
+    }
+}
+
+}  // namespace
 
 void build_fused_plan(const ParsedModel &pm, const std::vector<DevOp> &plain, std::vector<DevOp> &fused, bool wide_bottlenecks) {
     fuse_adds(pm, plain, fused);
@@ -572,6 +621,7 @@ void build_fused_plan(const ParsedModel &pm, const std::vector<DevOp> &plain, st
     chain_basic_blocks(pm, fused);
     fuse_trans_blocks(pm, fused);
     fuse_bottlenecks(pm, fused, wide_bottlenecks);
+    fuse_expand_reduce(pm, fused);
 }
 
 }  // namespace isr

@@ -23,6 +23,8 @@ struct DevOp {
     size_t chain_off = 0;               // first BlockDesc of the chain in the model's device array
     int trans = 0;                      // down-sampling block: this conv (3x3/2), conv2 (3x3) and conv3 (1x1/2 + add) in one kernel
     int bneck = 0;                      // 1: this 1x1 conv and the 3x3 conv2 in one kernel; 2: plus conv3 (1x1 + residual add); 3: as 2 with 128 middle channels; 4: as 2 with the residual computed by a projection 1x1 convolution of the block input (conv3 carries it as its second convolution)
+    int xr = 0;                         // this expanding 1x1 + residual add and the reducing 1x1 that reads its sum (conv2, output out2) in one kernel
+    int out2 = -1;                      // second output tensor of the op (xr != 0)
     int proj_is_main = 0;               // bneck == 4: conv3's first convolution is the projection of the block input, its second the closing 1x1
     ConvParams conv2{};
     ConvParams conv3{};

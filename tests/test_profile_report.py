@@ -20,6 +20,7 @@ def test_profiler_names_map_to_the_librarys_instance_names():
         "conv_dma_kernel<256, 256, 128, 2, 0, 1, 128x64>"
     assert f("void isr::(anonymous namespace)::conv_patch_kernel<128, 64, 2, false, true>(isr::ConvParams)") == \
         "conv_patch_kernel<128, 256, 64>"
+    assert f("void isr::(anonymous namespace)::expand_reduce_kernel<true>(isr::XrParams)") == "expand_reduce_kernel<128, 512, 128>"
     assert f("void isr::(anonymous namespace)::bottleneck_kernel<2, true>(isr::BneckParams)") == \
         "bottleneck_kernel<block + projection, true>"
     assert f("void isr::(anonymous namespace)::fconv_kernel<2, 2, 2, 2>(isr::FConvParams)") == "fconv_kernel<128 x 128>"
