@@ -230,21 +230,10 @@ int run_range(isr_model *m, const Plan &pl, const uint8_t *x, const DeviceNoiseT
                     break;
                 }
                 if (d.xr) {
-                    const ConvParams &e = d.conv, &r = d.conv2;
-                    XrParams xp{};
-                    xp.t2 = (const int8_t *)tptr(d.a, j0);
-                    xp.x = (const int8_t *)tptr(d.b, j0);
-                    xp.y = (int8_t *)tptr(d.out, j0);
-                    xp.t1n = (int8_t *)tptr(d.out2, j0);
-                    xp.a1 = e.wfrag; xp.a2 = r.wfrag;
-                    xp.bias1 = e.bias; xp.m0s1 = e.m0s; xp.chi1 = e.chi; xp.shm11 = e.shm1;
-                    xp.bias2 = r.bias; xp.m0s2 = r.m0s; xp.chi2 = r.chi; xp.shm12 = r.shm1;
-                    xp.lo1 = e.relu ? e.zp_out : -128;
-                    xp.lo2 = r.relu ? r.zp_out : -128;
-                    xp.add_mul_self = e.add_mul_self; xp.add_mul_res = e.add_mul_res; xp.add_c0 = e.add_c0;
-                    xp.add_k = e.add_k; xp.add_sh = e.add_sh; xp.add_lo = e.add_lo;
-                    xp.npix = (int32_t)(bn * e.Ho * e.Wo);
-                    HIP_TRY(launch_expand_reduce(xp, e.add_tie_free, m->stream));
+                    XrParams xp;
+                    expand_reduce_params(d.conv, d.conv2, (const int8_t *)tptr(d.a, j0), (const int8_t *)tptr(d.b, j0),
+                                         (int8_t *)tptr(d.out, j0), (int8_t *)tptr(d.out2, j0), (int32_t)bn, xp);
+                    HIP_TRY(launch_expand_reduce(xp, d.conv.add_tie_free, m->stream));
                     break;
                 }
                 ConvParams c = d.conv;

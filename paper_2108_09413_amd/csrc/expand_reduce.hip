@@ -5,7 +5,7 @@
 //
 // A workgroup of eight waves owns 32 consecutive pixels with ALL 512 channels and walks over such tiles
 // (persistent grid).  Per tile:
-//   * x (32 x 512 bytes) and t2 (32 x 128 bytes) arrive by direct-to-LDS loads one tile ahead (two buffers);
+//   * x (32 x 512 bytes) and t2 (32 x 128 bytes) arrive by direct-to-LDS loads two tiles ahead (three buffers);
 //   * expand: wave w computes channels 64 w .. 64 w + 63 of the 32 pixels (two 32x32x32 MFMA tiles, K = 128);
 //     its weight fragments stay in registers for the whole launch (fragment-major copy of the weights, made
 //     when the model is loaded), the pixel fragments come from the t2 tile;
@@ -16,6 +16,11 @@
 // Two barriers per tile.  LDS rows of the x / y tile are 512 bytes: 16-byte chunk c of pixel p sits at chunk
 // c ^ (p & 15), so that 16 consecutive pixels reading one logical chunk cover the 64 banks exactly once, for the
 // epilogue's 32x32 layout and for the 16x16x64 fragment reads alike.
+//
+// A second kernel does the same for a stage's FIRST block, whose residual is not a stored tensor but a projection
+// 1x1 convolution (256 -> 512 channels) of the block input: y = add(requant(W3 t2), requant(Wp x0)).  Sixteen waves,
+// 32 channels each, hold the fragments of all three weight matrices; x0 (32 x 256 bytes) takes the place of x
+// among the loads and the y tile is written, not overwritten.
 #include "conv_device.h"
 
 namespace isr {
@@ -183,21 +188,242 @@ __global__ __launch_bounds__(XNT, 4) void expand_reduce_kernel(const XrParams p)
     }
 }
 
+// ---- the same with the residual computed by a projection convolution of the block input ----
+
+constexpr int XPK = 256, XNW2 = 16, XNT2 = XNW2 * 64;
+
+template <bool TFA>
+__global__ __launch_bounds__(XNT2, 4) void proj_expand_reduce_kernel(const XrParams p) {
+    __shared__ __attribute__((aligned(256))) int8_t Y[XPX * XC];
+    __shared__ __attribute__((aligned(256))) int8_t X0[XNB][XPX * XPK];
+    __shared__ __attribute__((aligned(16))) int8_t T2[XNB][XPX * XK1];
+    __shared__ __attribute__((aligned(16))) int prm1[4][XC];    // bias, M0, chi, shift-1 of the expanding convolution
+    __shared__ __attribute__((aligned(16))) int prmp[4][XC];    // of the projection
+    __shared__ __attribute__((aligned(16))) int prm2[4][XN2];   // of the reducing convolution
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ntiles = (p.npix + XPX - 1) / XPX, G = gridDim.x;
+    const uint32_t x0_lds = lds_address(&X0[0][0]), t2_lds = lds_address(&T2[0][0]);
+
+    // direct-to-LDS loads of a tile: wave-load q of the x0 tile covers pixels 4 q .. 4 q + 3 (waves 0 .. 7), wave-load q
+    // of the t2 tile pixels 8 q .. 8 q + 7 (waves 8 .. 11)
+    auto issue_tile = [&](int tile, int buf) {
+        const int n0 = tile * XPX;
+        int l = lane;
+        asm volatile("" : "+v"(l));   // recompute the per-lane offsets per call: kept across the tile loop they would be spilled
+        if (wave < 8) {
+            const int px = 4 * wave + (l >> 4), c = (l & 15) ^ (px & 15);
+            int n = n0 + px;
+            n = n < p.npix ? n : p.npix - 1;
+            // the projection may be strided: output pixel (b, y, x) reads input pixel (b, s y, s x)
+            const int HoWo = p.Ho * p.Wo, b = n / HoWo, rem = n - b * HoWo, y = rem / p.Wo, x = rem - y * p.Wo;
+            const uint32_t src = (uint32_t)((b * p.Hin + y * p.pstride) * p.Win + x * p.pstride);
+            ISR_GLOBAL_TO_LDS16_AT(p.in2 + (src * (uint32_t)XPK + (uint32_t)(c * 16)), x0_lds + buf * (XPX * XPK) + wave * 1024);
+        } else if (wave < 12) {
+            const int q = wave - 8, row = 8 * q + (l >> 3), c = (l & 7) ^ swz<8>(row);
+            int n = n0 + row;
+            n = n < p.npix ? n : p.npix - 1;
+            ISR_GLOBAL_TO_LDS16_AT(p.t2 + ((uint32_t)n * (uint32_t)XK1 + (uint32_t)(c * 16)), t2_lds + buf * (XPX * XK1) + q * 1024);
+        }
+    };
+
+    int tile = blockIdx.x;
+    if (tile < ntiles) issue_tile(tile, 0);
+    if (tile + G < ntiles) issue_tile(tile + G, 1);
+    for (int i = tid; i < XC; i += XNT2) {
+        prm1[0][i] = p.bias1[i]; prm1[1][i] = p.m0s1[i]; prm1[2][i] = p.chi1[i]; prm1[3][i] = p.shm11[i];
+        prmp[0][i] = p.biasp[i]; prmp[1][i] = p.m0sp[i]; prmp[2][i] = p.chip[i]; prmp[3][i] = p.shm1p[i];
+    }
+    if (tid < XN2) {
+        prm2[0][tid] = p.bias2[tid]; prm2[1][tid] = p.m0s2[tid]; prm2[2][tid] = p.chi2[tid]; prm2[3][tid] = p.shm12[tid];
+    }
+    // weight fragments, kept in registers for the whole launch: wave w owns channels 32 w .. 32 w + 31 of the expanding
+    // convolution [ksub] and of the projection [ksub], and 16 channels x 16 pixels of the reducing convolution [kstep]
+    const uint32_t lane16 = (uint32_t)lane * 16;
+    v4i a1[XK1 / 32], ap[XPK / 32], a2[XC / 64];
+#pragma unroll
+    for (int ks = 0; ks < XK1 / 32; ++ks) a1[ks] = *(const v4i *)(p.a1 + (size_t)wave * (XK1 / 32) * 1024 + (lane16 + (uint32_t)(ks * 1024)));
+#pragma unroll
+    for (int ks = 0; ks < XPK / 32; ++ks) ap[ks] = *(const v4i *)(p.ap + (size_t)wave * (XPK / 32) * 1024 + (lane16 + (uint32_t)(ks * 1024)));
+#pragma unroll
+    for (int ks = 0; ks < XC / 64; ++ks) a2[ks] = *(const v4i *)(p.a2 + (size_t)(wave >> 1) * (XC / 64) * 1024 + (lane16 + (uint32_t)(ks * 1024)));
+    wait_vmcnt<0>();
+    __syncthreads();   // the constants are in LDS, the first tile has landed
+
+    int buf = 0;
+    for (int it = 0; tile < ntiles; tile += G, ++it) {
+        const int n0 = tile * XPX;
+        const bool prefetch = tile + 2 * G < ntiles;
+        if (it > 0) {
+            // as in expand_reduce_kernel: since this tile's loads, a wave has issued two stores per tile for two tiles and
+            // the load of the next tile (waves 0 .. 11)
+            if (it >= 2 && tile + G < ntiles) {
+                if (wave < 12) wait_vmcnt<5>();
+                else wait_vmcnt<4>();
+            } else {
+                wait_vmcnt<0>();
+            }
+            __builtin_amdgcn_s_barrier();    // every wave's loads of this tile landed; every wave is done with the previous tile
+        }
+        if (prefetch) issue_tile(tile + 2 * G, buf >= 1 ? buf - 1 : XNB - 1);
+
+        int l = lane;
+        asm volatile("" : "+v"(l));
+        const int half = l >> 5, px1 = l & 31;
+        const int g = l >> 4, px2 = l & 15;
+        const int oc = wave * 32 + half * 16;
+
+        // ---- projection of the block input: the residual, 32 channels x 32 pixels per wave, kept packed ----
+        v4i rq;
+        {
+            v16i acc;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] = prmp[0][oc + i];
+            const int8_t *xb = X0[buf];
+            const int x_off = px1 * XPK + ((half ^ (px1 & 15)) << 4);   // chunk (2 k + half) ^ (px & 15): sub-step k flips bits 5..7 by k
+#pragma unroll
+            for (int ks = 0; ks < XPK / 32; ++ks) {
+                const v4i fb = *(const v4i *)(xb + (x_off ^ (ks << 5)));
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(ap[ks], fb, acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int gi = 0; gi < 4; ++gi) {
+                __builtin_amdgcn_sched_barrier(0);   // one group's constants at a time: the registers are needed for weight fragments
+                const v4i mm = *(const v4i *)&prmp[1][oc + 4 * gi], ch = *(const v4i *)&prmp[2][oc + 4 * gi], ss = *(const v4i *)&prmp[3][oc + 4 * gi];
+                int q[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) q[i] = clamp3(requant_tie_free(acc[4 * gi + i], mm[i], ch[i], ss[i]), p.lop, 127);
+                rq[gi] = (int)pack4(q[0], q[1], q[2], q[3]);
+            }
+        }
+        // ---- expand + add ----
+        {
+            v16i acc;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] = prm1[0][oc + i];
+            const int8_t *t2b = T2[buf];
+            const int b_off1 = px1 * XK1 + ((half ^ swz<8>(px1)) << 4);
+#pragma unroll
+            for (int ks = 0; ks < XK1 / 32; ++ks) {
+                const v4i fb = *(const v4i *)(t2b + (b_off1 ^ (ks << 5)));
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[ks], fb, acc, 0, 0, 0);
+            }
+            v4i yv;
+#pragma unroll
+            for (int gi = 0; gi < 4; ++gi) {
+                __builtin_amdgcn_sched_barrier(0);
+                const v4i mm = *(const v4i *)&prm1[1][oc + 4 * gi], ch = *(const v4i *)&prm1[2][oc + 4 * gi], ss = *(const v4i *)&prm1[3][oc + 4 * gi];
+                int q[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int v = clamp3(requant_tie_free(acc[4 * gi + i], mm[i], ch[i], ss[i]), p.lo1, 127);
+                    const int r8 = (int)(int8_t)((uint32_t)rq[gi] >> (8 * i));
+                    if constexpr (TFA) {
+                        const int s = __mul24(v, p.add_mul_self) + (p.add_c0 + p.add_k) + __mul24(r8, p.add_mul_res);
+                        q[i] = clamp3(s >> p.add_sh, p.add_lo, 127);
+                    } else {
+                        const int s = __mul24(v, p.add_mul_self) + p.add_c0 + __mul24(r8, p.add_mul_res);
+                        q[i] = clamp3((s + p.add_k + (s >> 31)) >> p.add_sh, p.add_lo, 127);
+                    }
+                }
+                yv[gi] = (int)pack4(q[0], q[1], q[2], q[3]);
+            }
+            *(v4i *)(Y + px1 * XC + (((oc >> 4) ^ (px1 & 15)) << 4)) = yv;
+            const long n1 = (long)n0 + px1;
+            if (n1 < p.npix) *(v4i *)(p.y + n1 * XC + oc) = yv;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave's part of the y tile is in LDS
+        __builtin_amdgcn_s_barrier();                         // the y tile is complete
+        asm volatile("" ::: "memory");
+
+        // ---- reduce: wave w computes channels 16 (w / 2) .. + 15 of pixels 16 (w % 2) .. + 15 ----
+        {
+            const int mb = wave >> 1, px = px2 + 16 * (wave & 1);
+            v4acc acc2;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc2[i] = prm2[0][mb * 16 + g * 4 + i];
+#pragma unroll
+            for (int ks = 0; ks < XC / 64; ++ks) {
+                const v4i fb = *(const v4i *)(Y + px * XC + (((4 * ks + g) ^ px2) << 4));
+                acc2 = __builtin_amdgcn_mfma_i32_16x16x64_i8(a2[ks], fb, acc2, 0, 0, 0);
+            }
+            int q[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int c = mb * 16 + g * 4 + i;
+                q[i] = clamp3(requant_tie_free(acc2[i], prm2[1][c], prm2[2][c], prm2[3][c]), p.lo2, 127);
+            }
+            const long n2 = (long)n0 + px;
+            if (n2 < p.npix) *(uint32_t *)(p.t1n + n2 * XN2 + mb * 16 + g * 4) = pack4(q[0], q[1], q[2], q[3]);
+        }
+        buf = buf + 1 == XNB ? 0 : buf + 1;
+    }
+}
+
 }  // namespace
 
-// expand: 1x1, 128 -> 512 channels, fused residual add; reduce: 1x1 stride 1, 512 -> 128, reading the sum;
-// single-multiply tie-free requantisations (the add may meet ties); fragment-major weight copies present
+// Which of the two convolutions of a fuse_add == 2 descriptor is the projection: the main one (256 input channels, may be
+// strided; the expanding convolution is then the second, w2) or the second one.
+static bool projection_is_main(const ConvParams &e) { return e.fuse_add == 2 && e.Cin_p == XPK; }
+
+// expand: 1x1, 128 -> 512 channels, with a fused residual add (the residual a stored tensor, or the 1x1 projection of a
+// 256-channel tensor computed alongside); reduce: 1x1 stride 1, 512 -> 128, reading the sum; single-multiply tie-free
+// requantisations (the add may meet ties); fragment-major weight copies present
 bool expand_reduce_supported(const ConvParams &e, const ConvParams &r) {
-    return e.k == 1 && e.stride == 1 && e.pad == 0 && e.Cin_p == XK1 && e.Kp == XK1 && e.Cout_p == XC && e.fuse_add == 1 &&
-           e.fast_requant && e.tie_free && !e.c4 && e.wfrag && r.k == 1 && r.stride == 1 && r.pad == 0 && r.Cin_p == XC &&
-           r.Kp == XC && r.Cout_p == XN2 && !r.fuse_add && r.fast_requant && r.tie_free && !r.c4 && r.wfrag &&
-           e.Ho == r.H && e.Wo == r.W && r.Ho == r.H && r.Wo == r.W;
+    bool expand = e.k == 1 && e.pad == 0 && e.Cout_p == XC && e.fast_requant && e.tie_free && !e.c4 && e.wfrag;
+    if (e.fuse_add == 1) expand = expand && e.stride == 1 && e.Cin_p == XK1 && e.Kp == XK1;
+    else if (projection_is_main(e))   // main: projection 256 -> 512, stride 1 or 2; second: the expanding convolution on the output pixels
+        expand = expand && (e.stride == 1 || e.stride == 2) && e.Kp == XPK && e.Cin2_p == XK1 && e.tie_free2 && e.wfrag2 &&
+                 (long)e.H * e.W * XPK < (1l << 31);
+    else
+        expand = expand && e.fuse_add == 2 && e.stride == 1 && e.Cin_p == XK1 && e.Kp == XK1 && e.Cin2_p == XPK && e.tie_free2 && e.wfrag2;
+    const bool reduce = r.k == 1 && r.stride == 1 && r.pad == 0 && r.Cin_p == XC && r.Kp == XC && r.Cout_p == XN2 && !r.fuse_add &&
+                        r.fast_requant && r.tie_free && !r.c4 && r.wfrag;
+    return expand && reduce && e.Ho == r.H && e.Wo == r.W && r.Ho == r.H && r.Wo == r.W;
+}
+
+// The kernel's arguments from the descriptors of the expanding (+ add) and the reducing convolution and their tensors:
+// `a` is the main convolution's input, `b` the add's other operand (fuse_add == 1) or the second convolution's input.
+void expand_reduce_params(const ConvParams &e, const ConvParams &r, const int8_t *a, const int8_t *b, int8_t *y, int8_t *t1n,
+                          int32_t copies, XrParams &xp) {
+    xp = XrParams{};
+    xp.y = y; xp.t1n = t1n;
+    xp.a2 = r.wfrag; xp.bias2 = r.bias; xp.m0s2 = r.m0s; xp.chi2 = r.chi; xp.shm12 = r.shm1;
+    xp.lo2 = r.relu ? r.zp_out : -128;
+    xp.add_c0 = e.add_c0; xp.add_k = e.add_k; xp.add_sh = e.add_sh; xp.add_lo = e.add_lo;
+    xp.npix = copies * e.Ho * e.Wo;
+    xp.Hin = e.H; xp.Win = e.W; xp.Ho = e.Ho; xp.Wo = e.Wo; xp.pstride = 1;
+    const int lo_main = e.relu ? e.zp_out : -128;
+    if (projection_is_main(e)) {
+        xp.in2 = a; xp.pstride = e.stride;
+        xp.ap = e.wfrag; xp.biasp = e.bias; xp.m0sp = e.m0s; xp.chip = e.chi; xp.shm1p = e.shm1; xp.lop = lo_main;
+        xp.t2 = b;
+        xp.a1 = e.wfrag2; xp.bias1 = e.bias2; xp.m0s1 = e.m0s2; xp.chi1 = e.chi2; xp.shm11 = e.shm12; xp.lo1 = e.lo2;
+        xp.add_mul_self = e.add_mul_res; xp.add_mul_res = e.add_mul_self;   // "self" in the kernel = the expanding convolution
+    } else {
+        xp.t2 = a;
+        xp.a1 = e.wfrag; xp.bias1 = e.bias; xp.m0s1 = e.m0s; xp.chi1 = e.chi; xp.shm11 = e.shm1; xp.lo1 = lo_main;
+        xp.add_mul_self = e.add_mul_self; xp.add_mul_res = e.add_mul_res;
+        if (e.fuse_add == 2) {
+            xp.in2 = b;
+            xp.ap = e.wfrag2; xp.biasp = e.bias2; xp.m0sp = e.m0s2; xp.chip = e.chi2; xp.shm1p = e.shm12; xp.lop = e.lo2;
+        } else {
+            xp.x = b;
+        }
+    }
 }
 
 hipError_t launch_expand_reduce(const XrParams &p, int add_tie_free, hipStream_t st) {
     if (p.npix <= 0) return hipSuccess;
     if ((long)p.npix * XC >= (1l << 32)) return hipErrorInvalidValue;   // 32-bit byte offsets inside the tensors
     const int ntiles = (p.npix + XPX - 1) / XPX;
+    if (p.in2) {
+        const dim3 grid((unsigned)(ntiles < 256 ? ntiles : 256));   // one workgroup of sixteen waves per CU
+        set_kernel_name("proj_expand_reduce_kernel<256, 128, 512, 128>");
+        if (add_tie_free) hipLaunchKernelGGL((proj_expand_reduce_kernel<true>), grid, dim3(XNT2), 0, st, p);
+        else hipLaunchKernelGGL((proj_expand_reduce_kernel<false>), grid, dim3(XNT2), 0, st, p);
+        return hipGetLastError();
+    }
     const dim3 grid((unsigned)(ntiles < 512 ? ntiles : 512));
     set_kernel_name("expand_reduce_kernel<128, 512, 128>");
     if (add_tie_free) hipLaunchKernelGGL((expand_reduce_kernel<true>), grid, dim3(XNT), 0, st, p);

@@ -122,6 +122,7 @@ struct ConvParams {
     // 1x1 layers of the shapes expand_reduce.hip serves: the weights once more, one 1 KB block per MFMA operand
     // fragment (64 lanes x 16 bytes in lane order); null elsewhere
     const int8_t *wfrag;
+    const int8_t *wfrag2;    // fuse_add == 2: the same of the residual convolution (w2)
     int32_t H, W, Cin_p, Ho, Wo, Cout_p;
     int32_t k, stride, pad, Kp, Mp;   // k: kernel size (k x k taps)
     int32_t force_tile;      // 0: the launcher picks the output tile; 1..7: 128x128, 128x256, 256x128, 256x256, 256x256 with 128x128 / 128x64 per wave, 256x256 of conv_patch.hip
@@ -208,6 +209,12 @@ struct XrParams {
     int8_t *y;               // [npix][512] the sum (the next block's input and residual)
     int8_t *t1n;             // [npix][128] output of the reducing convolution
     const int8_t *a1, *a2;   // fragment-major weight copies (ConvParams::wfrag) of the two convolutions
+    // in2 != null: the residual is not x but clamp(requant(Wp in2)), a projection from 256 channels computed in the kernel
+    const int8_t *in2;       // [npix][256]
+    const int8_t *ap;        // fragment-major copy of the projection weights
+    const int32_t *biasp, *m0sp, *chip, *shm1p;   // [512]
+    int32_t lop;             // lower clamp of the projection's int8 result
+    int32_t Hin, Win, Ho, Wo, pstride;   // the projection reads pixel (pstride y, pstride x) of its Hin x Win input for output pixel (y, x)
     const int32_t *bias1, *m0s1, *chi1, *shm11;   // as in ConvParams, expanding convolution [512]
     const int32_t *bias2, *m0s2, *chi2, *shm12;   // reducing convolution [128]
     int32_t lo1, lo2;        // lower clamps of the two convolutions' int8 results
@@ -351,6 +358,8 @@ hipError_t launch_bottleneck(const BneckParams &p, hipStream_t st);
 bool bottleneck_supported(int cin_p, int cmid_p, int cout_p, int tail);
 hipError_t launch_bottleneck128(const BneckParams &p, hipStream_t st);
 bool expand_reduce_supported(const ConvParams &expand, const ConvParams &reduce);
+void expand_reduce_params(const ConvParams &expand, const ConvParams &reduce, const int8_t *a, const int8_t *b, int8_t *y,
+                          int8_t *t1n, int32_t copies, XrParams &xp);
 hipError_t launch_expand_reduce(const XrParams &p, int add_tie_free, hipStream_t st);   // expand_reduce.hip   // 128 middle channels, identity blocks (bottleneck128.hip)
 bool bottleneck128_supported(int cin_p, int cmid_p, int cout_p);
 hipError_t launch_trans_block(const TransParams &p, hipStream_t st);

@@ -174,6 +174,7 @@ void fuse_adds(const ParsedModel &pm, const std::vector<DevOp> &plain, std::vect
                         merged.conv.w2 = rc.w; merged.conv.bias2 = rc.bias; merged.conv.m0s2 = rc.m0s;
                         merged.conv.chi2 = rc.chi; merged.conv.shm12 = rc.shm1;
                         merged.conv.Cin2_p = rc.Cin_p;
+                        merged.conv.wfrag2 = rc.wfrag;
                         merged.conv.lo2 = rc.relu ? rc.zp_out : -128;
                         merged.conv.tie_free2 = rc.tie_free;
                         merged.b = r.a;   // second input tensor (kept alive until this op is issued)
@@ -475,7 +476,7 @@ int build_device_ops(const ParsedModel &pm, std::vector<DevOp> &ops, ConstArena 
             // fragment-major copies for the kernel that runs an expanding 1x1 + add and the next reducing 1x1 together
             // (expand_reduce.hip): one 1 KB block per MFMA operand fragment, 64 lanes x 16 bytes in lane order
             c.wfrag = (const int8_t *)~(uintptr_t)0;
-            if (flat && fast && perm && cin_p == 128 && cout_p == 512 && Kp == 128) {
+            if (!c4 && k == 1 && o.pad == 0 && fast && perm && (cin_p == 128 || cin_p == 256) && cout_p == 512 && Kp == cin_p) {
                 // 32x32x32 fragments [32-row block][K sub-step of 32]: lane l = row l & 31 (stored MFMA row order), K bytes 16 (l >> 5) ..
                 std::vector<int8_t> f((size_t)cout_p * Kp);
                 for (int blk = 0; blk < cout_p / 32; ++blk)

@@ -49,6 +49,8 @@ def library_name(profiler_name: str) -> str:
     m = re.match(r"conv_patch_kernel<(\d+), (\d+), \d+, (?:true|false), (?:true|false)>", n)
     if m:
         return "conv_patch_kernel<%s, 256, %s>" % m.groups()      # channels x pixels of the tile, K bytes per step
+    if re.match(r"proj_expand_reduce_kernel<(?:true|false)>", n):
+        return "proj_expand_reduce_kernel<256, 128, 512, 128>"     # block input, middle, block and next middle channels
     if re.match(r"expand_reduce_kernel<(?:true|false)>", n):
         return "expand_reduce_kernel<128, 512, 128>"               # middle, block and next middle channels
     m = re.match(r"bottleneck_kernel<(\d), (true|false)>", n)
@@ -64,7 +66,7 @@ def library_name(profiler_name: str) -> str:
 
 
 def is_conv(name: str) -> bool:
-    return name.startswith(("conv_dma_kernel", "conv_patch_kernel", "expand_reduce_kernel", "bottleneck_kernel", "stem_pool_kernel", "fconv_kernel"))
+    return name.startswith(("conv_dma_kernel", "conv_patch_kernel", "expand_reduce_kernel", "proj_expand_reduce_kernel", "bottleneck_kernel", "stem_pool_kernel", "fconv_kernel"))
 
 
 def last_json(path):

@@ -49,10 +49,16 @@ bool bottleneck_supported(int cin_p, int cmid_p, int cout_p, int tail) {
     return !tail || (cout_p == cin_p && cout_p <= 256);
 }
 bool expand_reduce_supported(const ConvParams &e, const ConvParams &r) {
-    return e.k == 1 && e.stride == 1 && e.pad == 0 && e.Cin_p == 128 && e.Kp == 128 && e.Cout_p == 512 && e.fuse_add == 1 &&
-           e.fast_requant && e.tie_free && !e.c4 && e.wfrag && r.k == 1 && r.stride == 1 && r.pad == 0 && r.Cin_p == 512 &&
-           r.Kp == 512 && r.Cout_p == 128 && !r.fuse_add && r.fast_requant && r.tie_free && !r.c4 && r.wfrag &&
-           e.Ho == r.H && e.Wo == r.W && r.Ho == r.H && r.Wo == r.W;
+    bool expand = e.k == 1 && e.pad == 0 && e.Cout_p == 512 && e.fast_requant && e.tie_free && !e.c4 && e.wfrag;
+    if (e.fuse_add == 1) expand = expand && e.stride == 1 && e.Cin_p == 128 && e.Kp == 128;
+    else if (e.fuse_add == 2 && e.Cin_p == 256)
+        expand = expand && (e.stride == 1 || e.stride == 2) && e.Kp == 256 && e.Cin2_p == 128 && e.tie_free2 && e.wfrag2 &&
+                 (long)e.H * e.W * 256 < (1l << 31);
+    else
+        expand = expand && e.fuse_add == 2 && e.stride == 1 && e.Cin_p == 128 && e.Kp == 128 && e.Cin2_p == 256 && e.tie_free2 && e.wfrag2;
+    const bool reduce = r.k == 1 && r.stride == 1 && r.pad == 0 && r.Cin_p == 512 && r.Kp == 512 && r.Cout_p == 128 && !r.fuse_add &&
+                        r.fast_requant && r.tie_free && !r.c4 && r.wfrag;
+    return expand && reduce && e.Ho == r.H && e.Wo == r.W && r.Ho == r.H && r.Wo == r.W;
 }
 bool bottleneck128_supported(int cin_p, int cmid_p, int cout_p) {
     return cmid_p == 128 && cin_p % 64 == 0 && cin_p >= 64 && cin_p <= 2048 && cout_p == cin_p && cout_p % 32 == 0;

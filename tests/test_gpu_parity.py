@@ -733,18 +733,26 @@ def test_3x3_layers_with_staged_pixel_rows_against_the_oracle(isr, in_shape, str
 
 
 def test_expand_add_and_next_reduce_in_one_kernel(isr):
-    """The kernel that runs a block's closing 1x1 (128 -> 512) + residual add and the next block's opening 1x1
-    (512 -> 128) on pixel tiles of all 512 channels: two such pairs in a row (the second with an add that meets
-    exact halves, i.e. the other template instance), residual as first and as second operand of the add.  Every
-    tensor of one copy; then 1001 copies of a 6x6 map = 1127 tiles of 32 pixels for 512 persistent workgroups
-    (three tiles for some: the counted waits of the steady state) with a ragged last tile, logits of a layer
-    that is fully connected over all pixels, against the oracle.  The timing report must name the kernel."""
+    """The kernels that run a block's closing 1x1 (128 -> 512) + residual add and the next block's opening 1x1
+    (512 -> 128) on pixel tiles of all 512 channels.  Four such pairs in a row: a first block whose residual is
+    a stride-2 projection of the 256-channel block input issued after the closing convolution (the order of a
+    ResNet-50), two identity blocks (the second with an add that meets exact halves, i.e. the other template
+    instance; residual as first and as second operand), and a projection block in the other order (projection
+    first, stride 1).  Every tensor of one copy; then 1001 copies of a 6x6 map = 1127 tiles of 32 pixels for 512
+    (256) persistent workgroups -- three and more tiles each, so the counted waits of the steady state run --
+    with a ragged last tile, logits of a layer that is fully connected over all pixels, against the oracle.
+    The timing report must name the kernels."""
     _say("expand + add + next reduce in one kernel")
     rng = np.random.default_rng(61)
-    b = NetBuilder(rng=np.random.default_rng(62), in_shape=(3, 12, 12), num_classes=7)
-    t0 = b.tensor(3, 12, 12, 0, 74.0)
-    t1 = b.conv(t0, 512, 3, 2, 1, True)                        # x: 512 channels on 6x6
-    t2 = b.conv(t1, 128, 1, 1, 0, True)
+    b = NetBuilder(rng=np.random.default_rng(62), in_shape=(3, 24, 24), num_classes=7)
+    t0 = b.tensor(3, 24, 24, 0, 74.0)
+    ta = b.conv(t0, 256, 3, 2, 1, True)                        # block input: 256 channels on 12x12
+    u = b.conv(ta, 128, 1, 1, 0, True)
+    u = b.conv(u, 128, 3, 2, 1, True)                          # 6x6
+    u = b.conv(u, 512, 1, 1, 0, False, sh=rng.integers(7, 10, size=512))
+    s_ = b.conv(ta, 512, 1, 2, 0, False, zp_out=-9)            # projection, stride 2, issued right before the add
+    t1 = b.add(s_, u, True)
+    t2 = b.conv(t1, 128, 1, 1, 0, True)                        # pair 0: projection + expand + add + t2
     t3 = b.conv(t2, 128, 3, 1, 1, True)
     t4 = b.conv(t3, 512, 1, 1, 0, False, zp_out=4, sh=rng.integers(7, 10, size=512))
     t5 = b.add(t1, t4, True)                                   # residual first
@@ -753,10 +761,17 @@ def test_expand_add_and_next_reduce_in_one_kernel(isr):
     t8 = b.conv(t7, 512, 1, 1, 0, False, sh=rng.integers(7, 10, size=512))
     t9 = b.add(t8, t5, True, ma=1 << 19, mb=1 << 19, sh=20, zp_out=-30)   # ties in the add, residual second
     t10 = b.conv(t9, 128, 1, 1, 0, True)                       # pair 2
-    t11 = b.conv(t10, 16, 1, 1, 0, True)
-    b.fc(t11, 7)
+    tb = b.conv(t10, 256, 1, 1, 0, True)                       # a block input of 256 channels on 6x6
+    v = b.conv(tb, 128, 1, 1, 0, True)
+    v = b.conv(v, 128, 3, 1, 1, True)
+    s2 = b.conv(tb, 512, 1, 1, 0, False)                       # projection first ...
+    v = b.conv(v, 512, 1, 1, 0, False, zp_out=11)              # ... the closing convolution right before the add
+    t11 = b.add(v, s2, True, ma=1 << 19, mb=3 << 18, sh=20)
+    t12 = b.conv(t11, 128, 1, 1, 0, True)                      # pair 3
+    t13 = b.conv(t12, 16, 1, 1, 0, True)
+    b.fc(t13, 7)
     blob = b.blob()
-    x = np.random.default_rng(63).integers(0, 256, size=(3, 12, 12)).astype(np.uint8)
+    x = np.random.default_rng(63).integers(0, 256, size=(3, 24, 24)).astype(np.uint8)
     _check_all_tensors(isr, blob, x, 64, sample=5, chunk=3)
     copies = 1001
     om = oracle.Model(blob)
@@ -767,6 +782,7 @@ def test_expand_add_and_next_reduce_in_one_kernel(isr):
     assert np.array_equal(lg, olg) and np.array_equal(am, oam) and np.array_equal(cnt, ocnt)
     stats = {s["name"]: s["launches"] for s in isr.isr_profile_read(m)}
     assert stats.get("expand_reduce_kernel<128, 512, 128>", 0) == 2, stats
+    assert stats.get("proj_expand_reduce_kernel<256, 128, 512, 128>", 0) == 2, stats
     isr.isr_set_fusion(m, 0)                                   # one kernel per op gives the same
     lg0, am0, cnt0 = isr.isr_debug_forward(m, x, 64, 3, 2, 1, 7, copies)
     assert np.array_equal(lg0, olg) and np.array_equal(cnt0, ocnt)
