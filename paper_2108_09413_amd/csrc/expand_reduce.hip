@@ -360,6 +360,158 @@ __global__ __launch_bounds__(XNT2, 4) void proj_expand_reduce_kernel(const XrPar
     }
 }
 
+// ---- identity block followed by a block with 256 middle channels (the first block of the next stage) ----
+// As expand_reduce_kernel, but the reducing convolution has 256 outputs: sixteen waves, wave w owns channels
+// 32 w .. 32 w + 31 of the expanding convolution and channels 16 w .. 16 w + 15 (all 32 pixels) of the reducing one.
+
+constexpr int XN2W = 256;
+
+template <bool TFA>
+__global__ __launch_bounds__(XNT2, 4) void expand_reduce256_kernel(const XrParams p) {
+    __shared__ __attribute__((aligned(256))) int8_t XY[XNB][XPX * XC];
+    __shared__ __attribute__((aligned(16))) int8_t T2[XNB][XPX * XK1];
+    __shared__ __attribute__((aligned(16))) int prm1[4][XC];     // bias, M0, chi, shift-1 of the expanding convolution
+    __shared__ __attribute__((aligned(16))) int prm2[4][XN2W];   // of the reducing convolution
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ntiles = (p.npix + XPX - 1) / XPX, G = gridDim.x;
+    const uint32_t xy_lds = lds_address(&XY[0][0]), t2_lds = lds_address(&T2[0][0]);
+
+    // direct-to-LDS loads of a tile: wave w fetches pixels 2 w, 2 w + 1 of the x tile, waves 0 .. 3 also pixels
+    // 8 w .. 8 w + 7 of the t2 tile
+    auto issue_tile = [&](int tile, int buf) {
+        const int n0 = tile * XPX;
+        int l = lane;
+        asm volatile("" : "+v"(l));   // recompute the per-lane offsets per call: kept across the tile loop they would be spilled
+        {
+            const int px = 2 * wave + (l >> 5), c = (l & 31) ^ (px & 15);
+            int n = n0 + px;
+            n = n < p.npix ? n : p.npix - 1;
+            ISR_GLOBAL_TO_LDS16_AT(p.x + ((uint32_t)n * (uint32_t)XC + (uint32_t)(c * 16)), xy_lds + buf * (XPX * XC) + wave * 1024);
+        }
+        if (wave < 4) {
+            const int row = 8 * wave + (l >> 3), c = (l & 7) ^ swz<8>(row);
+            int n = n0 + row;
+            n = n < p.npix ? n : p.npix - 1;
+            ISR_GLOBAL_TO_LDS16_AT(p.t2 + ((uint32_t)n * (uint32_t)XK1 + (uint32_t)(c * 16)), t2_lds + buf * (XPX * XK1) + wave * 1024);
+        }
+    };
+
+    int tile = blockIdx.x;
+    if (tile < ntiles) issue_tile(tile, 0);
+    if (tile + G < ntiles) issue_tile(tile + G, 1);
+    for (int i = tid; i < XC; i += XNT2) {
+        prm1[0][i] = p.bias1[i]; prm1[1][i] = p.m0s1[i]; prm1[2][i] = p.chi1[i]; prm1[3][i] = p.shm11[i];
+    }
+    if (tid < XN2W) {
+        prm2[0][tid] = p.bias2[tid]; prm2[1][tid] = p.m0s2[tid]; prm2[2][tid] = p.chi2[tid]; prm2[3][tid] = p.shm12[tid];
+    }
+    const uint32_t lane16 = (uint32_t)lane * 16;
+    v4i a1[XK1 / 32], a2[XC / 64];   // weight fragments, kept in registers for the whole launch
+#pragma unroll
+    for (int ks = 0; ks < XK1 / 32; ++ks) a1[ks] = *(const v4i *)(p.a1 + (size_t)wave * (XK1 / 32) * 1024 + (lane16 + (uint32_t)(ks * 1024)));
+#pragma unroll
+    for (int ks = 0; ks < XC / 64; ++ks) a2[ks] = *(const v4i *)(p.a2 + (size_t)wave * (XC / 64) * 1024 + (lane16 + (uint32_t)(ks * 1024)));
+    wait_vmcnt<0>();
+    __syncthreads();   // the constants are in LDS, the first tile has landed
+
+    int buf = 0;
+    for (int it = 0; tile < ntiles; tile += G, ++it) {
+        const int n0 = tile * XPX;
+        const bool prefetch = tile + 2 * G < ntiles;
+        if (it > 0) {
+            // as in expand_reduce_kernel: since this tile's loads, a wave has issued three stores per tile for two tiles and
+            // the loads of the next tile (two for waves 0 .. 3, one for the others)
+            if (it >= 2 && tile + G < ntiles) {
+                if (wave < 4) wait_vmcnt<8>();
+                else wait_vmcnt<7>();
+            } else {
+                wait_vmcnt<0>();
+            }
+            __builtin_amdgcn_s_barrier();    // every wave's loads of this tile landed; every wave is done with the previous tile
+        }
+        if (prefetch) issue_tile(tile + 2 * G, buf >= 1 ? buf - 1 : XNB - 1);
+
+        int l = lane;
+        asm volatile("" : "+v"(l));
+        const int half = l >> 5, px1 = l & 31;
+        const int g = l >> 4, px2 = l & 15;
+        const int oc = wave * 32 + half * 16;
+        int8_t *xyb = XY[buf];
+
+        // ---- expand + add: 32 channels x 32 pixels per wave ----
+        {
+            v16i acc;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] = prm1[0][oc + i];
+            const int8_t *t2b = T2[buf];
+            const int b_off1 = px1 * XK1 + ((half ^ swz<8>(px1)) << 4);
+#pragma unroll
+            for (int ks = 0; ks < XK1 / 32; ++ks) {
+                const v4i fb = *(const v4i *)(t2b + (b_off1 ^ (ks << 5)));
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[ks], fb, acc, 0, 0, 0);
+            }
+            int8_t *cell = xyb + px1 * XC + (((oc >> 4) ^ (px1 & 15)) << 4);
+            const v4i rv = *(const v4i *)cell;
+            v4i yv;
+#pragma unroll
+            for (int gi = 0; gi < 4; ++gi) {
+                __builtin_amdgcn_sched_barrier(0);
+                const v4i mm = *(const v4i *)&prm1[1][oc + 4 * gi], ch = *(const v4i *)&prm1[2][oc + 4 * gi], ss = *(const v4i *)&prm1[3][oc + 4 * gi];
+                int q[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int v = clamp3(requant_tie_free(acc[4 * gi + i], mm[i], ch[i], ss[i]), p.lo1, 127);
+                    const int r8 = (int)(int8_t)((uint32_t)rv[gi] >> (8 * i));
+                    if constexpr (TFA) {
+                        const int s = __mul24(v, p.add_mul_self) + (p.add_c0 + p.add_k) + __mul24(r8, p.add_mul_res);
+                        q[i] = clamp3(s >> p.add_sh, p.add_lo, 127);
+                    } else {
+                        const int s = __mul24(v, p.add_mul_self) + p.add_c0 + __mul24(r8, p.add_mul_res);
+                        q[i] = clamp3((s + p.add_k + (s >> 31)) >> p.add_sh, p.add_lo, 127);
+                    }
+                }
+                yv[gi] = (int)pack4(q[0], q[1], q[2], q[3]);
+            }
+            *(v4i *)cell = yv;
+            const long n1 = (long)n0 + px1;
+            if (n1 < p.npix) *(v4i *)(p.y + n1 * XC + oc) = yv;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave's part of the y tile is in LDS
+        __builtin_amdgcn_s_barrier();                         // the y tile is complete
+        asm volatile("" ::: "memory");
+
+        // ---- reduce: wave w computes channels 16 w .. 16 w + 15 of the 32 pixels ----
+        {
+            v4acc acc2[2];
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc2[nb][i] = prm2[0][wave * 16 + g * 4 + i];
+#pragma unroll
+            for (int ks = 0; ks < XC / 64; ++ks) {
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb) {
+                    const v4i fb = *(const v4i *)(xyb + (px2 + 16 * nb) * XC + (((4 * ks + g) ^ px2) << 4));
+                    acc2[nb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a2[ks], fb, acc2[nb], 0, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+                const long n2 = (long)n0 + px2 + 16 * nb;
+                int q[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int c = wave * 16 + g * 4 + i;
+                    q[i] = clamp3(requant_tie_free(acc2[nb][i], prm2[1][c], prm2[2][c], prm2[3][c]), p.lo2, 127);
+                }
+                if (n2 < p.npix) *(uint32_t *)(p.t1n + n2 * XN2W + wave * 16 + g * 4) = pack4(q[0], q[1], q[2], q[3]);
+            }
+        }
+        buf = buf + 1 == XNB ? 0 : buf + 1;
+    }
+}
+
 }  // namespace
 
 // Which of the two convolutions of a fuse_add == 2 descriptor is the projection: the main one (256 input channels, may be
@@ -377,8 +529,9 @@ bool expand_reduce_supported(const ConvParams &e, const ConvParams &r) {
                  (long)e.H * e.W * XPK < (1l << 31);
     else
         expand = expand && e.fuse_add == 2 && e.stride == 1 && e.Cin_p == XK1 && e.Kp == XK1 && e.Cin2_p == XPK && e.tie_free2 && e.wfrag2;
-    const bool reduce = r.k == 1 && r.stride == 1 && r.pad == 0 && r.Cin_p == XC && r.Kp == XC && r.Cout_p == XN2 && !r.fuse_add &&
-                        r.fast_requant && r.tie_free && !r.c4 && r.wfrag;
+    const bool reduce = r.k == 1 && r.stride == 1 && r.pad == 0 && r.Cin_p == XC && r.Kp == XC &&
+                        (r.Cout_p == XN2 || (r.Cout_p == XN2W && e.fuse_add == 1)) && !r.fuse_add && r.fast_requant && r.tie_free &&
+                        !r.c4 && r.wfrag;
     return expand && reduce && e.Ho == r.H && e.Wo == r.W && r.Ho == r.H && r.Wo == r.W;
 }
 
@@ -392,6 +545,7 @@ void expand_reduce_params(const ConvParams &e, const ConvParams &r, const int8_t
     xp.lo2 = r.relu ? r.zp_out : -128;
     xp.add_c0 = e.add_c0; xp.add_k = e.add_k; xp.add_sh = e.add_sh; xp.add_lo = e.add_lo;
     xp.npix = copies * e.Ho * e.Wo;
+    xp.n2 = r.Cout_p;
     xp.Hin = e.H; xp.Win = e.W; xp.Ho = e.Ho; xp.Wo = e.Wo; xp.pstride = 1;
     const int lo_main = e.relu ? e.zp_out : -128;
     if (projection_is_main(e)) {
@@ -422,6 +576,13 @@ hipError_t launch_expand_reduce(const XrParams &p, int add_tie_free, hipStream_t
         set_kernel_name("proj_expand_reduce_kernel<256, 128, 512, 128>");
         if (add_tie_free) hipLaunchKernelGGL((proj_expand_reduce_kernel<true>), grid, dim3(XNT2), 0, st, p);
         else hipLaunchKernelGGL((proj_expand_reduce_kernel<false>), grid, dim3(XNT2), 0, st, p);
+        return hipGetLastError();
+    }
+    if (p.n2 == XN2W) {
+        const dim3 grid((unsigned)(ntiles < 256 ? ntiles : 256));
+        set_kernel_name("expand_reduce_kernel<128, 512, 256>");
+        if (add_tie_free) hipLaunchKernelGGL((expand_reduce256_kernel<true>), grid, dim3(XNT2), 0, st, p);
+        else hipLaunchKernelGGL((expand_reduce256_kernel<false>), grid, dim3(XNT2), 0, st, p);
         return hipGetLastError();
     }
     const dim3 grid((unsigned)(ntiles < 512 ? ntiles : 512));

@@ -220,6 +220,7 @@ struct XrParams {
     int32_t lo1, lo2;        // lower clamps of the two convolutions' int8 results
     int32_t add_mul_self, add_mul_res, add_c0, add_k, add_sh, add_lo;   // as in ConvParams
     int32_t npix;
+    int32_t n2;              // output channels of the reducing convolution: 128, or 256 (stored residual only)
 };
 
 // Down-sampling residual block in one kernel (trans_block.hip): t = conv3x3/2(x), u = conv3x3(t),

@@ -485,7 +485,7 @@ int build_device_ops(const ParsedModel &pm, std::vector<DevOp> &ops, ConstArena 
                             std::memcpy(&f[(((size_t)blk * (Kp / 32) + ks) * 64 + l) * 16],
                                         &w[(size_t)(32 * blk + (l & 31)) * Kp + ks * 32 + 16 * (l >> 5)], 16);
                 c.wfrag = (const int8_t *)arena.put(f.data(), f.size());
-            } else if (flat && fast && perm && cin_p == 512 && cout_p == 128 && Kp == 512) {
+            } else if (flat && fast && perm && cin_p == 512 && (cout_p == 128 || cout_p == 256) && Kp == 512) {
                 // 16x16x64 fragments [16-channel block][K step of 64]: lane l = channel l & 15 of the block, K bytes 16 (l >> 4) ..
                 std::vector<int8_t> f((size_t)cout_p * Kp);
                 for (int mb = 0; mb < cout_p / 16; ++mb)

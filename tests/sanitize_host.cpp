@@ -56,8 +56,9 @@ bool expand_reduce_supported(const ConvParams &e, const ConvParams &r) {
                  (long)e.H * e.W * 256 < (1l << 31);
     else
         expand = expand && e.fuse_add == 2 && e.stride == 1 && e.Cin_p == 128 && e.Kp == 128 && e.Cin2_p == 256 && e.tie_free2 && e.wfrag2;
-    const bool reduce = r.k == 1 && r.stride == 1 && r.pad == 0 && r.Cin_p == 512 && r.Kp == 512 && r.Cout_p == 128 && !r.fuse_add &&
-                        r.fast_requant && r.tie_free && !r.c4 && r.wfrag;
+    const bool reduce = r.k == 1 && r.stride == 1 && r.pad == 0 && r.Cin_p == 512 && r.Kp == 512 &&
+                        (r.Cout_p == 128 || (r.Cout_p == 256 && e.fuse_add == 1)) && !r.fuse_add && r.fast_requant && r.tie_free &&
+                        !r.c4 && r.wfrag;
     return expand && reduce && e.Ho == r.H && e.Wo == r.W && r.Ho == r.H && r.Wo == r.W;
 }
 bool bottleneck128_supported(int cin_p, int cmid_p, int cout_p) {

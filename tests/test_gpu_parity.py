@@ -734,11 +734,11 @@ def test_3x3_layers_with_staged_pixel_rows_against_the_oracle(isr, in_shape, str
 
 def test_expand_add_and_next_reduce_in_one_kernel(isr):
     """The kernels that run a block's closing 1x1 (128 -> 512) + residual add and the next block's opening 1x1
-    (512 -> 128) on pixel tiles of all 512 channels.  Four such pairs in a row: a first block whose residual is
+    (512 -> 128, or 256 for the first block of a next stage) on pixel tiles of all 512 channels.  Five such pairs in a row: a first block whose residual is
     a stride-2 projection of the 256-channel block input issued after the closing convolution (the order of a
     ResNet-50), two identity blocks (the second with an add that meets exact halves, i.e. the other template
-    instance; residual as first and as second operand), and a projection block in the other order (projection
-    first, stride 1).  Every tensor of one copy; then 1001 copies of a 6x6 map = 1127 tiles of 32 pixels for 512
+    instance; residual as first and as second operand), a projection block in the other order (projection
+    first, stride 1), and an identity block followed by a 256-channel opening convolution.  Every tensor of one copy; then 1001 copies of a 6x6 map = 1127 tiles of 32 pixels for 512
     (256) persistent workgroups -- three and more tiles each, so the counted waits of the steady state run --
     with a ragged last tile, logits of a layer that is fully connected over all pixels, against the oracle.
     The timing report must name the kernels."""
@@ -768,8 +768,12 @@ def test_expand_add_and_next_reduce_in_one_kernel(isr):
     v = b.conv(v, 512, 1, 1, 0, False, zp_out=11)              # ... the closing convolution right before the add
     t11 = b.add(v, s2, True, ma=1 << 19, mb=3 << 18, sh=20)
     t12 = b.conv(t11, 128, 1, 1, 0, True)                      # pair 3
-    t13 = b.conv(t12, 16, 1, 1, 0, True)
-    b.fc(t13, 7)
+    w_ = b.conv(t12, 128, 3, 1, 1, True)
+    w_ = b.conv(w_, 512, 1, 1, 0, False)
+    t13 = b.add(t11, w_, True)
+    t14 = b.conv(t13, 256, 1, 1, 0, True)                      # pair 4: the next block has 256 middle channels
+    t15 = b.conv(t14, 16, 1, 1, 0, True)
+    b.fc(t15, 7)
     blob = b.blob()
     x = np.random.default_rng(63).integers(0, 256, size=(3, 24, 24)).astype(np.uint8)
     _check_all_tensors(isr, blob, x, 64, sample=5, chunk=3)
@@ -783,6 +787,7 @@ def test_expand_add_and_next_reduce_in_one_kernel(isr):
     stats = {s["name"]: s["launches"] for s in isr.isr_profile_read(m)}
     assert stats.get("expand_reduce_kernel<128, 512, 128>", 0) == 2, stats
     assert stats.get("proj_expand_reduce_kernel<256, 128, 512, 128>", 0) == 2, stats
+    assert stats.get("expand_reduce_kernel<128, 512, 256>", 0) == 1, stats
     isr.isr_set_fusion(m, 0)                                   # one kernel per op gives the same
     lg0, am0, cnt0 = isr.isr_debug_forward(m, x, 64, 3, 2, 1, 7, copies)
     assert np.array_equal(lg0, olg) and np.array_equal(cnt0, ocnt)
