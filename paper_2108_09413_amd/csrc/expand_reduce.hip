@@ -512,6 +512,176 @@ __global__ __launch_bounds__(XNT2, 4) void expand_reduce256_kernel(const XrParam
     }
 }
 
+// ---- the 14x14 stage: 256 middle and 1024 block channels ----
+// Same scheme, sixteen waves: wave w owns channels 64 w .. 64 w + 63 of the expanding convolution (K = 256: 64 registers
+// of fragments, kept for the whole launch) and channels 16 w .. 16 w + 15 of the reducing one, whose K = 1024 no longer
+// fits next to them: its fragments are re-read from L2 per tile, two K steps at a time, one group ahead of the MFMAs
+// (256 KB per tile and workgroup, contiguous 1 KB wave-loads).  Rows of the x / y tile are 1024 bytes, of the t2 tile
+// 256 bytes; chunk c of pixel p sits at chunk c ^ (p & 15) in both.
+
+constexpr int DK1 = 256, DC = 1024, DN2 = 256;
+
+template <bool TFA>
+__global__ __launch_bounds__(XNT2, 4) void expand_reduce1024_kernel(const XrParams p) {
+    __shared__ __attribute__((aligned(256))) int8_t XY[XNB][XPX * DC];
+    __shared__ __attribute__((aligned(256))) int8_t T2[XNB][XPX * DK1];
+    __shared__ __attribute__((aligned(16))) int prm1[4][DC];     // bias, M0, chi, shift-1 of the expanding convolution
+    __shared__ __attribute__((aligned(16))) int prm2[4][DN2];    // of the reducing convolution
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ntiles = (p.npix + XPX - 1) / XPX, G = gridDim.x;
+    const uint32_t xy_lds = lds_address(&XY[0][0]), t2_lds = lds_address(&T2[0][0]);
+
+    // direct-to-LDS loads of a tile: wave w fetches pixels 2 w and 2 w + 1 of the x tile (one 1024-byte row per load),
+    // waves 0 .. 7 also pixels 4 w .. 4 w + 3 of the t2 tile
+    auto issue_tile = [&](int tile, int buf) {
+        const int n0 = tile * XPX;
+        int l = lane;
+        asm volatile("" : "+v"(l));   // recompute the per-lane offsets per call: kept across the tile loop they would be spilled
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int px = 2 * wave + j, c = l ^ (px & 15);
+            int n = n0 + px;
+            n = n < p.npix ? n : p.npix - 1;
+            ISR_GLOBAL_TO_LDS16_AT(p.x + ((uint32_t)n * (uint32_t)DC + (uint32_t)(c * 16)), xy_lds + buf * (XPX * DC) + px * 1024);
+        }
+        if (wave < 8) {
+            const int px = 4 * wave + (l >> 4), c = (l & 15) ^ (px & 15);
+            int n = n0 + px;
+            n = n < p.npix ? n : p.npix - 1;
+            ISR_GLOBAL_TO_LDS16_AT(p.t2 + ((uint32_t)n * (uint32_t)DK1 + (uint32_t)(c * 16)), t2_lds + buf * (XPX * DK1) + wave * 1024);
+        }
+    };
+
+    int tile = blockIdx.x;
+    if (tile < ntiles) issue_tile(tile, 0);
+    if (tile + G < ntiles) issue_tile(tile + G, 1);
+    for (int i = tid; i < DC; i += XNT2) {
+        prm1[0][i] = p.bias1[i]; prm1[1][i] = p.m0s1[i]; prm1[2][i] = p.chi1[i]; prm1[3][i] = p.shm11[i];
+    }
+    if (tid < DN2) {
+        prm2[0][tid] = p.bias2[tid]; prm2[1][tid] = p.m0s2[tid]; prm2[2][tid] = p.chi2[tid]; prm2[3][tid] = p.shm12[tid];
+    }
+    const uint32_t lane16 = (uint32_t)lane * 16;
+    // expand fragments [fm][ksub], kept in registers for the whole launch
+    const int8_t *a1w = p.a1 + (size_t)wave * (2 * (DK1 / 32) * 1024);
+    v4i a1[2 * (DK1 / 32)];
+#pragma unroll
+    for (int f = 0; f < 2 * (DK1 / 32); ++f) a1[f] = *(const v4i *)(a1w + (lane16 + (uint32_t)(f * 1024)));
+    const int8_t *a2w = p.a2 + (size_t)wave * ((DC / 64) * 1024);   // this wave's reduce fragments [kstep]
+    // the fragments are in their registers before the tile loop starts (else the compiler carries "load pending" into the
+    // loop and waits for every outstanding memory operation at their first use in each tile)
+#pragma unroll
+    for (int f = 0; f < 2 * (DK1 / 32); ++f) asm volatile("" : "+v"(a1[f]));
+    wait_vmcnt<0>();
+    __syncthreads();   // the constants are in LDS, the first tile has landed
+
+    int buf = 0;
+    for (int it = 0; tile < ntiles; tile += G, ++it) {
+        const int n0 = tile * XPX;
+        const bool prefetch = tile + 2 * G < ntiles;
+        if (it > 0) {
+            // Vector memory operations complete in issue order and the reduce below has already waited for its own fragment
+            // loads, which were issued after the loads of this tile: all that may still be under way are the two stores that
+            // ended the previous tile.
+            wait_vmcnt<2>();
+            __builtin_amdgcn_s_barrier();    // every wave's loads of this tile landed; every wave is done with the previous tile
+        }
+        if (prefetch) issue_tile(tile + 2 * G, buf >= 1 ? buf - 1 : XNB - 1);
+        int l = lane;
+        asm volatile("" : "+v"(l));   // per-lane values below are recomputed per tile, loads from them are not hoisted out of the loop
+        const int half = l >> 5, px1 = l & 31;
+        const int g = l >> 4, px2 = l & 15;
+        int8_t *xyb = XY[buf];
+
+        // ---- expand + add: 64 channels x 32 pixels per wave, 32 channels at a time ----
+        const int8_t *t2b = T2[buf];
+        const int b_off1 = px1 * DK1 + ((half ^ (px1 & 15)) << 4);   // chunk (2 k + half) ^ (px & 15): sub-step k flips bits 5..7 by k
+        const long n1 = (long)n0 + px1;
+#pragma unroll
+        for (int fm = 0; fm < 2; ++fm) {
+            const int oc = wave * 64 + fm * 32 + half * 16;
+            v16i acc;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] = prm1[0][oc + i];
+#pragma unroll
+            for (int ks = 0; ks < DK1 / 32; ++ks) {
+                const v4i fb = *(const v4i *)(t2b + (b_off1 ^ (ks << 5)));
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[fm * (DK1 / 32) + ks], fb, acc, 0, 0, 0);
+            }
+            int8_t *cell = xyb + px1 * DC + (((oc >> 4) ^ (px1 & 15)) << 4);
+            const v4i rv = *(const v4i *)cell;
+            v4i yv;
+#pragma unroll
+            for (int gi = 0; gi < 4; ++gi) {
+                __builtin_amdgcn_sched_barrier(0);   // one group's constants at a time: the registers are needed for weight fragments
+                const v4i mm = *(const v4i *)&prm1[1][oc + 4 * gi], ch = *(const v4i *)&prm1[2][oc + 4 * gi], ss = *(const v4i *)&prm1[3][oc + 4 * gi];
+                int q[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int v = clamp3(requant_tie_free(acc[4 * gi + i], mm[i], ch[i], ss[i]), p.lo1, 127);
+                    const int r8 = (int)(int8_t)((uint32_t)rv[gi] >> (8 * i));
+                    if constexpr (TFA) {
+                        const int s = __mul24(v, p.add_mul_self) + (p.add_c0 + p.add_k) + __mul24(r8, p.add_mul_res);
+                        q[i] = clamp3(s >> p.add_sh, p.add_lo, 127);
+                    } else {
+                        const int s = __mul24(v, p.add_mul_self) + p.add_c0 + __mul24(r8, p.add_mul_res);
+                        q[i] = clamp3((s + p.add_k + (s >> 31)) >> p.add_sh, p.add_lo, 127);
+                    }
+                }
+                yv[gi] = (int)pack4(q[0], q[1], q[2], q[3]);
+            }
+            *(v4i *)cell = yv;
+            if (n1 < p.npix) *(v4i *)(p.y + n1 * DC + oc) = yv;
+        }
+        // the first group of reduce fragments is on its way while the workgroup meets at the barrier
+        constexpr int GK = 2;   // K steps per group of reduce fragments (four measured no faster)
+        v4i a2c[2][GK];
+#pragma unroll
+        for (int i = 0; i < GK; ++i) a2c[0][i] = *(const v4i *)(a2w + ((uint32_t)l * 16 + (uint32_t)(i * 1024)));
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave's part of the y tile is in LDS
+        __builtin_amdgcn_s_barrier();                         // the y tile is complete
+        asm volatile("" ::: "memory");
+
+        // ---- reduce: wave w computes channels 16 w .. 16 w + 15 of the 32 pixels, K = 1024 ----
+        {
+            v4acc acc2[2];
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc2[nb][i] = prm2[0][wave * 16 + g * 4 + i];
+#pragma unroll
+            for (int j = 0; j < DC / 64 / GK; ++j) {
+                if (j + 1 < DC / 64 / GK) {
+#pragma unroll
+                    for (int i = 0; i < GK; ++i) a2c[(j + 1) & 1][i] = *(const v4i *)(a2w + ((uint32_t)l * 16 + (uint32_t)(((j + 1) * GK + i) * 1024)));
+                }
+#pragma unroll
+                for (int i = 0; i < GK; ++i) {
+                    const int ks = GK * j + i;
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb) {
+                        const v4i fb = *(const v4i *)(xyb + (px2 + 16 * nb) * DC + (((4 * ks + g) ^ px2) << 4));
+                        acc2[nb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a2c[j & 1][i], fb, acc2[nb], 0, 0, 0);
+                    }
+                }
+            }
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+                const long n2 = (long)n0 + px2 + 16 * nb;
+                int q[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int c = wave * 16 + g * 4 + i;
+                    q[i] = clamp3(requant_tie_free(acc2[nb][i], prm2[1][c], prm2[2][c], prm2[3][c]), p.lo2, 127);
+                }
+                if (n2 < p.npix) *(uint32_t *)(p.t1n + n2 * DN2 + wave * 16 + g * 4) = pack4(q[0], q[1], q[2], q[3]);
+            }
+        }
+        buf = buf + 1 == XNB ? 0 : buf + 1;
+    }
+}
+
 }  // namespace
 
 // Which of the two convolutions of a fuse_add == 2 descriptor is the projection: the main one (256 input channels, may be
@@ -522,6 +692,10 @@ static bool projection_is_main(const ConvParams &e) { return e.fuse_add == 2 && 
 // 256-channel tensor computed alongside); reduce: 1x1 stride 1, 512 -> 128, reading the sum; single-multiply tie-free
 // requantisations (the add may meet ties); fragment-major weight copies present
 bool expand_reduce_supported(const ConvParams &e, const ConvParams &r) {
+    if (e.fuse_add == 1 && e.Cin_p == DK1)   // the 14 x 14 stage: 256 -> 1024 + add, then 1024 -> 256
+        return e.k == 1 && e.stride == 1 && e.pad == 0 && e.Kp == DK1 && e.Cout_p == DC && e.fast_requant && e.tie_free && !e.c4 && e.wfrag &&
+               r.k == 1 && r.stride == 1 && r.pad == 0 && r.Cin_p == DC && r.Kp == DC && r.Cout_p == DN2 && !r.fuse_add && r.fast_requant &&
+               r.tie_free && !r.c4 && r.wfrag && e.Ho == r.H && e.Wo == r.W && r.Ho == r.H && r.Wo == r.W;
     bool expand = e.k == 1 && e.pad == 0 && e.Cout_p == XC && e.fast_requant && e.tie_free && !e.c4 && e.wfrag;
     if (e.fuse_add == 1) expand = expand && e.stride == 1 && e.Cin_p == XK1 && e.Kp == XK1;
     else if (projection_is_main(e))   // main: projection 256 -> 512, stride 1 or 2; second: the expanding convolution on the output pixels
@@ -546,6 +720,7 @@ void expand_reduce_params(const ConvParams &e, const ConvParams &r, const int8_t
     xp.add_c0 = e.add_c0; xp.add_k = e.add_k; xp.add_sh = e.add_sh; xp.add_lo = e.add_lo;
     xp.npix = copies * e.Ho * e.Wo;
     xp.n2 = r.Cout_p;
+    xp.k1 = e.fuse_add == 1 ? e.Cin_p : XK1;
     xp.Hin = e.H; xp.Win = e.W; xp.Ho = e.Ho; xp.Wo = e.Wo; xp.pstride = 1;
     const int lo_main = e.relu ? e.zp_out : -128;
     if (projection_is_main(e)) {
@@ -569,8 +744,15 @@ void expand_reduce_params(const ConvParams &e, const ConvParams &r, const int8_t
 
 hipError_t launch_expand_reduce(const XrParams &p, int add_tie_free, hipStream_t st) {
     if (p.npix <= 0) return hipSuccess;
-    if ((long)p.npix * XC >= (1l << 32)) return hipErrorInvalidValue;   // 32-bit byte offsets inside the tensors
+    if ((long)p.npix * DC >= (1l << 32)) return hipErrorInvalidValue;   // 32-bit byte offsets inside the tensors
     const int ntiles = (p.npix + XPX - 1) / XPX;
+    if (p.k1 == DK1) {
+        const dim3 grid((unsigned)(ntiles < 256 ? ntiles : 256));
+        set_kernel_name("expand_reduce_kernel<256, 1024, 256>");
+        if (add_tie_free) hipLaunchKernelGGL((expand_reduce1024_kernel<true>), grid, dim3(XNT2), 0, st, p);
+        else hipLaunchKernelGGL((expand_reduce1024_kernel<false>), grid, dim3(XNT2), 0, st, p);
+        return hipGetLastError();
+    }
     if (p.in2) {
         const dim3 grid((unsigned)(ntiles < 256 ? ntiles : 256));   // one workgroup of sixteen waves per CU
         set_kernel_name("proj_expand_reduce_kernel<256, 128, 512, 128>");

@@ -221,6 +221,7 @@ struct XrParams {
     int32_t add_mul_self, add_mul_res, add_c0, add_k, add_sh, add_lo;   // as in ConvParams
     int32_t npix;
     int32_t n2;              // output channels of the reducing convolution: 128, or 256 (stored residual only)
+    int32_t k1;              // input channels of the expanding convolution: 128 (512 block channels) or 256 (1024; stored residual, n2 = 256)
 };
 
 // Down-sampling residual block in one kernel (trans_block.hip): t = conv3x3/2(x), u = conv3x3(t),

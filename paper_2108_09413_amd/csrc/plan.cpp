@@ -476,7 +476,8 @@ int build_device_ops(const ParsedModel &pm, std::vector<DevOp> &ops, ConstArena 
             // fragment-major copies for the kernel that runs an expanding 1x1 + add and the next reducing 1x1 together
             // (expand_reduce.hip): one 1 KB block per MFMA operand fragment, 64 lanes x 16 bytes in lane order
             c.wfrag = (const int8_t *)~(uintptr_t)0;
-            if (!c4 && k == 1 && o.pad == 0 && fast && perm && (cin_p == 128 || cin_p == 256) && cout_p == 512 && Kp == cin_p) {
+            if (!c4 && k == 1 && o.pad == 0 && fast && perm && Kp == cin_p &&
+                (((cin_p == 128 || cin_p == 256) && cout_p == 512) || (cin_p == 256 && cout_p == 1024))) {
                 // 32x32x32 fragments [32-row block][K sub-step of 32]: lane l = row l & 31 (stored MFMA row order), K bytes 16 (l >> 5) ..
                 std::vector<int8_t> f((size_t)cout_p * Kp);
                 for (int blk = 0; blk < cout_p / 32; ++blk)
@@ -485,7 +486,7 @@ int build_device_ops(const ParsedModel &pm, std::vector<DevOp> &ops, ConstArena 
                             std::memcpy(&f[(((size_t)blk * (Kp / 32) + ks) * 64 + l) * 16],
                                         &w[(size_t)(32 * blk + (l & 31)) * Kp + ks * 32 + 16 * (l >> 5)], 16);
                 c.wfrag = (const int8_t *)arena.put(f.data(), f.size());
-            } else if (flat && fast && perm && cin_p == 512 && (cout_p == 128 || cout_p == 256) && Kp == 512) {
+            } else if (flat && fast && perm && Kp == cin_p && ((cin_p == 512 && (cout_p == 128 || cout_p == 256)) || (cin_p == 1024 && cout_p == 256))) {
                 // 16x16x64 fragments [16-channel block][K step of 64]: lane l = channel l & 15 of the block, K bytes 16 (l >> 4) ..
                 std::vector<int8_t> f((size_t)cout_p * Kp);
                 for (int mb = 0; mb < cout_p / 16; ++mb)

@@ -51,6 +51,8 @@ def library_name(profiler_name: str) -> str:
         return "conv_patch_kernel<%s, 256, %s>" % m.groups()      # channels x pixels of the tile, K bytes per step
     if re.match(r"proj_expand_reduce_kernel<(?:true|false)>", n):
         return "proj_expand_reduce_kernel<256, 128, 512, 128>"     # block input, middle, block and next middle channels
+    if re.match(r"expand_reduce1024_kernel<(?:true|false)>", n):
+        return "expand_reduce_kernel<256, 1024, 256>"
     if re.match(r"expand_reduce256_kernel<(?:true|false)>", n):
         return "expand_reduce_kernel<128, 512, 256>"
     if re.match(r"expand_reduce_kernel<(?:true|false)>", n):

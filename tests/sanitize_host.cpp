@@ -49,6 +49,10 @@ bool bottleneck_supported(int cin_p, int cmid_p, int cout_p, int tail) {
     return !tail || (cout_p == cin_p && cout_p <= 256);
 }
 bool expand_reduce_supported(const ConvParams &e, const ConvParams &r) {
+    if (e.fuse_add == 1 && e.Cin_p == 256)
+        return e.k == 1 && e.stride == 1 && e.pad == 0 && e.Kp == 256 && e.Cout_p == 1024 && e.fast_requant && e.tie_free && !e.c4 && e.wfrag &&
+               r.k == 1 && r.stride == 1 && r.pad == 0 && r.Cin_p == 1024 && r.Kp == 1024 && r.Cout_p == 256 && !r.fuse_add && r.fast_requant &&
+               r.tie_free && !r.c4 && r.wfrag && e.Ho == r.H && e.Wo == r.W && r.Ho == r.H && r.Wo == r.W;
     bool expand = e.k == 1 && e.pad == 0 && e.Cout_p == 512 && e.fast_requant && e.tie_free && !e.c4 && e.wfrag;
     if (e.fuse_add == 1) expand = expand && e.stride == 1 && e.Cin_p == 128 && e.Kp == 128;
     else if (e.fuse_add == 2 && e.Cin_p == 256)

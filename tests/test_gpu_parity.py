@@ -734,7 +734,7 @@ def test_3x3_layers_with_staged_pixel_rows_against_the_oracle(isr, in_shape, str
 
 def test_expand_add_and_next_reduce_in_one_kernel(isr):
     """The kernels that run a block's closing 1x1 (128 -> 512) + residual add and the next block's opening 1x1
-    (512 -> 128, or 256 for the first block of a next stage) on pixel tiles of all 512 channels.  Five such pairs in a row: a first block whose residual is
+    (512 -> 128, or 256 for the first block of a next stage) on pixel tiles of all 512 channels.  Seven such pairs in a row (the last two with the 14x14 stage's 256 / 1024 channels): a first block whose residual is
     a stride-2 projection of the 256-channel block input issued after the closing convolution (the order of a
     ResNet-50), two identity blocks (the second with an add that meets exact halves, i.e. the other template
     instance; residual as first and as second operand), a projection block in the other order (projection
@@ -772,8 +772,19 @@ def test_expand_add_and_next_reduce_in_one_kernel(isr):
     w_ = b.conv(w_, 512, 1, 1, 0, False)
     t13 = b.add(t11, w_, True)
     t14 = b.conv(t13, 256, 1, 1, 0, True)                      # pair 4: the next block has 256 middle channels
-    t15 = b.conv(t14, 16, 1, 1, 0, True)
-    b.fc(t15, 7)
+    # the 14 x 14 stage's shapes: 256 middle, 1024 block channels
+    tc = b.conv(t14, 1024, 1, 1, 0, True)
+    w_ = b.conv(tc, 256, 1, 1, 0, True)
+    w_ = b.conv(w_, 256, 3, 1, 1, True)
+    w_ = b.conv(w_, 1024, 1, 1, 0, False, zp_out=-3)
+    t15 = b.add(tc, w_, True)
+    t16 = b.conv(t15, 256, 1, 1, 0, True)                      # pair 5
+    w_ = b.conv(t16, 256, 3, 1, 1, True)
+    w_ = b.conv(w_, 1024, 1, 1, 0, False)
+    t17 = b.add(w_, t15, True, ma=1 << 19, mb=1 << 19, sh=20)  # ties in the add
+    t18 = b.conv(t17, 256, 1, 1, 0, True)                      # pair 6
+    t19 = b.conv(t18, 16, 1, 1, 0, True)
+    b.fc(t19, 7)
     blob = b.blob()
     x = np.random.default_rng(63).integers(0, 256, size=(3, 24, 24)).astype(np.uint8)
     _check_all_tensors(isr, blob, x, 64, sample=5, chunk=3)
@@ -788,6 +799,7 @@ def test_expand_add_and_next_reduce_in_one_kernel(isr):
     assert stats.get("expand_reduce_kernel<128, 512, 128>", 0) == 2, stats
     assert stats.get("proj_expand_reduce_kernel<256, 128, 512, 128>", 0) == 2, stats
     assert stats.get("expand_reduce_kernel<128, 512, 256>", 0) == 1, stats
+    assert stats.get("expand_reduce_kernel<256, 1024, 256>", 0) == 2, stats
     isr.isr_set_fusion(m, 0)                                   # one kernel per op gives the same
     lg0, am0, cnt0 = isr.isr_debug_forward(m, x, 64, 3, 2, 1, 7, copies)
     assert np.array_equal(lg0, olg) and np.array_equal(cnt0, ocnt)

@@ -21,6 +21,7 @@ def test_profiler_names_map_to_the_librarys_instance_names():
     assert f("void isr::(anonymous namespace)::conv_patch_kernel<128, 64, 2, false, true>(isr::ConvParams)") == \
         "conv_patch_kernel<128, 256, 64>"
     assert f("void isr::(anonymous namespace)::expand_reduce_kernel<true>(isr::XrParams)") == "expand_reduce_kernel<128, 512, 128>"
+    assert f("void isr::(anonymous namespace)::expand_reduce1024_kernel<true>(isr::XrParams)") == "expand_reduce_kernel<256, 1024, 256>"
     assert f("void isr::(anonymous namespace)::expand_reduce256_kernel<true>(isr::XrParams)") == "expand_reduce_kernel<128, 512, 256>"
     assert f("void isr::(anonymous namespace)::proj_expand_reduce_kernel<false>(isr::XrParams)") == \
         "proj_expand_reduce_kernel<256, 128, 512, 128>"
