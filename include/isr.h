@@ -287,7 +287,9 @@ int isr_certified_metrics(const isr_result *results, const int32_t *labels, uint
  * into the convolution before it; the first convolution with the max pooling after
  * it; a 1x1 convolution that only feeds a residual add into that add's kernel;
  * whole residual blocks of the narrow nets; the convolutions of a bottleneck block
- * with 64 middle channels); 2 also folds identity bottleneck blocks with 128 middle
+ * with 64 middle channels; the closing 1x1 convolution + add of a bottleneck block
+ * with 128 or 256 middle channels together with the opening 1x1 convolution of the
+ * next block, which still writes the sum but does not read it back); 2 also folds identity bottleneck blocks with 128 middle
  * channels into one kernel (correct, at present slower than their three kernels);
  * 0 runs every op of the blob as its own kernel.  Results are identical in every
  * mode; tensors that a fused kernel never stores are served by the unfused plan
